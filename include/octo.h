@@ -1,0 +1,270 @@
+/*
+ * libocto - the data-parallel hot path of a cascaded video-analytics serving
+ * pipeline on one AMD MI355X (gfx950).
+ *
+ * The serving problem follows OctopInf (arXiv 2502.01277): a pipeline is a DAG of
+ * DNN models (Sec. II), each served with a batch size and an execution slot
+ * [bz, d, g, t]; all queries of a batch finish together (Sec. II, Eq. 1); the
+ * pipeline has an SLO (Eq. 3); co-located pipelines share the GPU in space and
+ * time through "inference streams" (Sec. III-C).  The paper leaves the execution
+ * of a model to an inference engine; this library is that engine: letterbox,
+ * convolution graphs, box decode, top-k, class-wise NMS, ROI compaction,
+ * crop-resize and classifier tail as HIP kernels.
+ *
+ * Conventions
+ *  - Plain C ABI.  Every call returns an octo_status; nothing throws or aborts.
+ *  - "device" pointers are HIP device memory owned by the caller; "host" pointers
+ *    are ordinary host memory.  The library allocates no device memory: the
+ *    caller passes a workspace.  It does allocate pinned host memory for results.
+ *  - Streams are passed as void* (hipStream_t).  Calls that take a stream only
+ *    enqueue work on it.
+ *  - NULL pointers, bad sizes or enum values give OCTO_EINVAL and change nothing.
+ *  - One pipeline handle per host thread at a time; different handles may be used
+ *    concurrently.
+ */
+#ifndef OCTO_H_
+#define OCTO_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define OCTO_MAX_LEVELS 3
+#define OCTO_MAX_ANCHORS 3
+#define OCTO_MAX_EDGES 4
+#define OCTO_MAX_CHILD_LABELS 2
+#define OCTO_MAX_LAYER_INPUTS 4
+
+typedef enum {
+  OCTO_OK = 0,
+  OCTO_EINVAL = -1,    /* bad argument */
+  OCTO_ENOMEM = -2,    /* workspace too small / host allocation failed */
+  OCTO_ECAP = -3,      /* a capacity was exceeded; results were clamped and flagged */
+  OCTO_ESTATE = -4,    /* call not valid in the handle's current state */
+  OCTO_EHIP = -5,      /* a HIP runtime call failed; see octo_last_error */
+  OCTO_ENOTREADY = -6  /* non-blocking collect: nothing has finished yet */
+} octo_status;
+
+typedef enum { OCTO_F32 = 0, OCTO_F16 = 1, OCTO_BF16 = 2 } octo_dtype;
+typedef enum { OCTO_CONV = 0, OCTO_MAXPOOL = 1, OCTO_UPSAMPLE2X = 2, OCTO_CONCAT = 3, OCTO_ADD = 4, OCTO_GAP = 5, OCTO_FC = 6 } octo_op;
+typedef enum { OCTO_ACT_NONE = 0, OCTO_ACT_RELU = 1, OCTO_ACT_SILU = 2 } octo_act;
+typedef enum { OCTO_RES_NONE = 0, OCTO_RES_BEFORE_ACT = 1, OCTO_RES_AFTER_ACT = 2 } octo_res_mode;
+typedef enum { OCTO_DETECTOR = 0, OCTO_CLASSIFIER = 1 } octo_model_kind;
+
+/* ---- records that live in device memory (also used by the stage-level calls) ---- */
+
+/* One decoded detection candidate: corners in model-input pixels (not clamped). */
+typedef struct { float x1, y1, x2, y2, score; int32_t cls; int32_t idx; int32_t pad_; } octo_cand;   /* 32 bytes */
+/* One region of interest routed to a child model: source frame position in the batch,
+ * rank in that frame's keep-list, class, corners in SOURCE pixels (clamped to the frame). */
+typedef struct { int32_t frame, rank, cls, pad_; float x1, y1, x2, y2; } octo_roi;                   /* 32 bytes */
+/* One final detection as returned by octo_collect: corners in source pixels. */
+typedef struct { float x1, y1, x2, y2, score; int32_t cls; int32_t child_label[OCTO_MAX_CHILD_LABELS]; } octo_box;  /* 32 bytes */
+
+/* ---- pipeline description (host memory; copied at create) ---- */
+
+/* One layer of a model graph.  Tensor 0 is the model input (NHWC, in_c channels);
+ * layer i produces tensor i+1.  conv: y = act(conv(x) + bias [+ res]) or act(conv(x) + bias) + res,
+ * cross-correlation, zero padding.  fc is a 1x1 conv on a 1x1 map whose output stays fp32. */
+typedef struct {
+  int32_t op;                          /* octo_op */
+  int32_t n_in;
+  int32_t in[OCTO_MAX_LAYER_INPUTS];   /* tensor ids; conv with n_in == 2: in[1] is the residual */
+  int32_t cout, kh, kw, stride, pad;
+  int32_t act;                         /* octo_act */
+  int32_t res_mode;                    /* octo_res_mode */
+  const void* weight;                  /* host; [cout][kh][kw][cin] in the model's storage type (fp32 / IEEE half bits / bf16 bits) */
+  const float* bias;                   /* host; fp32 [cout] */
+} octo_layer;
+
+/* One model (the paper's m).  batch_size is bz_m (Sec. II): the most items one launch processes. */
+typedef struct {
+  const char* name;
+  int32_t dtype;                       /* octo_dtype: storage type of activations and weights; accumulation is fp32 */
+  int32_t kind;                        /* octo_model_kind */
+  int32_t in_h, in_w, in_c;            /* model input: letterbox target (root) or crop size (child) */
+  const octo_layer* layers;
+  int32_t n_layers;
+  int32_t outputs[OCTO_MAX_LEVELS];    /* detector: head tensors, largest grid first; classifier: outputs[0] = fp32 logits */
+  int32_t n_outputs;
+  /* detector post-processing */
+  int32_t n_classes, n_anchors;
+  int32_t stride[OCTO_MAX_LEVELS];
+  float anchors[OCTO_MAX_LEVELS][OCTO_MAX_ANCHORS][2];   /* (w, h) in model-input pixels */
+  float score_thr, iou_thr;            /* keep iff score > score_thr; suppress iff inter > iou_thr * union (same class) */
+  int32_t topk, max_det;               /* threshold -> top-k -> NMS -> cut to max_det */
+  /* pre-processing of this model's input */
+  float norm_scale[3], norm_bias[3];   /* out = pixel * scale + bias per channel */
+  int32_t pad_value;                   /* letterbox padding colour (0..255) */
+  int32_t batch_size;
+} octo_model_desc;
+
+/* DAG edge (Sec. II: models form a DAG): detections of `parent` whose class bit is set go to `child`. */
+typedef struct { int32_t parent, child; uint64_t class_mask[2]; } octo_edge;
+
+typedef struct {
+  const octo_model_desc* models; int32_t n_models;    /* models[0] is the root detector; a later model without an incoming
+                                                         edge is detached (runs only through octo_debug_run_model) */
+  const octo_edge* edges; int32_t n_edges;
+  float slo_ms;                                       /* SLO_p (Eq. 3) */
+  int32_t src_h, src_w;                               /* camera frame size; frames are uint8 HWC RGB */
+  int32_t max_frames;                                 /* capacity of one detector batch (>= models[0].batch_size) */
+  int32_t max_rois_per_frame;                         /* per-edge ROI capacity = max_frames * max_rois_per_frame */
+  int32_t max_queue;                                  /* submitted-but-not-run frames; 0 = 4 * max_frames */
+  int32_t keep_all_tensors;                           /* != 0: every tensor gets its own memory, so octo_debug_get_tensor can
+                                                         read any of them after a run (otherwise only model outputs are safe) */
+} octo_pipeline_desc;
+
+typedef struct octo_pipeline octo_pipeline;
+
+/* Result of one frame.  latency_ms = completion - arrival on the clock of octo_now_ms; all frames of a batch
+ * complete together (Sec. II).  slo_met = latency_ms <= slo_ms (effective throughput counts these, Sec. II). */
+typedef struct { int64_t frame_id; int32_t n_boxes; float latency_ms; int32_t slo_met; int32_t flags; int32_t box_offset; int32_t pad_; } octo_frame_result;
+#define OCTO_FLAG_ROI_OVERFLOW 1
+#define OCTO_FLAG_CAND_OVERFLOW 2
+
+/* ---- the serving calls ---- */
+
+/* Device bytes octo_pipeline_create needs for this description (activations of every model at its capacity,
+ * packed weights, post-processing tables).  Host only. */
+octo_status octo_pipeline_workspace_size(const octo_pipeline_desc* desc, size_t* device_bytes);
+
+/* Build a pipeline.  `device_workspace` (256-byte aligned, `bytes` long, caller-owned, must outlive the handle)
+ * receives packed weights (copied synchronously) and all intermediate tensors.  OCTO_ENOMEM if too small. */
+octo_status octo_pipeline_create(const octo_pipeline_desc* desc, void* device_workspace, size_t bytes, octo_pipeline** out);
+octo_status octo_pipeline_destroy(octo_pipeline* p);
+
+/* Queue n frames.  d_frames[i] is a device pointer to uint8 [src_h][pitch_bytes[i]] with 3*src_w valid bytes per row;
+ * the arrays themselves are host memory.  Frame memory must stay valid until the frame has been collected.
+ * arrival_ms uses the clock of octo_now_ms.  OCTO_ECAP (nothing queued) if the queue would overflow. */
+octo_status octo_submit_frames(octo_pipeline* p, const void* const* d_frames, const size_t* pitch_bytes,
+                               const double* arrival_ms, const int64_t* frame_ids, int32_t n);
+
+/* Form one batch of up to bz (models[0].batch_size, or the value set by octo_set_batch_size) queued frames in
+ * arrival order and enqueue the whole cascade for it on `hip_stream`; no host-device synchronisation.
+ * *n_frames_launched = 0 and OCTO_OK if the queue is empty; OCTO_ESTATE if too many batches are uncollected. */
+octo_status octo_run(octo_pipeline* p, void* hip_stream, int32_t* n_frames_launched);
+
+/* Fetch finished batches, oldest first.  frames[0..*n_frames) and boxes[0..*n_boxes) are host arrays; a frame's
+ * boxes are boxes[box_offset .. box_offset + n_boxes) in keep-list (score) order.  blocking != 0 waits for the
+ * oldest batch; otherwise OCTO_ENOTREADY if none has finished.  A batch is only returned if it fits entirely. */
+octo_status octo_collect(octo_pipeline* p, octo_frame_result* frames, int32_t frame_cap, octo_box* boxes, int32_t box_cap,
+                         int32_t* n_frames, int32_t* n_boxes, int32_t blocking);
+
+octo_status octo_set_batch_size(octo_pipeline* p, int32_t model, int32_t bz);   /* 1 <= bz <= the model's capacity */
+const char* octo_last_error(const octo_pipeline* p);    /* library-owned text, valid until the next call on p (NULL p: last create error) */
+double octo_now_ms(void);                               /* monotonic host clock used for arrival / completion times */
+
+/* Spatial sharing (Sec. III-C: a stream's width is its share of compute): create / destroy a HIP stream
+ * restricted to the compute units whose bit is set (cu_mask: n_words 32-bit words), default priority. */
+octo_status octo_stream_create_masked(const uint32_t* cu_mask, int32_t n_words, void** hip_stream);
+octo_status octo_stream_destroy(void* hip_stream);
+octo_status octo_device_cu_count(int32_t* n_cu);
+
+/* ---- scheduling (host only; Algorithm 1 batch-size part and Algorithm 2 of the paper) ---- */
+
+typedef struct {
+  int32_t parent;                 /* index of the upstream model in the pipeline, -1 for the root */
+  int32_t n_profile;              /* profiled batch sizes (ascending powers of two starting at 1) */
+  int32_t profile_bz[8];
+  float profile_ms[8];            /* L_{m|bz}: batch latency in ms */
+  float rate;                     /* requests per second reaching the model */
+  float burstiness;               /* coefficient of variation of inter-arrival times (Sec. III-B) */
+  float util;                     /* U_m: share of GPU compute (portion width), 0..1 */
+  float weight_mem, inter_mem;    /* W_m, I_m (any one unit) */
+  int32_t bz;                     /* in/out: chosen batch size */
+} octo_sched_model;
+
+typedef struct { octo_sched_model* models; int32_t n_models; float slo_ms; } octo_sched_pipeline;
+typedef struct { int32_t pipeline, model, stream; float start_ms, end_ms, duty_cycle_ms; } octo_placement;  /* stream -1: not placed */
+
+/* Algorithm 1, batch-size search with device and GPU fixed and one instance per model: start at bz = 1, visit
+ * models from the burstiest down, double, drop if the estimated latency exceeds SLO/2, adopt if the estimated
+ * throughput improves, repeat until a sweep adopts nothing.  Writes models[i].bz. */
+octo_status octo_cwd_search(octo_sched_pipeline* p);
+/* Algorithm 2: per model (pipelines in order, models in order) the tightest free portion that contains the
+ * model's window, keeps memory and utilisation within the GPU and whose stream's duty cycle is not longer
+ * than SLO/2.  out has sum(n_models) entries. */
+octo_status octo_coral_schedule(octo_sched_pipeline* ps, int32_t n_pipelines, double gpu_mem, double util_max,
+                                int32_t n_streams, octo_placement* out);
+float octo_est_latency_ms(const octo_sched_pipeline* p);
+float octo_est_throughput(const octo_sched_pipeline* p);
+
+/* Temporal sharing: run only model `model` of the pipeline on `hip_stream` (used by a slot executor that places
+ * each model's portion itself).  Model 0 forms the batch as octo_run does and stops after ROI compaction;
+ * a child model consumes the ROIs of the most recent model-0 run; after the last child the batch becomes
+ * collectable.  octo_run is the same sequence on one stream. */
+octo_status octo_run_model(octo_pipeline* p, int32_t model, void* hip_stream, int32_t* n_items_launched);
+
+/* ---- profiling and parity hooks ---- */
+
+/* Time every layer of a model: each layer is launched `iters` times back to back between two HIP events on
+ * `hip_stream` for `n` items; ms[i] = mean duration of layer i, flops[i] / bytes[i] its dense FLOPs and the
+ * element bytes of its external tensors for n items.  Synchronises the stream. */
+octo_status octo_profile_layers(octo_pipeline* p, int32_t model, int32_t n, int32_t iters, void* hip_stream,
+                                float* ms, double* flops, double* bytes, int32_t cap);
+/* Per-stage GPU time of the most recently collected batch, ms: letterbox, detector layers, decode, top-k, NMS,
+ * compaction, then per edge (crop, child layers, child post-processing).  Only measured after
+ * octo_set_stage_timing(p, 1), which adds event records between stages. */
+octo_status octo_set_stage_timing(octo_pipeline* p, int32_t enable);
+octo_status octo_get_stage_ms(octo_pipeline* p, float* ms, int32_t cap, int32_t* n);
+
+/* Copy a tensor of the last run to host as dense NHWC in the tensor's type (fp32 for fc outputs).
+ * tensor_id as in octo_layer; n_items items.  Synchronises the device. */
+octo_status octo_debug_get_tensor(octo_pipeline* p, int32_t model, int32_t tensor_id, int32_t n_items, void* host_dst, size_t bytes);
+octo_status octo_debug_tensor_shape(octo_pipeline* p, int32_t model, int32_t tensor_id, int32_t* h, int32_t* w, int32_t* c);
+/* Replace (d_head != NULL) or restore (NULL) the head tensor of `level` that decode reads: dense
+ * [items][G][G][A*(5+C)] in the model's type, device memory owned by the caller. */
+octo_status octo_debug_set_head(octo_pipeline* p, int32_t model, int32_t level, const void* d_head);
+/* Run one model on a caller-provided dense input [n][in_h][in_w][in_c] (device, model's type). */
+octo_status octo_debug_run_model(octo_pipeline* p, int32_t model, const void* d_input, int32_t n, void* hip_stream);
+/* Copy post-processing tables of the last batch to host (synchronises): per item candidate count, top-k list,
+ * keep-list; per edge ROI table. */
+octo_status octo_debug_get_detections(octo_pipeline* p, int32_t model, int32_t item, int32_t* cand_count,
+                                      octo_cand* top, int32_t top_cap, int32_t* n_top, int32_t* keep, int32_t keep_cap, int32_t* n_keep);
+octo_status octo_debug_get_rois(octo_pipeline* p, int32_t edge, octo_roi* rois, int32_t cap, int32_t* n_rois);
+octo_status octo_debug_get_labels(octo_pipeline* p, int32_t edge, int32_t* labels, int32_t cap, int32_t* n);
+
+/* ---- stage-level calls: the same kernels the pipeline launches, on caller-owned device buffers ---- */
+
+/* Letterbox + normalise: aspect-preserving bilinear resize (half-pixel centres, no antialias) of n uint8 HWC
+ * frames into dst [n][dst_h][dst_w][3] of `dtype`, centred, padded with pad_value, out = px*scale + bias.
+ * d_frame_ptrs / d_pitches: device arrays of n frame pointers / row pitches. */
+octo_status octo_op_letterbox(const void* d_frame_ptrs, const void* d_pitches, int32_t n, int32_t src_h, int32_t src_w,
+                              void* d_dst, int32_t dst_h, int32_t dst_w, int32_t dtype, const float* scale3, const float* bias3,
+                              int32_t pad_value, void* hip_stream);
+/* Crop-resize: for ROI j < min(*d_n_rois, cap) bilinear stretch of its source box from frame rois[j].frame
+ * (clamped to 0..n_frames-1) into dst [cap][out_h][out_w][3]. */
+octo_status octo_op_crop_resize(const void* d_frame_ptrs, const void* d_pitches, int32_t n_frames, int32_t src_h, int32_t src_w,
+                                const octo_roi* d_rois, const int32_t* d_n_rois, int32_t cap,
+                                void* d_dst, int32_t out_h, int32_t out_w, int32_t dtype, const float* scale3, const float* bias3,
+                                void* hip_stream);
+/* Decode + threshold of n items: d_heads[l] dense [n][G_l][G_l][A*(5+C)].  Appends candidates with
+ * score > thr to d_cand[item*cap ...] (order unspecified), d_count[item] = number found (may exceed cap:
+ * then only cap were stored).  Geometry and thresholds are read from `model`. */
+octo_status octo_op_decode(const octo_model_desc* model, const void* const* d_heads, int32_t n,
+                           octo_cand* d_cand, int32_t* d_count, int32_t cap, void* hip_stream);
+/* Top-k of each item's list by (score descending, idx ascending): d_out[item*k_cap ...] sorted, d_out_count[item]
+ * = min(count, k).  k <= k_cap. */
+octo_status octo_op_topk(const octo_cand* d_in, const int32_t* d_in_count, int32_t in_cap, int32_t n, int32_t k,
+                         octo_cand* d_out, int32_t* d_out_count, int32_t k_cap, void* hip_stream);
+/* Greedy class-wise NMS over sorted lists; d_keep[item*max_det ...] = kept positions ascending, cut to max_det.
+ * d_mask_scratch: octo_op_nms_scratch_bytes(n, k_cap) bytes.  k_cap must be a multiple of 64, at most 4096. */
+octo_status octo_op_nms(const octo_cand* d_top, const int32_t* d_top_count, int32_t k_cap, int32_t n, float iou_thr, int32_t max_det,
+                        void* d_mask_scratch, int32_t* d_keep, int32_t* d_n_keep, void* hip_stream);
+size_t octo_op_nms_scratch_bytes(int32_t n, int32_t k_cap);
+/* ROI compaction for one edge: kept boxes with class bit set, in (item, rank) order, converted to source pixels
+ * (letterbox undone for a src_h x src_w frame letterboxed into in_h x in_w) and clamped.
+ * d_n_rois[0] = count (clamped to cap); d_boxes [n][max_det] receives every kept box in source pixels. */
+octo_status octo_op_compact(const octo_cand* d_top, int32_t k_cap, const int32_t* d_keep, const int32_t* d_n_keep, int32_t max_det,
+                            int32_t n, int32_t src_h, int32_t src_w, int32_t in_h, int32_t in_w, const uint64_t* class_mask2,
+                            octo_roi* d_rois, int32_t* d_n_rois, int32_t cap, int32_t* d_roi_of, octo_box* d_boxes, int32_t* d_flags,
+                            void* hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* OCTO_H_ */

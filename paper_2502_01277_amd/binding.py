@@ -1,0 +1,521 @@
+"""ctypes binding over libocto.so (see include/octo.h).
+
+Argument marshalling only: every step of the path runs inside the library's HIP
+kernels.  PyTorch appears here solely as the owner of device memory and streams.
+The binding fails loudly when the shared library is missing; there is no CPU
+fallback.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import List, Optional, Sequence
+
+import numpy as np
+
+from . import zoo
+from .synth import to_storage
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libocto.so")
+
+MAX_LEVELS, MAX_ANCHORS, MAX_EDGES, MAX_CHILD_LABELS, MAX_LAYER_INPUTS = 3, 3, 4, 2, 4
+OK, EINVAL, ENOMEM, ECAP, ESTATE, EHIP, ENOTREADY = 0, -1, -2, -3, -4, -5, -6
+DTYPES = {"f32": 0, "f16": 1, "bf16": 2}
+OPS = {"conv": 0, "maxpool": 1, "upsample2x": 2, "concat": 3, "add": 4, "gap": 5, "fc": 6}
+KINDS = {"detector": 0, "classifier": 1}
+
+CAND_DTYPE = np.dtype([("x1", "<f4"), ("y1", "<f4"), ("x2", "<f4"), ("y2", "<f4"), ("score", "<f4"),
+                       ("cls", "<i4"), ("idx", "<i4"), ("pad_", "<i4")])
+ROI_DTYPE = np.dtype([("frame", "<i4"), ("rank", "<i4"), ("cls", "<i4"), ("pad_", "<i4"),
+                      ("x1", "<f4"), ("y1", "<f4"), ("x2", "<f4"), ("y2", "<f4")])
+BOX_DTYPE = np.dtype([("x1", "<f4"), ("y1", "<f4"), ("x2", "<f4"), ("y2", "<f4"), ("score", "<f4"),
+                      ("cls", "<i4"), ("child_label", "<i4", (MAX_CHILD_LABELS,))])
+FRAME_DTYPE = np.dtype([("frame_id", "<i8"), ("n_boxes", "<i4"), ("latency_ms", "<f4"), ("slo_met", "<i4"),
+                        ("flags", "<i4"), ("box_offset", "<i4"), ("pad_", "<i4")])
+
+
+class OctoLayer(C.Structure):
+    _fields_ = [("op", C.c_int32), ("n_in", C.c_int32), ("in_", C.c_int32 * MAX_LAYER_INPUTS),
+                ("cout", C.c_int32), ("kh", C.c_int32), ("kw", C.c_int32), ("stride", C.c_int32), ("pad", C.c_int32),
+                ("act", C.c_int32), ("res_mode", C.c_int32), ("weight", C.c_void_p), ("bias", C.c_void_p)]
+
+
+class OctoModelDesc(C.Structure):
+    _fields_ = [("name", C.c_char_p), ("dtype", C.c_int32), ("kind", C.c_int32),
+                ("in_h", C.c_int32), ("in_w", C.c_int32), ("in_c", C.c_int32),
+                ("layers", C.POINTER(OctoLayer)), ("n_layers", C.c_int32),
+                ("outputs", C.c_int32 * MAX_LEVELS), ("n_outputs", C.c_int32),
+                ("n_classes", C.c_int32), ("n_anchors", C.c_int32), ("stride", C.c_int32 * MAX_LEVELS),
+                ("anchors", C.c_float * (MAX_LEVELS * MAX_ANCHORS * 2)),
+                ("score_thr", C.c_float), ("iou_thr", C.c_float), ("topk", C.c_int32), ("max_det", C.c_int32),
+                ("norm_scale", C.c_float * 3), ("norm_bias", C.c_float * 3), ("pad_value", C.c_int32),
+                ("batch_size", C.c_int32)]
+
+
+class OctoEdge(C.Structure):
+    _fields_ = [("parent", C.c_int32), ("child", C.c_int32), ("class_mask", C.c_uint64 * 2)]
+
+
+class OctoPipelineDesc(C.Structure):
+    _fields_ = [("models", C.POINTER(OctoModelDesc)), ("n_models", C.c_int32),
+                ("edges", C.POINTER(OctoEdge)), ("n_edges", C.c_int32), ("slo_ms", C.c_float),
+                ("src_h", C.c_int32), ("src_w", C.c_int32), ("max_frames", C.c_int32),
+                ("max_rois_per_frame", C.c_int32), ("max_queue", C.c_int32), ("keep_all_tensors", C.c_int32)]
+
+
+class OctoSchedModel(C.Structure):
+    _fields_ = [("parent", C.c_int32), ("n_profile", C.c_int32), ("profile_bz", C.c_int32 * 8),
+                ("profile_ms", C.c_float * 8), ("rate", C.c_float), ("burstiness", C.c_float), ("util", C.c_float),
+                ("weight_mem", C.c_float), ("inter_mem", C.c_float), ("bz", C.c_int32)]
+
+
+class OctoSchedPipeline(C.Structure):
+    _fields_ = [("models", C.POINTER(OctoSchedModel)), ("n_models", C.c_int32), ("slo_ms", C.c_float)]
+
+
+class OctoPlacement(C.Structure):
+    _fields_ = [("pipeline", C.c_int32), ("model", C.c_int32), ("stream", C.c_int32),
+                ("start_ms", C.c_float), ("end_ms", C.c_float), ("duty_cycle_ms", C.c_float)]
+
+
+# Every symbol include/octo.h declares.
+EXPORTS = [
+    "octo_pipeline_workspace_size", "octo_pipeline_create", "octo_pipeline_destroy", "octo_submit_frames", "octo_run",
+    "octo_collect", "octo_set_batch_size", "octo_last_error", "octo_now_ms", "octo_stream_create_masked",
+    "octo_stream_destroy", "octo_device_cu_count", "octo_cwd_search", "octo_coral_schedule", "octo_est_latency_ms",
+    "octo_est_throughput", "octo_run_model", "octo_profile_layers", "octo_set_stage_timing", "octo_get_stage_ms",
+    "octo_debug_get_tensor", "octo_debug_tensor_shape", "octo_debug_set_head", "octo_debug_run_model",
+    "octo_debug_get_detections", "octo_debug_get_rois", "octo_debug_get_labels", "octo_op_letterbox",
+    "octo_op_crop_resize", "octo_op_decode", "octo_op_topk", "octo_op_nms", "octo_op_nms_scratch_bytes", "octo_op_compact",
+]
+
+_lib = None
+
+
+def lib() -> C.CDLL:
+    """Load libocto.so (built by paper_2502_01277_amd.build); raises if it is not there."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError("libocto.so not found at %s - build it with `python -m paper_2502_01277_amd.build`" % LIB_PATH)
+        L = C.CDLL(LIB_PATH)
+        L.octo_last_error.restype = C.c_char_p
+        L.octo_last_error.argtypes = [C.c_void_p]
+        L.octo_now_ms.restype = C.c_double
+        L.octo_op_nms_scratch_bytes.restype = C.c_size_t
+        L.octo_est_latency_ms.restype = C.c_float
+        L.octo_est_throughput.restype = C.c_float
+        vp, i32, f32 = C.c_void_p, C.c_int32, C.c_float
+        L.octo_pipeline_workspace_size.argtypes = [vp, vp]
+        L.octo_pipeline_create.argtypes = [vp, vp, C.c_size_t, vp]
+        L.octo_pipeline_destroy.argtypes = [vp]
+        L.octo_submit_frames.argtypes = [vp, vp, vp, vp, vp, i32]
+        L.octo_run.argtypes = [vp, vp, vp]
+        L.octo_run_model.argtypes = [vp, i32, vp, vp]
+        L.octo_collect.argtypes = [vp, vp, i32, vp, i32, vp, vp, i32]
+        L.octo_set_batch_size.argtypes = [vp, i32, i32]
+        L.octo_stream_create_masked.argtypes = [vp, i32, vp]
+        L.octo_stream_destroy.argtypes = [vp]
+        L.octo_device_cu_count.argtypes = [vp]
+        L.octo_cwd_search.argtypes = [vp]
+        L.octo_coral_schedule.argtypes = [vp, i32, C.c_double, C.c_double, i32, vp]
+        L.octo_est_latency_ms.argtypes = [vp]
+        L.octo_est_throughput.argtypes = [vp]
+        L.octo_profile_layers.argtypes = [vp, i32, i32, i32, vp, vp, vp, vp, i32]
+        L.octo_set_stage_timing.argtypes = [vp, i32]
+        L.octo_get_stage_ms.argtypes = [vp, vp, i32, vp]
+        L.octo_debug_get_tensor.argtypes = [vp, i32, i32, i32, vp, C.c_size_t]
+        L.octo_debug_tensor_shape.argtypes = [vp, i32, i32, vp, vp, vp]
+        L.octo_debug_set_head.argtypes = [vp, i32, i32, vp]
+        L.octo_debug_run_model.argtypes = [vp, i32, vp, i32, vp]
+        L.octo_debug_get_detections.argtypes = [vp, i32, i32, vp, vp, i32, vp, vp, i32, vp]
+        L.octo_debug_get_rois.argtypes = [vp, i32, vp, i32, vp]
+        L.octo_debug_get_labels.argtypes = [vp, i32, vp, i32, vp]
+        L.octo_op_letterbox.argtypes = [vp, vp, i32, i32, i32, vp, i32, i32, i32, vp, vp, i32, vp]
+        L.octo_op_crop_resize.argtypes = [vp, vp, i32, i32, i32, vp, vp, i32, vp, i32, i32, i32, vp, vp, vp]
+        L.octo_op_decode.argtypes = [vp, vp, i32, vp, vp, i32, vp]
+        L.octo_op_topk.argtypes = [vp, vp, i32, i32, i32, vp, vp, i32, vp]
+        L.octo_op_nms.argtypes = [vp, vp, i32, i32, f32, i32, vp, vp, vp, vp]
+        L.octo_op_nms_scratch_bytes.argtypes = [i32, i32]
+        L.octo_op_compact.argtypes = [vp, i32, vp, vp, i32, i32, i32, i32, i32, i32, vp, vp, vp, i32, vp, vp, vp, vp]
+        _lib = L
+    return _lib
+
+
+class OctoError(RuntimeError):
+    def __init__(self, status, msg):
+        super().__init__("octo status %d: %s" % (status, msg))
+        self.status = status
+
+
+def _torch():
+    import torch
+    return torch
+
+
+def torch_dtype(dtype: str):
+    t = _torch()
+    return {"f32": t.float32, "f16": t.float16, "bf16": t.bfloat16}[dtype]
+
+
+def to_device(x_f32: np.ndarray, dtype: str, device="cuda"):
+    """fp32 numpy values (representable in `dtype`) -> device tensor of that type."""
+    t = _torch()
+    raw = to_storage(x_f32, dtype)
+    if dtype == "bf16":
+        return t.from_numpy(raw.view(np.int16)).to(device).view(t.bfloat16)
+    return t.from_numpy(raw).to(device)
+
+
+def _stream_ptr(stream) -> int:
+    if stream is None:
+        return int(_torch().cuda.current_stream().cuda_stream)
+    if isinstance(stream, int):
+        return stream
+    return int(stream.cuda_stream)
+
+
+def model_desc(m: zoo.ModelSpec, keep: list) -> OctoModelDesc:
+    """Marshal a ModelSpec; host arrays the struct points to are appended to `keep`."""
+    layers = (OctoLayer * len(m.layers))()
+    for i, L in enumerate(m.layers):
+        o = layers[i]
+        o.op = OPS[L.op]; o.n_in = len(L.inputs)
+        for k, t in enumerate(L.inputs):
+            o.in_[k] = t
+        o.cout, o.kh, o.kw, o.stride, o.pad, o.act, o.res_mode = L.cout, L.kh, L.kw, L.stride, L.pad, L.act, L.res_mode
+        if L.weight is not None:
+            w = np.ascontiguousarray(to_storage(L.weight, m.dtype))
+            b = np.ascontiguousarray(L.bias, dtype=np.float32)
+            keep += [w, b]
+            o.weight = w.ctypes.data; o.bias = b.ctypes.data
+    keep.append(layers)
+    d = OctoModelDesc()
+    name = m.name.encode(); keep.append(name)
+    d.name = name; d.dtype = DTYPES[m.dtype]; d.kind = KINDS[m.kind]
+    d.in_h, d.in_w, d.in_c = m.in_h, m.in_w, m.in_c
+    d.layers = layers; d.n_layers = len(m.layers)
+    for k, t in enumerate(m.outputs):
+        d.outputs[k] = t
+    d.n_outputs = len(m.outputs)
+    d.n_classes, d.n_anchors = m.n_classes, m.n_anchors
+    for k, s in enumerate(m.strides):
+        d.stride[k] = s
+    if m.anchors is not None:
+        for l in range(m.anchors.shape[0]):
+            for a in range(m.anchors.shape[1]):
+                for j in range(2):
+                    d.anchors[(l * MAX_ANCHORS + a) * 2 + j] = float(m.anchors[l, a, j])
+    d.score_thr, d.iou_thr, d.topk, d.max_det = m.score_thr, m.iou_thr, m.topk, m.max_det
+    for c in range(3):
+        d.norm_scale[c] = m.norm_scale[c]; d.norm_bias[c] = m.norm_bias[c]
+    d.pad_value = m.pad_value; d.batch_size = m.batch_size
+    return d
+
+
+def pipeline_desc(p: zoo.PipelineSpec, keep: list, keep_all_tensors=False) -> OctoPipelineDesc:
+    models = (OctoModelDesc * len(p.models))(*[model_desc(m, keep) for m in p.models])
+    edges = (OctoEdge * max(1, len(p.edges)))()
+    for i, e in enumerate(p.edges):
+        edges[i].parent, edges[i].child = e.parent, e.child
+        edges[i].class_mask[0] = e.class_mask & ((1 << 64) - 1)
+        edges[i].class_mask[1] = (e.class_mask >> 64) & ((1 << 64) - 1)
+    keep += [models, edges]
+    d = OctoPipelineDesc()
+    d.models = models; d.n_models = len(p.models); d.edges = edges; d.n_edges = len(p.edges)
+    d.slo_ms = p.slo_ms; d.src_h, d.src_w = p.src_h, p.src_w
+    d.max_frames, d.max_rois_per_frame = p.max_frames, p.max_rois_per_frame
+    d.max_queue = 0; d.keep_all_tensors = 1 if keep_all_tensors else 0
+    return d
+
+
+class Pipeline:
+    """Owner of one octo_pipeline handle and of the device workspace behind it."""
+
+    def __init__(self, spec: zoo.PipelineSpec, keep_all_tensors=False, device="cuda"):
+        t = _torch()
+        self.L = lib()
+        self.spec = spec
+        self._keep: list = []
+        self.desc = pipeline_desc(spec, self._keep, keep_all_tensors)
+        nbytes = C.c_size_t(0)
+        st = self.L.octo_pipeline_workspace_size(C.byref(self.desc), C.byref(nbytes))
+        if st != OK:
+            raise OctoError(st, self.L.octo_last_error(None).decode())
+        self.workspace_bytes = nbytes.value
+        self.workspace = t.empty(nbytes.value + 256, dtype=t.uint8, device=device)
+        base = (self.workspace.data_ptr() + 255) & ~255
+        self.h = C.c_void_p()
+        st = self.L.octo_pipeline_create(C.byref(self.desc), base, nbytes.value, C.byref(self.h))
+        if st != OK:
+            raise OctoError(st, self.L.octo_last_error(None).decode())
+        self._frames_alive: list = []
+
+    def _check(self, st, ok=(OK,)):
+        if st not in ok:
+            raise OctoError(st, self.L.octo_last_error(self.h).decode())
+        return st
+
+    def close(self):
+        if self.h:
+            self.L.octo_pipeline_destroy(self.h)
+            self.h = C.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    # ---- serving calls ----
+    def submit(self, frames: Sequence, arrival_ms: Optional[Sequence[float]] = None, frame_ids: Optional[Sequence[int]] = None):
+        """frames: device uint8 tensors [H][W][3] (rows may be strided)."""
+        n = len(frames)
+        ptrs = (C.c_void_p * n)(*[int(f.data_ptr()) for f in frames])
+        pitches = (C.c_size_t * n)(*[int(f.stride(0)) for f in frames])
+        arr = (C.c_double * n)(*arrival_ms) if arrival_ms is not None else None
+        ids = (C.c_int64 * n)(*frame_ids) if frame_ids is not None else None
+        self._frames_alive.append(list(frames))
+        if len(self._frames_alive) > 16:
+            self._frames_alive.pop(0)
+        return self._check(self.L.octo_submit_frames(self.h, ptrs, pitches, arr, ids, n))
+
+    def run(self, stream=None) -> int:
+        n = C.c_int32(0)
+        self._check(self.L.octo_run(self.h, _stream_ptr(stream), C.byref(n)))
+        return n.value
+
+    def run_model(self, model: int, stream=None) -> int:
+        n = C.c_int32(0)
+        self._check(self.L.octo_run_model(self.h, model, _stream_ptr(stream), C.byref(n)))
+        return n.value
+
+    def collect(self, blocking=True, frame_cap=None, box_cap=None):
+        frame_cap = frame_cap or 4 * self.spec.max_frames
+        box_cap = box_cap or frame_cap * self.spec.models[0].max_det
+        frames = np.zeros(frame_cap, FRAME_DTYPE)
+        boxes = np.zeros(box_cap, BOX_DTYPE)
+        nf, nb = C.c_int32(0), C.c_int32(0)
+        st = self._check(self.L.octo_collect(self.h, frames.ctypes.data, frame_cap, boxes.ctypes.data, box_cap,
+                                             C.byref(nf), C.byref(nb), 1 if blocking else 0), ok=(OK, ECAP, ENOTREADY))
+        return frames[:nf.value], boxes[:nb.value], st
+
+    def set_batch_size(self, model: int, bz: int):
+        self._check(self.L.octo_set_batch_size(self.h, model, bz))
+
+    # ---- hooks ----
+    def tensor_shape(self, model: int, tid: int):
+        h, w, c = C.c_int32(), C.c_int32(), C.c_int32()
+        self._check(self.L.octo_debug_tensor_shape(self.h, model, tid, C.byref(h), C.byref(w), C.byref(c)))
+        return h.value, w.value, c.value
+
+    def get_tensor(self, model: int, tid: int, n: int) -> np.ndarray:
+        """Tensor of the last run as fp32 numpy [n][h][w][c]."""
+        from .synth import from_storage
+        h, w, c = self.tensor_shape(model, tid)
+        m = self.spec.models[model]
+        is_fc = tid > 0 and m.layers[tid - 1].op == "fc"
+        dt = "f32" if is_fc else m.dtype
+        raw = np.empty((n, h, w, c), {"f32": np.float32, "f16": np.float16, "bf16": np.uint16}[dt])
+        self._check(self.L.octo_debug_get_tensor(self.h, model, tid, n, raw.ctypes.data, raw.nbytes))
+        return from_storage(raw, dt)
+
+    def set_head(self, model: int, level: int, tensor):
+        self._check(self.L.octo_debug_set_head(self.h, model, level, None if tensor is None else int(tensor.data_ptr())))
+
+    def run_model_on(self, model: int, x, stream=None):
+        self._check(self.L.octo_debug_run_model(self.h, model, int(x.data_ptr()), int(x.shape[0]), _stream_ptr(stream)))
+
+    def get_detections(self, model: int, item: int):
+        m = self.spec.models[model]
+        kc = (min(m.topk, m.n_cand()) + 63) // 64 * 64
+        top = np.zeros(kc, CAND_DTYPE)
+        keep = np.zeros(m.max_det, np.int32)
+        cc, nt, nk = C.c_int32(), C.c_int32(), C.c_int32()
+        self._check(self.L.octo_debug_get_detections(self.h, model, item, C.byref(cc), top.ctypes.data, kc, C.byref(nt),
+                                                     keep.ctypes.data, m.max_det, C.byref(nk)))
+        return cc.value, top[:nt.value], keep[:nk.value]
+
+    def get_rois(self, edge: int):
+        cap = self.spec.max_frames * self.spec.max_rois_per_frame
+        rois = np.zeros(cap, ROI_DTYPE)
+        n = C.c_int32()
+        self._check(self.L.octo_debug_get_rois(self.h, edge, rois.ctypes.data, cap, C.byref(n)))
+        return rois[:min(n.value, cap)]
+
+    def get_labels(self, edge: int):
+        cap = self.spec.max_frames * self.spec.max_rois_per_frame
+        lab = np.zeros(cap, np.int32)
+        n = C.c_int32()
+        self._check(self.L.octo_debug_get_labels(self.h, edge, lab.ctypes.data, cap, C.byref(n)))
+        return lab[:min(n.value, cap)]
+
+    def profile_layers(self, model: int, n: int, iters: int = 10, stream=None):
+        nl = len(self.spec.models[model].layers)
+        ms = np.zeros(nl, np.float32); fl = np.zeros(nl, np.float64); by = np.zeros(nl, np.float64)
+        self._check(self.L.octo_profile_layers(self.h, model, n, iters, _stream_ptr(stream), ms.ctypes.data,
+                                               fl.ctypes.data, by.ctypes.data, nl))
+        return ms, fl, by
+
+    def set_stage_timing(self, on: bool):
+        self._check(self.L.octo_set_stage_timing(self.h, 1 if on else 0))
+
+    def stage_ms(self) -> np.ndarray:
+        ms = np.zeros(32, np.float32); n = C.c_int32()
+        self._check(self.L.octo_get_stage_ms(self.h, ms.ctypes.data, 32, C.byref(n)))
+        return ms[:n.value]
+
+
+# ---- stage-level calls -------------------------------------------------------
+def _st(st):
+    if st != OK:
+        raise OctoError(st, "stage call failed")
+
+
+def frame_tables(frames: Sequence):
+    """Device tables (pointers, pitches) for a list of device uint8 frames."""
+    t = _torch()
+    ptrs = t.tensor([int(f.data_ptr()) for f in frames], dtype=t.int64, device=frames[0].device)
+    pitches = t.tensor([int(f.stride(0)) for f in frames], dtype=t.int64, device=frames[0].device)
+    return ptrs, pitches
+
+
+def op_letterbox(frames: Sequence, dst_h, dst_w, dtype: str, scale=(1 / 255.0,) * 3, bias=(0.0,) * 3, pad_value=114, stream=None):
+    t = _torch()
+    ptrs, pitches = frame_tables(frames)
+    n, (sh, sw) = len(frames), frames[0].shape[:2]
+    out = t.empty((n, dst_h, dst_w, 3), dtype=torch_dtype(dtype), device=frames[0].device)
+    sc = (C.c_float * 3)(*scale); bi = (C.c_float * 3)(*bias)
+    _st(lib().octo_op_letterbox(ptrs.data_ptr(), pitches.data_ptr(), n, sh, sw, out.data_ptr(), dst_h, dst_w, DTYPES[dtype],
+                                sc, bi, pad_value, _stream_ptr(stream)))
+    return out
+
+
+def op_crop_resize(frames: Sequence, rois: np.ndarray, out_h, out_w, dtype: str, cap=None, scale=(1 / 255.0,) * 3,
+                   bias=(0.0,) * 3, stream=None):
+    t = _torch()
+    ptrs, pitches = frame_tables(frames)
+    sh, sw = frames[0].shape[:2]
+    cap = cap or max(1, len(rois))
+    d_rois = t.from_numpy(np.ascontiguousarray(rois).view(np.uint8).reshape(-1)).to(frames[0].device)
+    if len(rois) == 0:
+        d_rois = t.zeros(32, dtype=t.uint8, device=frames[0].device)
+    d_n = t.tensor([len(rois)], dtype=t.int32, device=frames[0].device)
+    out = t.zeros((cap, out_h, out_w, 3), dtype=torch_dtype(dtype), device=frames[0].device)
+    sc = (C.c_float * 3)(*scale); bi = (C.c_float * 3)(*bias)
+    _st(lib().octo_op_crop_resize(ptrs.data_ptr(), pitches.data_ptr(), len(frames), sh, sw, d_rois.data_ptr(), d_n.data_ptr(), cap,
+                                  out.data_ptr(), out_h, out_w, DTYPES[dtype], sc, bi, _stream_ptr(stream)))
+    return out
+
+
+def op_decode(m: zoo.ModelSpec, heads: Sequence, cap=None, stream=None):
+    """heads: device tensors [n][G][G][A*(5+C)] of the model's type.  Returns (cand tensor uint8 view, counts)."""
+    t = _torch()
+    keep: list = []
+    hdr = zoo.ModelSpec(name=m.name, dtype=m.dtype, in_h=m.in_h, in_w=m.in_w, kind=m.kind)   # geometry and thresholds only
+    hdr.outputs = list(range(1, len(m.outputs) + 1))
+    hdr.n_classes, hdr.n_anchors, hdr.grids, hdr.strides, hdr.anchors = m.n_classes, m.n_anchors, m.grids, m.strides, m.anchors
+    hdr.score_thr, hdr.iou_thr, hdr.topk, hdr.max_det = m.score_thr, m.iou_thr, m.topk, m.max_det
+    d = model_desc(hdr, keep)
+    n = int(heads[0].shape[0])
+    cap = cap or m.n_cand()
+    cand = t.zeros((n, cap, 32), dtype=t.uint8, device=heads[0].device)
+    count = t.zeros(n, dtype=t.int32, device=heads[0].device)
+    hp = (C.c_void_p * len(heads))(*[int(h.data_ptr()) for h in heads])
+    _st(lib().octo_op_decode(C.byref(d), hp, n, cand.data_ptr(), count.data_ptr(), cap, _stream_ptr(stream)))
+    return cand, count
+
+
+def cands_to_device(lists: List[np.ndarray], cap: int, device="cuda"):
+    """Pack per-item candidate arrays (CAND_DTYPE) into a device table [n][cap] plus counts."""
+    t = _torch()
+    n = len(lists)
+    host = np.zeros((n, cap), CAND_DTYPE)
+    for i, l in enumerate(lists):
+        host[i, :len(l)] = l
+    cand = t.from_numpy(host.view(np.uint8).reshape(n, cap, 32)).to(device)
+    count = t.tensor([len(l) for l in lists], dtype=t.int32, device=device)
+    return cand, count
+
+
+def cands_from_device(cand, count) -> List[np.ndarray]:
+    c = cand.cpu().numpy().reshape(cand.shape[0], cand.shape[1] * 32).view(CAND_DTYPE)
+    k = count.cpu().numpy()
+    return [c[i, :min(int(k[i]), c.shape[1])].copy() for i in range(c.shape[0])]
+
+
+def op_topk(cand, count, k: int, stream=None):
+    t = _torch()
+    n, in_cap = int(cand.shape[0]), int(cand.shape[1])
+    k_cap = (k + 63) // 64 * 64
+    out = t.zeros((n, k_cap, 32), dtype=t.uint8, device=cand.device)
+    oc = t.zeros(n, dtype=t.int32, device=cand.device)
+    _st(lib().octo_op_topk(cand.data_ptr(), count.data_ptr(), in_cap, n, k, out.data_ptr(), oc.data_ptr(), k_cap, _stream_ptr(stream)))
+    return out, oc
+
+
+def op_nms(top, top_count, iou_thr: float, max_det: int, stream=None):
+    t = _torch()
+    n, k_cap = int(top.shape[0]), int(top.shape[1])
+    scratch = t.empty(max(8, lib().octo_op_nms_scratch_bytes(n, k_cap)), dtype=t.uint8, device=top.device)
+    keep = t.zeros((n, max_det), dtype=t.int32, device=top.device)
+    nk = t.zeros(n, dtype=t.int32, device=top.device)
+    _st(lib().octo_op_nms(top.data_ptr(), top_count.data_ptr(), k_cap, n, iou_thr, max_det, scratch.data_ptr(),
+                          keep.data_ptr(), nk.data_ptr(), _stream_ptr(stream)))
+    return keep, nk
+
+
+def op_compact(top, keep, n_keep, src_hw, in_hw, class_mask: int, cap: int, stream=None):
+    t = _torch()
+    n, k_cap, max_det = int(top.shape[0]), int(top.shape[1]), int(keep.shape[1])
+    dev = top.device
+    rois = t.zeros((max(cap, 1), 32), dtype=t.uint8, device=dev)
+    n_roi = t.zeros(1, dtype=t.int32, device=dev)
+    roi_of = t.full((n, max_det), -1, dtype=t.int32, device=dev)
+    boxes = t.zeros((n, max_det, 32), dtype=t.uint8, device=dev)
+    flags = t.zeros(n, dtype=t.int32, device=dev)
+    cm = (C.c_uint64 * 2)(class_mask & ((1 << 64) - 1), (class_mask >> 64) & ((1 << 64) - 1))
+    _st(lib().octo_op_compact(top.data_ptr(), k_cap, keep.data_ptr(), n_keep.data_ptr(), max_det, n, src_hw[0], src_hw[1],
+                              in_hw[0], in_hw[1], cm, rois.data_ptr(), n_roi.data_ptr(), cap, roi_of.data_ptr(),
+                              boxes.data_ptr(), flags.data_ptr(), _stream_ptr(stream)))
+    nr = int(n_roi.cpu()[0])
+    r = rois.cpu().numpy().reshape(-1).view(ROI_DTYPE)[:nr].copy()
+    b = boxes.cpu().numpy().reshape(n, max_det * 32).view(BOX_DTYPE)
+    return r, roi_of.cpu().numpy(), b, flags.cpu().numpy()
+
+
+# ---- scheduling ---------------------------------------------------------------
+def sched_pipeline(models: Sequence[dict], slo_ms: float, keep: list) -> OctoSchedPipeline:
+    """models: dicts with parent, profile {bz: ms}, rate, burstiness, util, weight_mem, inter_mem, bz."""
+    arr = (OctoSchedModel * len(models))()
+    for i, m in enumerate(models):
+        a = arr[i]
+        a.parent = m["parent"]
+        bzs = sorted(m["profile"])
+        a.n_profile = len(bzs)
+        for k, b in enumerate(bzs):
+            a.profile_bz[k] = b; a.profile_ms[k] = m["profile"][b]
+        a.rate = m.get("rate", 15.0); a.burstiness = m.get("burstiness", 0.0); a.util = m.get("util", 0.25)
+        a.weight_mem = m.get("weight_mem", 0.0); a.inter_mem = m.get("inter_mem", 0.0); a.bz = m.get("bz", 1)
+    keep.append(arr)
+    p = OctoSchedPipeline()
+    p.models = arr; p.n_models = len(models); p.slo_ms = slo_ms
+    return p
+
+
+def cwd_search(models: Sequence[dict], slo_ms: float) -> List[int]:
+    keep: list = []
+    p = sched_pipeline(models, slo_ms, keep)
+    _st(lib().octo_cwd_search(C.byref(p)))
+    return [p.models[i].bz for i in range(len(models))]
+
+
+def coral_schedule(pipelines: Sequence[tuple], mem: float, util_max: float, n_streams: int):
+    """pipelines: (models, slo_ms) tuples with bz already chosen.  Returns placement tuples."""
+    keep: list = []
+    ps = (OctoSchedPipeline * len(pipelines))(*[sched_pipeline(m, slo, keep) for m, slo in pipelines])
+    total = sum(len(m) for m, _ in pipelines)
+    out = (OctoPlacement * total)()
+    _st(lib().octo_coral_schedule(ps, len(pipelines), mem, util_max, n_streams, out))
+    return [(o.pipeline, o.model, o.stream, o.start_ms, o.end_ms, o.duty_cycle_ms) for o in out]

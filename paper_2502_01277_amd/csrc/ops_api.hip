@@ -1,0 +1,103 @@
+// Stage-level C ABI entry points: argument checks and one launch each of the
+// kernels the pipeline itself uses, on caller-owned device buffers.
+#include <cstring>
+
+#include "octo_internal.h"
+
+using namespace octo;
+
+namespace {
+octo_status from_hip(hipError_t e) { return e == hipSuccess ? OCTO_OK : (e == hipErrorInvalidValue ? OCTO_EINVAL : OCTO_EHIP); }
+bool valid_dtype(int dt) { return dt == OCTO_F32 || dt == OCTO_F16 || dt == OCTO_BF16; }
+}  // namespace
+
+extern "C" {
+
+octo_status octo_op_letterbox(const void* d_frame_ptrs, const void* d_pitches, int32_t n, int32_t src_h, int32_t src_w,
+                              void* d_dst, int32_t dst_h, int32_t dst_w, int32_t dtype, const float* scale3, const float* bias3,
+                              int32_t pad_value, void* hip_stream) {
+  if (!d_frame_ptrs || !d_pitches || !d_dst || !scale3 || !bias3 || n < 0 || src_h <= 0 || src_w <= 0 || dst_h <= 0 || dst_w <= 0 ||
+      !valid_dtype(dtype) || pad_value < 0 || pad_value > 255 || src_h > 16384 || src_w > 16384 || dst_h > 16384 || dst_w > 16384)
+    return OCTO_EINVAL;
+  ResizeArgs a{};
+  a.frames = (const uint8_t* const*)d_frame_ptrs; a.pitches = (const size_t*)d_pitches; a.src_h = src_h; a.src_w = src_w;
+  a.dst = d_dst; a.dst_h = dst_h; a.dst_w = dst_w; a.pad_value = pad_value; a.n = n; a.n_frames = n;
+  for (int c = 0; c < 3; ++c) { a.scale[c] = scale3[c]; a.bias[c] = bias3[c]; }
+  return from_hip(launch_letterbox(dtype, a, (hipStream_t)hip_stream));
+}
+
+octo_status octo_op_crop_resize(const void* d_frame_ptrs, const void* d_pitches, int32_t n_frames, int32_t src_h, int32_t src_w,
+                                const octo_roi* d_rois, const int32_t* d_n_rois, int32_t cap,
+                                void* d_dst, int32_t out_h, int32_t out_w, int32_t dtype, const float* scale3, const float* bias3,
+                                void* hip_stream) {
+  if (!d_frame_ptrs || !d_pitches || !d_rois || !d_n_rois || !d_dst || !scale3 || !bias3 || cap < 0 || n_frames < 1 || src_h <= 0 || src_w <= 0 ||
+      out_h <= 0 || out_w <= 0 || !valid_dtype(dtype))
+    return OCTO_EINVAL;
+  ResizeArgs a{};
+  a.frames = (const uint8_t* const*)d_frame_ptrs; a.pitches = (const size_t*)d_pitches; a.src_h = src_h; a.src_w = src_w;
+  a.dst = d_dst; a.dst_h = out_h; a.dst_w = out_w; a.n = cap; a.n_dyn = d_n_rois; a.rois = d_rois;
+  a.n_frames = n_frames;
+  for (int c = 0; c < 3; ++c) { a.scale[c] = scale3[c]; a.bias[c] = bias3[c]; }
+  return from_hip(launch_crop_resize(dtype, a, (hipStream_t)hip_stream));
+}
+
+octo_status octo_op_decode(const octo_model_desc* model, const void* const* d_heads, int32_t n,
+                           octo_cand* d_cand, int32_t* d_count, int32_t cap, void* hip_stream) {
+  if (!model || !d_heads || !d_cand || !d_count || n < 0 || cap < 1 || !valid_dtype(model->dtype) || model->n_outputs < 1 ||
+      model->n_outputs > OCTO_MAX_LEVELS || model->n_anchors < 1 || model->n_anchors > OCTO_MAX_ANCHORS || model->n_classes < 1)
+    return OCTO_EINVAL;
+  DecodeArgs a{};
+  a.n_levels = model->n_outputs;
+  for (int l = 0; l < a.n_levels; ++l) {
+    if (!d_heads[l] || model->stride[l] <= 0 || model->in_h % model->stride[l] || model->in_w % model->stride[l]) return OCTO_EINVAL;
+    a.head[l] = d_heads[l];
+    a.head_ld[l] = model->n_anchors * (5 + model->n_classes);
+    a.gh[l] = model->in_h / model->stride[l]; a.gw[l] = model->in_w / model->stride[l]; a.stride[l] = model->stride[l];
+    memcpy(a.anchors[l], model->anchors[l], sizeof a.anchors[l]);
+  }
+  a.n_anchors = model->n_anchors; a.n_classes = model->n_classes; a.score_thr = model->score_thr;
+  a.n = n; a.cand = d_cand; a.count = d_count; a.cap = cap;
+  hipStream_t s = (hipStream_t)hip_stream;
+  hipError_t e = launch_fill_i32(d_count, 0, n, s);
+  if (e != hipSuccess) return from_hip(e);
+  return from_hip(launch_decode(model->dtype, a, s));
+}
+
+octo_status octo_op_topk(const octo_cand* d_in, const int32_t* d_in_count, int32_t in_cap, int32_t n, int32_t k,
+                         octo_cand* d_out, int32_t* d_out_count, int32_t k_cap, void* hip_stream) {
+  if (!d_in || !d_in_count || !d_out || !d_out_count || n < 0 || k < 1 || k > k_cap || in_cap < 1) return OCTO_EINVAL;
+  TopkArgs a{d_in, d_in_count, in_cap, d_out, d_out_count, k, k_cap, n, nullptr};
+  return from_hip(launch_topk(a, (hipStream_t)hip_stream));
+}
+
+size_t octo_op_nms_scratch_bytes(int32_t n, int32_t k_cap) { return n > 0 && k_cap > 0 ? nms_mask_bytes(n, k_cap) : 0; }
+
+octo_status octo_op_nms(const octo_cand* d_top, const int32_t* d_top_count, int32_t k_cap, int32_t n, float iou_thr, int32_t max_det,
+                        void* d_mask_scratch, int32_t* d_keep, int32_t* d_n_keep, void* hip_stream) {
+  if (!d_top || !d_top_count || !d_mask_scratch || !d_keep || !d_n_keep || n < 0 || max_det < 1 || k_cap < 64 || k_cap % 64 || k_cap > 4096 ||
+      !(iou_thr >= 0))
+    return OCTO_EINVAL;
+  NmsArgs a{d_top, d_top_count, k_cap, iou_thr, max_det, (unsigned long long*)d_mask_scratch, d_keep, d_n_keep, n, nullptr};
+  return from_hip(launch_nms(a, (hipStream_t)hip_stream));
+}
+
+octo_status octo_op_compact(const octo_cand* d_top, int32_t k_cap, const int32_t* d_keep, const int32_t* d_n_keep, int32_t max_det,
+                            int32_t n, int32_t src_h, int32_t src_w, int32_t in_h, int32_t in_w, const uint64_t* class_mask2,
+                            octo_roi* d_rois, int32_t* d_n_rois, int32_t cap, int32_t* d_roi_of, octo_box* d_boxes, int32_t* d_flags,
+                            void* hip_stream) {
+  if (!d_top || !d_keep || !d_n_keep || !class_mask2 || !d_rois || !d_n_rois || n < 0 || cap < 0 || max_det < 1 || k_cap < 1 ||
+      src_h <= 0 || src_w <= 0 || in_h <= 0 || in_w <= 0)
+    return OCTO_EINVAL;
+  int nw, nh, left, top;
+  letterbox_geometry(src_h, src_w, in_h, in_w, &nw, &nh, &left, &top);
+  CompactArgs a{};
+  a.top = d_top; a.k_cap = k_cap; a.keep = d_keep; a.n_keep = d_n_keep; a.max_det = max_det; a.n = n;
+  a.left = (float)left; a.top_pad = (float)top; a.rx = (float)nw / (float)src_w; a.ry = (float)nh / (float)src_h;
+  a.src_w = (float)src_w; a.src_h = (float)src_h;
+  a.n_edges = 1; a.class_mask[0][0] = class_mask2[0]; a.class_mask[0][1] = class_mask2[1];
+  a.rois[0] = d_rois; a.n_roi[0] = d_n_rois; a.roi_cap[0] = cap; a.roi_of[0] = d_roi_of;
+  a.boxes = d_boxes; a.flags = d_flags;
+  return from_hip(launch_compact(a, (hipStream_t)hip_stream));
+}
+
+}  // extern "C"

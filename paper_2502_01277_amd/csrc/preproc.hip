@@ -1,0 +1,191 @@
+// Frame pre-processing: letterbox-resize + normalise (uint8 HWC frame -> NHWC
+// tensor of the model's type) and ROI crop-resize (a variable number of source
+// boxes -> fixed-size crops).  Both are bilinear with half-pixel centres, taps
+// clamped to the frame, no antialias filter, one rounding to the output type.
+//
+// Each lane produces PX neighbouring output pixels of one row and writes them
+// with 8/16-byte stores; a wavefront therefore covers a contiguous output span
+// and a contiguous span of each tapped source row.
+#include "octo_internal.h"
+
+namespace octo {
+
+__device__ __forceinline__ int clampi(int v, int lo, int hi) { return v < lo ? lo : (v > hi ? hi : v); }
+
+template <typename T, int N> struct OutVec { alignas(sizeof(T) * 4) T v[N]; };
+
+template <typename T, int PX>
+__device__ __forceinline__ void store_pixels(T* dst, const float* v) {
+  // PX pixels x 3 channels, contiguous
+  if (PX == 4) {
+    alignas(16) T o[12];
+#pragma unroll
+    for (int i = 0; i < 12; ++i) o[i] = (T)v[i];
+    if (sizeof(T) == 2) {
+      uint2* d = (uint2*)dst; const uint2* s = (const uint2*)o;
+      d[0] = s[0]; d[1] = s[1]; d[2] = s[2];
+    } else {
+      float4* d = (float4*)dst; const float4* s = (const float4*)o;
+      d[0] = s[0]; d[1] = s[1]; d[2] = s[2];
+    }
+  } else {
+#pragma unroll
+    for (int i = 0; i < 3 * PX; ++i) dst[i] = (T)v[i];
+  }
+}
+
+__device__ __forceinline__ void bilinear_rgb(const uint8_t* row_a, const uint8_t* row_b, int xa, int xb, float fx, float fy,
+                                             const float* scale, const float* bias, float* out) {
+  const uint8_t* p00 = row_a + 3 * xa; const uint8_t* p01 = row_a + 3 * xb;
+  const uint8_t* p10 = row_b + 3 * xa; const uint8_t* p11 = row_b + 3 * xb;
+#pragma unroll
+  for (int c = 0; c < 3; ++c) {
+    float top = (1.0f - fx) * (float)p00[c] + fx * (float)p01[c];
+    float bot = (1.0f - fx) * (float)p10[c] + fx * (float)p11[c];
+    out[c] = ((1.0f - fy) * top + fy * bot) * scale[c] + bias[c];
+  }
+}
+
+struct LetterboxGeom { int nw, nh, left, top; };
+
+template <typename T, int PX>
+__global__ void letterbox_kernel(const ResizeArgs a, const LetterboxGeom g) {
+  const int wq = a.dst_w / PX;
+  int n_items = a.n;
+  if (a.n_dyn) { int d = *a.n_dyn; n_items = d < a.n ? d : a.n; }
+  const long long total = (long long)n_items * a.dst_h * wq;
+  T* dst = (T*)a.dst;
+  for (long long i = blockIdx.x * (long long)blockDim.x + threadIdx.x; i < total; i += (long long)gridDim.x * blockDim.x) {
+    const int xq = (int)(i % wq);
+    const long long t = i / wq;
+    const int y = (int)(t % a.dst_h);
+    const int img = (int)(t / a.dst_h);
+    float v[3 * PX];
+    const int yi = y - g.top;
+    const bool row_in = (unsigned)yi < (unsigned)g.nh;
+    const uint8_t* base = a.frames[img];
+    const size_t pitch = a.pitches[img];
+    int ya = 0, yb = 0; float fy = 0.f;
+    if (row_in) {
+      // source y = (yi + 0.5) * Hs / nh - 0.5 = ((2 yi + 1) Hs - nh) / (2 nh), split exactly into floor and fraction
+      const int num = (2 * yi + 1) * a.src_h - g.nh, den = 2 * g.nh;
+      int y0 = num >= 0 ? num / den : -((-num + den - 1) / den);
+      fy = (float)(num - y0 * den) / (float)den;
+      ya = clampi(y0, 0, a.src_h - 1); yb = clampi(y0 + 1, 0, a.src_h - 1);
+    }
+#pragma unroll
+    for (int px = 0; px < PX; ++px) {
+      const int xi = xq * PX + px - g.left;
+      if (row_in && (unsigned)xi < (unsigned)g.nw) {
+        const int num = (2 * xi + 1) * a.src_w - g.nw, den = 2 * g.nw;
+        int x0 = num >= 0 ? num / den : -((-num + den - 1) / den);
+        const float fx = (float)(num - x0 * den) / (float)den;
+        const int xa = clampi(x0, 0, a.src_w - 1), xb = clampi(x0 + 1, 0, a.src_w - 1);
+        bilinear_rgb(base + (size_t)ya * pitch, base + (size_t)yb * pitch, xa, xb, fx, fy, a.scale, a.bias, v + 3 * px);
+      } else {
+#pragma unroll
+        for (int c = 0; c < 3; ++c) v[3 * px + c] = (float)a.pad_value * a.scale[c] + a.bias[c];
+      }
+    }
+    store_pixels<T, PX>(dst + (((size_t)img * a.dst_h + y) * a.dst_w + (size_t)xq * PX) * 3, v);
+  }
+}
+
+template <typename T, int PX>
+__global__ void crop_resize_kernel(const ResizeArgs a) {
+  const int wq = a.dst_w / PX;
+  int n_items = a.n;
+  if (a.n_dyn) { int d = *a.n_dyn; n_items = d < a.n ? (d < 0 ? 0 : d) : a.n; }
+  const long long total = (long long)n_items * a.dst_h * wq;
+  T* dst = (T*)a.dst;
+  for (long long i = blockIdx.x * (long long)blockDim.x + threadIdx.x; i < total; i += (long long)gridDim.x * blockDim.x) {
+    const int xq = (int)(i % wq);
+    const long long t = i / wq;
+    const int y = (int)(t % a.dst_h);
+    const int roi = (int)(t / a.dst_h);
+    const octo_roi r = a.rois[roi];
+    const int fr = clampi(r.frame, 0, a.n_frames - 1);
+    const uint8_t* base = a.frames[fr];
+    const size_t pitch = a.pitches[fr];
+    const float sy = r.y1 + ((float)y + 0.5f) * ((r.y2 - r.y1) / (float)a.dst_h) - 0.5f;
+    const float y0f = floorf(sy);
+    const float fy = sy - y0f;
+    const int ya = clampi((int)y0f, 0, a.src_h - 1), yb = clampi((int)y0f + 1, 0, a.src_h - 1);
+    const float step = (r.x2 - r.x1) / (float)a.dst_w;
+    float v[3 * PX];
+#pragma unroll
+    for (int px = 0; px < PX; ++px) {
+      const float sx = r.x1 + ((float)(xq * PX + px) + 0.5f) * step - 0.5f;
+      const float x0f = floorf(sx);
+      const float fx = sx - x0f;
+      const int xa = clampi((int)x0f, 0, a.src_w - 1), xb = clampi((int)x0f + 1, 0, a.src_w - 1);
+      bilinear_rgb(base + (size_t)ya * pitch, base + (size_t)yb * pitch, xa, xb, fx, fy, a.scale, a.bias, v + 3 * px);
+    }
+    store_pixels<T, PX>(dst + (((size_t)roi * a.dst_h + y) * a.dst_w + (size_t)xq * PX) * 3, v);
+  }
+}
+
+static inline unsigned resize_grid(long long work) {
+  long long g = (work + 255) / 256;
+  if (g < 1) g = 1;
+  if (g > 256 * 32) g = 256 * 32;
+  return (unsigned)g;
+}
+
+static LetterboxGeom letterbox_geom(int src_h, int src_w, int dst_h, int dst_w) {
+  // scale r = min(dst_w/src_w, dst_h/src_h); resized size rounded half-up; centred with floor
+  double r = (double)dst_w / src_w;
+  if ((double)dst_h / src_h < r) r = (double)dst_h / src_h;
+  LetterboxGeom g;
+  g.nw = (int)(src_w * r + 0.5);
+  g.nh = (int)(src_h * r + 0.5);
+  if (g.nw < 1) g.nw = 1;
+  if (g.nh < 1) g.nh = 1;
+  g.left = (dst_w - g.nw) / 2;
+  g.top = (dst_h - g.nh) / 2;
+  return g;
+}
+
+void letterbox_geometry(int src_h, int src_w, int dst_h, int dst_w, int* nw, int* nh, int* left, int* top) {
+  LetterboxGeom g = letterbox_geom(src_h, src_w, dst_h, dst_w);
+  *nw = g.nw; *nh = g.nh; *left = g.left; *top = g.top;
+}
+
+template <typename T> static hipError_t letterbox_t(const ResizeArgs& a, hipStream_t s) {
+  LetterboxGeom g = letterbox_geom(a.src_h, a.src_w, a.dst_h, a.dst_w);
+  if (a.dst_w % 4 == 0 && ((uintptr_t)a.dst & 15) == 0) {
+    hipLaunchKernelGGL((letterbox_kernel<T, 4>), dim3(resize_grid((long long)a.n * a.dst_h * (a.dst_w / 4))), dim3(256), 0, s, a, g);
+  } else {
+    hipLaunchKernelGGL((letterbox_kernel<T, 1>), dim3(resize_grid((long long)a.n * a.dst_h * a.dst_w)), dim3(256), 0, s, a, g);
+  }
+  return hipGetLastError();
+}
+template <typename T> static hipError_t crop_t(const ResizeArgs& a, hipStream_t s) {
+  if (a.dst_w % 4 == 0 && ((uintptr_t)a.dst & 15) == 0) {
+    hipLaunchKernelGGL((crop_resize_kernel<T, 4>), dim3(resize_grid((long long)a.n * a.dst_h * (a.dst_w / 4))), dim3(256), 0, s, a);
+  } else {
+    hipLaunchKernelGGL((crop_resize_kernel<T, 1>), dim3(resize_grid((long long)a.n * a.dst_h * a.dst_w)), dim3(256), 0, s, a);
+  }
+  return hipGetLastError();
+}
+
+hipError_t launch_letterbox(int dtype, const ResizeArgs& a, hipStream_t s) {
+  if (a.n <= 0) return hipSuccess;
+  switch (dtype) {
+    case OCTO_F32: return letterbox_t<float>(a, s);
+    case OCTO_F16: return letterbox_t<_Float16>(a, s);
+    case OCTO_BF16: return letterbox_t<__bf16>(a, s);
+  }
+  return hipErrorInvalidValue;
+}
+hipError_t launch_crop_resize(int dtype, const ResizeArgs& a, hipStream_t s) {
+  if (a.n <= 0) return hipSuccess;
+  switch (dtype) {
+    case OCTO_F32: return crop_t<float>(a, s);
+    case OCTO_F16: return crop_t<_Float16>(a, s);
+    case OCTO_BF16: return crop_t<__bf16>(a, s);
+  }
+  return hipErrorInvalidValue;
+}
+
+}  // namespace octo

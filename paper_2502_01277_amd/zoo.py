@@ -79,13 +79,14 @@ class ModelSpec:
     norm_bias: tuple = (0.0, 0.0, 0.0)
     pad_value: int = 114
     batch_size: int = 1
+    in_c: int = 3
 
     def n_cand(self) -> int:
         return sum(self.n_anchors * (self.in_h // s) * (self.in_w // s) for s in self.strides)
 
     def tensor_shapes(self):
         """(h, w, c) of every tensor, by walking the graph (shape bookkeeping only)."""
-        shp = [(self.in_h, self.in_w, 3)]
+        shp = [(self.in_h, self.in_w, self.in_c)]
         for L in self.layers:
             h, w, c = shp[L.inputs[0]]
             if L.op == "conv":

@@ -1,0 +1,253 @@
+"""GPU parity of every stage against the oracle, through the C ABI (stage-level calls and detached models)."""
+import numpy as np
+import pytest
+
+from oracle import nn, postprocess as pp, preprocess as pre
+from oracle.cascade import postprocess_heads
+from paper_2502_01277_amd import synth, zoo
+from helpers import TOL, cands_to_records, records_to_cands, rel_err, small_root
+
+pytestmark = pytest.mark.gpu
+
+
+def _dev_frames(frames):
+    import torch
+    return [torch.from_numpy(f).cuda() for f in frames]
+
+
+def _host(t, dtype):
+    import torch
+    return t.float().cpu().numpy() if dtype != "f32" else t.cpu().numpy()
+
+
+# ---------------------------------------------------------------- letterbox / crop
+@pytest.mark.parametrize("dtype", ["f32", "f16", "bf16"])
+@pytest.mark.parametrize("sh,sw,dst", [(270, 480, 160), (45, 83, 64), (20, 30, 64), (64, 64, 64), (100, 37, 62), (360, 640, 320)])
+def test_letterbox_parity(octo, dtype, sh, sw, dst):
+    rng = np.random.default_rng(sh * sw)
+    frames = rng.integers(0, 256, (3, sh, sw, 3), dtype=np.uint8)
+    got = _host(octo.op_letterbox(_dev_frames(frames), dst, dst, dtype), dtype)
+    ref = pre.letterbox(frames, dst, dst, dtype)
+    ulp = {"f32": 2e-6, "f16": 1e-3, "bf16": 8e-3}[dtype]       # one unit in the last place at 1.0, plus fp32 interpolation error
+    assert np.abs(got - ref).max() <= ulp
+    if dtype == "f32":
+        assert (got != ref).mean() < 0.5
+
+
+def test_letterbox_strided_rows_and_normalisation(octo):
+    import torch
+    rng = np.random.default_rng(5)
+    big = torch.from_numpy(rng.integers(0, 256, (2, 50, 96, 3), dtype=np.uint8)).cuda()
+    views = [big[i, :, 8:72] for i in range(2)]                     # row pitch 288 bytes, 64 valid pixels
+    frames = np.stack([v.cpu().numpy() for v in views])
+    got = octo.op_letterbox(views, 96, 96, "f32", scale=(0.5, 1.0, 2.0), bias=(1.0, 0.0, -1.0), pad_value=10).cpu().numpy()
+    ref = pre.letterbox(frames, 96, 96, "f32", (0.5, 1.0, 2.0), (1.0, 0.0, -1.0), 10)
+    assert np.abs(got - ref).max() <= 2e-4
+
+
+@pytest.mark.parametrize("dtype", ["f32", "f16", "bf16"])
+def test_crop_resize_parity(octo, dtype):
+    rng = np.random.default_rng(6)
+    frames = rng.integers(0, 256, (3, 90, 120, 3), dtype=np.uint8)
+    n = 37
+    xy = rng.uniform(0, 1, (n, 2)) * [100, 70]
+    wh = rng.uniform(2, 60, (n, 2))
+    box = np.concatenate([xy, np.minimum(xy + wh, [120, 90])], axis=1).astype(np.float32)
+    box[0] = [0, 0, 120, 90]; box[1] = [7, 5, 7 + 16, 5 + 12]; box[2] = [120, 3, 120, 9]; box[3] = [4, 90, 9, 90]
+    fr = rng.integers(0, 3, n).astype(np.int32)
+    rois = np.zeros(n, octo.ROI_DTYPE)
+    rois["frame"], rois["x1"], rois["y1"], rois["x2"], rois["y2"] = fr, box[:, 0], box[:, 1], box[:, 2], box[:, 3]
+    for (oh, ow) in ((12, 16), (32, 20), (17, 19)):
+        got = _host(octo.op_crop_resize(_dev_frames(frames), rois, oh, ow, dtype, cap=n + 5), dtype)
+        ref = pre.crop_resize(frames, fr, box, oh, ow, dtype)
+        tol = {"f32": 2e-4, "f16": 1.5e-3, "bf16": 8e-3}[dtype]    # fp32 source coordinates on a noise image
+        assert np.abs(got[:n] - ref).max() <= tol
+        assert np.all(got[n:] == 0)                                  # nothing written past the ROI count
+    empty = octo.op_crop_resize(_dev_frames(frames), rois[:0], 8, 8, dtype, cap=4)
+    assert float(empty.float().abs().max()) == 0.0
+
+
+# ---------------------------------------------------------------- conv graph
+def _model(dtype, in_hw, in_c, build, batch):
+    rng = np.random.default_rng(7)
+    B = zoo._Builder("t", dtype, in_hw[0], in_hw[1], "classifier", rng)
+    B.ch = [in_c]
+    B.m.in_c = in_c
+    out = build(B)
+    B.m.outputs = [B.fc(B.gap(out), 10)]
+    B.m.batch_size = batch
+    return B.m
+
+
+def _run_detached(octo, m, x_f32):
+    root = small_root(m.dtype)
+    spec = zoo.PipelineSpec("t", [root, m], [], 200.0, 32, 32, 1, 1)
+    P = octo.Pipeline(spec, keep_all_tensors=True)
+    P.run_model_on(1, octo.to_device(x_f32, m.dtype))
+    n = x_f32.shape[0]
+    got = [P.get_tensor(1, t, n) for t in range(len(m.layers) + 1)]
+    P.close()
+    return got
+
+
+CONV_CASES = [
+    # (h, w, cin, cout, k, stride, pad, batch)
+    (20, 20, 64, 64, 3, 1, 1, 3), (17, 23, 32, 96, 3, 2, 1, 2), (9, 9, 128, 256, 1, 1, 0, 5),
+    (33, 31, 3, 32, 6, 2, 2, 2), (30, 30, 3, 64, 7, 2, 3, 2), (12, 12, 48, 40, 3, 1, 1, 3),
+    (8, 8, 16, 255, 1, 1, 0, 4), (40, 40, 8, 16, 3, 2, 1, 2), (7, 7, 512, 512, 3, 1, 1, 2),
+    (14, 14, 24, 520, 1, 1, 0, 1), (5, 5, 200, 72, 3, 1, 1, 2),
+]
+
+
+@pytest.mark.parametrize("dtype", ["f16", "bf16", "f32"])
+@pytest.mark.parametrize("case", CONV_CASES)
+def test_conv_parity(octo, dtype, case):
+    h, w, cin, cout, k, s, p, n = case
+    m = _model(dtype, (h, w), cin, lambda B: B.conv(0, cout, k, s, p, act=zoo.ACT_SILU), n)
+    x = zoo.round_to_dtype(np.random.default_rng(8).uniform(-1, 1, (n, h, w, cin)).astype(np.float32), dtype)
+    got = _run_detached(octo, m, x)
+    ref = nn.run_model(m, x, keep_all=True)
+    assert rel_err(got[1], ref[1]) <= TOL[dtype]
+    assert rel_err(got[-1], ref[-1]) <= TOL[dtype]
+
+
+@pytest.mark.parametrize("dtype", ["f16", "f32"])
+def test_residual_concat_pool_upsample_graph(octo, dtype):
+    def build(B):
+        a = B.conv(0, 32, 3, 1, act=zoo.ACT_RELU)
+        b = B.conv(a, 32, 3, 1, act=zoo.ACT_RELU, res=a, res_mode=zoo.RES_BEFORE_ACT)
+        c = B.conv(b, 32, 1, 1, act=zoo.ACT_SILU, res=a, res_mode=zoo.RES_AFTER_ACT)
+        d = B.maxpool(c, 3, 2, 1)
+        e = B.up(B.conv(d, 16, 1))
+        f = B.cat([e, c, b])                      # upsample + two convs written straight into the concat buffer
+        y1 = B.maxpool(f, 5, 1, 2)
+        g = B.cat([f, y1, 0])                     # the model input cannot be aliased: copy path
+        hh = B.add(B.conv(g, 24, 1), B.conv(g, 24, 3), act=zoo.ACT_RELU)
+        return B.conv(hh, 40, 3, 2)
+    m = _model(dtype, (18, 22), 8, build, 3)
+    x = zoo.round_to_dtype(np.random.default_rng(9).uniform(-1, 1, (3, 18, 22, 8)).astype(np.float32), dtype)
+    got = _run_detached(octo, m, x)
+    ref = nn.run_model(m, x, keep_all=True)
+    for t in range(1, len(ref)):
+        assert rel_err(got[t], ref[t]) <= TOL[dtype], (t, m.layers[t - 1].op)
+
+
+def test_memory_reuse_keeps_outputs_intact(octo):
+    # same graph with and without per-tensor buffers must give the same logits
+    m = zoo.residual_classifier("r", "f16", 64, 64, "basic", (1, 1, 1, 1), 10, seed=3, batch_size=4)
+    x = zoo.round_to_dtype(np.random.default_rng(10).uniform(0, 1, (4, 64, 64, 3)).astype(np.float32), "f16")
+    outs = []
+    for keep in (True, False):
+        spec = zoo.PipelineSpec("t", [small_root("f16"), m], [], 200.0, 32, 32, 1, 1)
+        P = octo.Pipeline(spec, keep_all_tensors=keep)
+        P.run_model_on(1, octo.to_device(x, "f16"))
+        outs.append(P.get_tensor(1, m.outputs[0], 4))
+        P.close()
+    assert np.array_equal(outs[0], outs[1])
+    assert rel_err(outs[0], nn.run_model(m, x)[m.outputs[0]]) <= TOL["f16"]
+
+
+# ---------------------------------------------------------------- post-processing
+def _planted(dtype, n=3, seed=11, dups=4, clutter=0, det=None, hw=(270, 480)):
+    rng = np.random.default_rng(seed)
+    det = det or zoo.csp_detector("d", dtype, 320, zoo.S_WIDTHS, zoo.S_DEPTHS, 80, seed=3, topk=300, max_det=50)
+    counts = synth.counts_poisson(rng, n, 8, 64)
+    scene = synth.make_scene(rng, n, hw[0], hw[1], counts, 12, 120, log_uniform=True)
+    heads = synth.planted_heads(rng, det, scene, hw[0], hw[1], max_dups=dups, n_clutter=clutter)
+    return det, scene, heads
+
+
+@pytest.mark.parametrize("dtype", ["f32", "f16", "bf16"])
+def test_decode_parity(octo, dtype):
+    det, scene, heads = _planted(dtype, clutter=40)
+    cand, count = octo.op_decode(det, [octo.to_device(h, dtype) for h in heads])
+    got = octo.cands_from_device(cand, count)
+    for f in range(heads[0].shape[0]):
+        ref = pp.decode_frame([h[f] for h in heads], det)
+        g = got[f][np.argsort(got[f]["idx"])]
+        assert np.array_equal(g["idx"], ref.idx) and np.array_equal(g["cls"], ref.cls)      # same survivors, same classes
+        gb = np.stack([g["x1"], g["y1"], g["x2"], g["y2"]], axis=1)
+        assert np.abs(gb - ref.box).max() <= 1e-3 and np.abs(g["score"] - ref.score).max() <= 1e-6
+
+
+def test_decode_natural_head_statistics(octo):
+    # random logits: many candidates straddle the threshold; survivors may differ only where the score is within rounding of it
+    det = zoo.plain_detector("d", "f32", 64, (8, 8, 8), 4, seed=1)
+    h = np.random.default_rng(12).standard_normal((2, 8, 8, 27)).astype(np.float32) * 2
+    cand, count = octo.op_decode(det, [octo.to_device(h, "f32")])
+    got = octo.cands_from_device(cand, count)
+    for f in range(2):
+        ref = pp.decode_frame([h[f]], det)
+        diff = set(got[f]["idx"].tolist()) ^ set(ref.idx.tolist())
+        assert len(ref) > 20 and len(diff) <= 1
+
+
+@pytest.mark.parametrize("k", [5, 100, 300])
+def test_topk_nms_compact_bit_exact_from_oracle_candidates(octo, k):
+    det, scene, heads = _planted("f16", n=4, clutter=150)
+    det.topk, det.max_det = k, 40
+    ref_dets = postprocess_heads(heads, det)
+    lists = [cands_to_records(pp.decode_frame([h[f] for h in heads], det)) for f in range(4)]
+    rng = np.random.default_rng(13)
+    lists = [l[rng.permutation(len(l))] for l in lists]                      # list order must not matter
+    cand, count = octo.cands_to_device(lists, max(len(l) for l in lists) + 3)
+    top, tc = octo.op_topk(cand, count, k)
+    got_top = octo.cands_from_device(top, tc)
+    keep, nk = octo.op_nms(top, tc, det.iou_thr, det.max_det)
+    keep, nk = keep.cpu().numpy(), nk.cpu().numpy()
+    kept = []
+    for f, d in enumerate(ref_dets):
+        assert got_top[f].tobytes() == cands_to_records(d.top).tobytes()
+        assert keep[f, :nk[f]].tolist() == d.keep.tolist()
+        kept.append((d.top.cls[d.keep], pp.to_source_box(d.top.box[d.keep], 270, 480, 320, 180, 0, 70)))
+    for mask in ((1 << 128) - 1, sum(1 << c for c in range(0, 80, 3)), 0):
+        rois, roi_of, boxes, flags = octo.op_compact(top, octo._torch().from_numpy(keep).cuda(), octo._torch().from_numpy(nk).cuda(),
+                                                     (270, 480), (320, 320), mask, cap=4 * 40)
+        ref = pp.compact_rois(kept, mask)
+        assert rois["frame"].tolist() == ref.frame.tolist() and rois["rank"].tolist() == ref.rank.tolist()
+        assert rois["cls"].tolist() == ref.cls.tolist()
+        gb = np.stack([rois["x1"], rois["y1"], rois["x2"], rois["y2"]], axis=1).reshape(-1, 4)
+        assert np.array_equal(gb, ref.box)
+        for j in range(len(rois)):
+            assert roi_of[rois["frame"][j], rois["rank"][j]] == j
+        assert (roi_of >= 0).sum() == len(rois) and not flags.any()
+    # capacity overflow clamps and flags
+    rois, roi_of, boxes, flags = octo.op_compact(top, octo._torch().from_numpy(keep).cuda(), octo._torch().from_numpy(nk).cuda(),
+                                                 (270, 480), (320, 320), (1 << 128) - 1, cap=3)
+    assert len(rois) == 3 and flags.any()
+
+
+def test_topk_long_lists_and_ties(octo):
+    # more candidates than one LDS pass holds, with many equal scores
+    rng = np.random.default_rng(14)
+    n = 9000
+    lists = []
+    for f in range(2):
+        r = np.zeros(n, octo.CAND_DTYPE)
+        r["score"] = (np.round(rng.uniform(0.3, 1.0, n) * 50) / 50).astype(np.float32)
+        r["idx"] = rng.permutation(3 * n)[:n]
+        r["x1"] = rng.uniform(0, 100, n); r["x2"] = r["x1"] + 5; r["y2"] = 5
+        lists.append(r)
+    lists.append(lists[0][:0])                                                   # an empty item
+    cand, count = octo.cands_to_device(lists, n)
+    top, tc = octo.op_topk(cand, count, 1000)
+    got = octo.cands_from_device(top, tc)
+    for f in range(3):
+        ref = pp.topk(records_to_cands(lists[f]), 1000)
+        assert got[f]["idx"].tolist() == ref.idx.tolist()
+
+
+def test_nms_dense_overlaps_and_max_det(octo):
+    rng = np.random.default_rng(15)
+    lists = []
+    for f, n in enumerate((700, 64, 1, 0, 130)):
+        xy = rng.uniform(0, 60, (n, 2)); wh = rng.uniform(5, 40, (n, 2))
+        c = pp.Candidates(np.concatenate([xy, xy + wh], 1).astype(np.float32), rng.uniform(0.3, 1, n).astype(np.float32),
+                          rng.integers(0, 3, n).astype(np.int32), rng.permutation(n).astype(np.int32))
+        lists.append(pp.topk(c, 1000))
+    cand, count = octo.cands_to_device([cands_to_records(c) for c in lists], 704)
+    for max_det in (1000, 7):
+        keep, nk = octo.op_nms(cand, count, 0.45, max_det)
+        keep, nk = keep.cpu().numpy(), nk.cpu().numpy()
+        for f, c in enumerate(lists):
+            assert keep[f, :nk[f]].tolist() == pp.nms(c, 0.45, max_det).tolist()
