@@ -28,7 +28,7 @@ def _check_postprocessing_from_gpu_candidates(P, spec, model, n_items, heads_gpu
         assert keep.tolist() == pp.nms(c, det.iou_thr, det.max_det).tolist()
         if cc == len(ref):
             rt = pp.topk(ref, det.topk)
-            if np.array_equal(rt.idx, c.idx):
+            if len(c) and np.array_equal(rt.idx, c.idx):
                 assert np.abs(rt.box - c.box).max() < 1e-3 and np.abs(rt.score - c.score).max() < 1e-5
 
 
@@ -140,8 +140,13 @@ def test_queueing_batching_and_empty_frames(octo):
     P.submit(dev, frame_ids=list(range(5)))
     launched = [P.run(), P.run(), P.run(), P.run()]
     assert launched == [2, 2, 1, 0]
-    frames, boxes, st = P.collect()
-    assert st == octo.OK and len(frames) == 5 and frames["frame_id"].tolist() == [0, 1, 2, 3, 4]
+    got_f, got_b = [], []
+    while sum(len(f) for f in got_f) < 5:                    # a blocking collect returns at least the oldest batch
+        f, b, st = P.collect()
+        assert st == octo.OK and 1 <= len(f) <= 5
+        got_f.append(f); got_b.append(b)
+    frames, boxes = np.concatenate(got_f), np.concatenate(got_b)
+    assert frames["frame_id"].tolist() == [0, 1, 2, 3, 4]
     assert frames["n_boxes"].sum() == 0 and len(boxes) == 0 and len(P.get_rois(0)) == 0
     _, _, st = P.collect(blocking=False)
     assert st == octo.ENOTREADY
