@@ -84,7 +84,7 @@ EXPORTS = [
     "octo_pipeline_workspace_size", "octo_pipeline_create", "octo_pipeline_destroy", "octo_submit_frames", "octo_run",
     "octo_collect", "octo_set_batch_size", "octo_last_error", "octo_now_ms", "octo_stream_create_masked",
     "octo_stream_destroy", "octo_device_cu_count", "octo_cwd_search", "octo_coral_schedule", "octo_est_latency_ms",
-    "octo_est_throughput", "octo_run_model", "octo_profile_layers", "octo_set_stage_timing", "octo_get_stage_ms",
+    "octo_est_throughput", "octo_run_model", "octo_profile_layers", "octo_set_layer_timing", "octo_get_layer_info", "octo_set_stage_timing", "octo_get_stage_ms",
     "octo_debug_get_tensor", "octo_debug_tensor_shape", "octo_debug_set_head", "octo_debug_run_model",
     "octo_debug_get_detections", "octo_debug_get_rois", "octo_debug_get_labels", "octo_op_letterbox",
     "octo_op_crop_resize", "octo_op_decode", "octo_op_topk", "octo_op_nms", "octo_op_nms_scratch_bytes", "octo_op_compact",
@@ -124,6 +124,8 @@ def lib() -> C.CDLL:
         L.octo_est_throughput.argtypes = [vp]
         L.octo_profile_layers.argtypes = [vp, i32, i32, i32, vp, vp, vp, vp, i32]
         L.octo_set_stage_timing.argtypes = [vp, i32]
+        L.octo_set_layer_timing.argtypes = [vp, i32]
+        L.octo_get_layer_info.argtypes = [vp, i32, vp, vp, vp, vp, i32, vp]
         L.octo_get_stage_ms.argtypes = [vp, vp, i32, vp]
         L.octo_debug_get_tensor.argtypes = [vp, i32, i32, i32, vp, C.c_size_t]
         L.octo_debug_tensor_shape.argtypes = [vp, i32, i32, vp, vp, vp]
@@ -357,6 +359,17 @@ class Pipeline:
         self._check(self.L.octo_profile_layers(self.h, model, n, iters, _stream_ptr(stream), ms.ctypes.data,
                                                fl.ctypes.data, by.ctypes.data, nl))
         return ms, fl, by
+
+    def set_layer_timing(self, on: bool):
+        self._check(self.L.octo_set_layer_timing(self.h, 1 if on else 0))
+
+    def layer_info(self, model: int):
+        """(ms, kernel_id, flops per item, bytes per item) per layer for the most recently collected batch."""
+        nl = len(self.spec.models[model].layers)
+        ms = np.zeros(nl, np.float32); kid = np.zeros(nl, np.int32); fl = np.zeros(nl, np.float64); by = np.zeros(nl, np.float64)
+        n = C.c_int32()
+        self._check(self.L.octo_get_layer_info(self.h, model, ms.ctypes.data, kid.ctypes.data, fl.ctypes.data, by.ctypes.data, nl, C.byref(n)))
+        return ms, kid, fl, by
 
     def set_stage_timing(self, on: bool):
         self._check(self.L.octo_set_stage_timing(self.h, 1 if on else 0))

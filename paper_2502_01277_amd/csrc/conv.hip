@@ -18,62 +18,75 @@ typedef _Float16 half8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 typedef float floatx4 __attribute__((ext_vector_type(4)));
-
-struct alignas(16) Vec16 { uint32_t v[4]; };
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));   // one 16-byte operand vector
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
 template <typename T> struct Elem;
 template <> struct Elem<_Float16> {
   static constexpr int N = 8;   // elements per 16-byte vector
-  static __device__ __forceinline__ void mfma(const Vec16& a, const Vec16& b, floatx16& c) {
-    c = __builtin_amdgcn_mfma_f32_32x32x16_f16(*(const half8*)&a, *(const half8*)&b, c, 0, 0, 0);
+  static __device__ __forceinline__ floatx16 mfma(u32x4 a, u32x4 b, floatx16 c) {
+    return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(half8, a), __builtin_bit_cast(half8, b), c, 0, 0, 0);
   }
-  static __device__ __forceinline__ float to_f32(_Float16 v) { return (float)v; }
-  static __device__ __forceinline__ _Float16 from_f32(float v) { return (_Float16)v; }
 };
 template <> struct Elem<__bf16> {
   static constexpr int N = 8;
-  static __device__ __forceinline__ void mfma(const Vec16& a, const Vec16& b, floatx16& c) {
-    c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*(const bf16x8*)&a, *(const bf16x8*)&b, c, 0, 0, 0);
+  static __device__ __forceinline__ floatx16 mfma(u32x4 a, u32x4 b, floatx16 c) {
+    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
   }
-  static __device__ __forceinline__ float to_f32(__bf16 v) { return (float)v; }
-  static __device__ __forceinline__ __bf16 from_f32(float v) { return (__bf16)v; }
 };
 template <> struct Elem<float> {
   static constexpr int N = 4;
-  static __device__ __forceinline__ void mfma(const Vec16& a, const Vec16& b, floatx16& c) {
-    const float* fa = (const float*)&a;
-    const float* fb = (const float*)&b;
+  static __device__ __forceinline__ floatx16 mfma(u32x4 a, u32x4 b, floatx16 c) {
+    const floatx4 fa = __builtin_bit_cast(floatx4, a), fb = __builtin_bit_cast(floatx4, b);
 #pragma unroll
     for (int j = 0; j < 4; ++j) c = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[j], fb[j], c, 0, 0, 0);
+    return c;
   }
-  static __device__ __forceinline__ float to_f32(float v) { return v; }
-  static __device__ __forceinline__ float from_f32(float v) { return v; }
 };
 
-__device__ __forceinline__ float apply_act(float v, int act) {
-  if (act == OCTO_ACT_RELU) return fmaxf(v, 0.0f);
-  if (act == OCTO_ACT_SILU) return v / (1.0f + __expf(-v));
-  return v;
+// four consecutive output values: residual, activation, conversion and one 8/16-byte store
+template <typename T>
+__device__ __forceinline__ floatx4 load4(const T* p) {
+  if constexpr (sizeof(T) == 4) {
+    return *(const floatx4*)p;
+  } else {
+    typedef T t4 __attribute__((ext_vector_type(4)));
+    const t4 v = __builtin_bit_cast(t4, *(const u32x2*)p);
+    return floatx4{(float)v[0], (float)v[1], (float)v[2], (float)v[3]};
+  }
 }
+template <typename T>
+__device__ __forceinline__ void store4(T* p, floatx4 v) {
+  if constexpr (sizeof(T) == 4) {
+    *(floatx4*)p = v;
+  } else {
+    typedef T t4 __attribute__((ext_vector_type(4)));
+    const t4 o = {(T)v[0], (T)v[1], (T)v[2], (T)v[3]};
+    *(u32x2*)p = __builtin_bit_cast(u32x2, o);
+  }
+}
+__device__ __forceinline__ float silu(float v) { return v / (1.0f + __expf(-v)); }
 
-constexpr int KVEC = 4;                 // 16-byte vectors per tile row along K (one K step = 64 bytes per row)
-constexpr int ROWV = KVEC + 1;          // LDS row pitch in vectors (80 bytes: conflict-free 16-byte reads)
 constexpr int THREADS = 256;
 
-// BC: output channels per tile, BP: pixels per tile, WC x WP: wavefront grid (WC * WP == 4).
-template <typename T, int BC, int BP, int WC, int WP, bool VEC>
+// BC: output channels per tile, BP: pixels per tile, WC x WP: wavefront grid (WC * WP == 4),
+// KV: 16-byte vectors per tile row and K step (one K step = KV*16 bytes of K per row).
+template <typename T, int BC, int BP, int WC, int WP, int KV, bool VEC>
 __global__ __launch_bounds__(THREADS) void conv_mfma_kernel(const ConvArgs a) {
   using E = Elem<T>;
   constexpr int VN = E::N;
-  constexpr int BK = KVEC * VN;          // elements per K step
+  constexpr int BK = KV * VN;            // elements per K step
+  constexpr int ROWV = KV + 1;           // LDS row pitch in vectors: (16*KV + 16) bytes keeps 16-byte reads conflict-free
+  constexpr int RP = THREADS / KV;       // tile rows covered by one pass of the 256 loader lanes
   constexpr int TC = BC / WC / 32;       // 32x32 blocks per wavefront along channels
   constexpr int TP = BP / WP / 32;
-  constexpr int LA = (BC * KVEC + THREADS - 1) / THREADS;  // vectors per thread per K step (weights)
-  constexpr int LB = BP * KVEC / THREADS;                  // (pixels)
-  static_assert(WC * WP == 4 && TC >= 1 && TP >= 1 && LB >= 1 && BP % 64 == 0 && BC % 32 == 0, "tile shape");
+  constexpr int LA = (BC + RP - 1) / RP; // vectors per lane per K step (weights)
+  constexpr int LB = BP / RP;            // (pixels)
+  static_assert(WC * WP == 4 && TC >= 1 && TP >= 1 && LB >= 1 && BP % RP == 0 && BC % 32 == 0, "tile shape");
 
-  __shared__ Vec16 sA[2][BC][ROWV];
-  __shared__ Vec16 sB[2][BP][ROWV];
+  __shared__ u32x4 sA[2][BC][ROWV];
+  __shared__ u32x4 sB[2][BP][ROWV];
+  __shared__ float sBias[BC];
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -88,11 +101,17 @@ __global__ __launch_bounds__(THREADS) void conv_mfma_kernel(const ConvArgs a) {
   const long long tiles_p = (M + BP - 1) / BP;
   const long long n_tiles = tiles_p * tiles_c;
   const int nk = a.Kp / BK;
-  const T* __restrict__ xg = (const T*)a.x;
+  const T* __restrict__ xg = (const T*)a.x + a.x_coff;
   const T* __restrict__ wg = (const T*)a.w;
+  const int HoWo = a.Ho * a.Wo;
 
-  const int ld_row = tid >> 2;           // 0..63
-  const int ld_kv = tid & 3;
+  const int ld_row = tid / KV;
+  const int ld_kv = tid % KV;
+  const bool vec_ok = ((a.y_ld | a.y_coff) & 3) == 0 && (!a.res || ((a.res_ld | a.res_coff) & 3) == 0);
+  const bool is_silu = a.act == OCTO_ACT_SILU;
+  const float act_lo = a.act == OCTO_ACT_RELU ? 0.0f : -INFINITY;
+  const float res_pre = a.res_mode == OCTO_RES_BEFORE_ACT ? 1.0f : 0.0f;
+  const float res_post = a.res_mode == OCTO_RES_AFTER_ACT ? 1.0f : 0.0f;
 
   for (long long tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
     const int tc = (int)(tile % tiles_c);
@@ -100,27 +119,26 @@ __global__ __launch_bounds__(THREADS) void conv_mfma_kernel(const ConvArgs a) {
     const int c0 = tc * BC;
     const long long p0 = tp * BP;
 
-    // per-thread pixel rows for the gather
+    // per-lane pixel rows of the gather: pointer to the (possibly out-of-image) pixel of tap (0, 0)
     int hi0[LB], wi0[LB];
-    long long pixbase[LB];
+    const T* rowp[LB];
 #pragma unroll
     for (int i = 0; i < LB; ++i) {
-      long long m = p0 + ld_row + 64 * i;
+      const long long m = p0 + ld_row + RP * i;
       if (m < M) {
-        int img = (int)(m / (a.Ho * a.Wo));
-        int rem = (int)(m - (long long)img * (a.Ho * a.Wo));
-        int ho = rem / a.Wo, wo = rem - ho * a.Wo;
+        const int img = (int)(m / HoWo);
+        const int rem = (int)(m - (long long)img * HoWo);
+        const int ho = rem / a.Wo, wo = rem - ho * a.Wo;
         hi0[i] = ho * a.stride - a.pad;
         wi0[i] = wo * a.stride - a.pad;
-        pixbase[i] = (long long)img * a.H * a.W;
+        rowp[i] = xg + (((long long)img * a.H + hi0[i]) * a.W + wi0[i]) * a.x_ld;
       } else {
-        hi0[i] = -1000000; wi0[i] = 0; pixbase[i] = 0;
+        hi0[i] = -1000000; wi0[i] = 0; rowp[i] = xg;
       }
     }
-    // this thread's position along K: element k = kb*BK + ld_kv*VN -> (tap r, s; channel c)
-    int kc = ld_kv * VN, kr = 0, ks = 0;
-    if (VEC) { while (kc >= a.Cin) { kc -= a.Cin; if (++ks == a.kw) { ks = 0; ++kr; } } }
-
+    const T* wrow[LA];
+#pragma unroll
+    for (int i = 0; i < LA; ++i) wrow[i] = wg + (size_t)(c0 + ld_row + RP * i) * a.Kp + ld_kv * VN;
     floatx16 acc[TC][TP];
 #pragma unroll
     for (int i = 0; i < TC; ++i)
@@ -129,68 +147,69 @@ __global__ __launch_bounds__(THREADS) void conv_mfma_kernel(const ConvArgs a) {
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
 
-    Vec16 ra[LA], rb[LB];
-    auto load_tiles = [&](int kb) {
-#pragma unroll
-      for (int i = 0; i < LA; ++i) {
-        if (BC % 64 == 0 || ld_row + 64 * i < BC) {
-          const T* src = wg + (size_t)(c0 + ld_row + 64 * i) * a.Kp + (size_t)kb * BK + ld_kv * VN;
-          ra[i] = *(const Vec16*)src;
-        }
-      }
-      if (VEC) {
-#pragma unroll
-        for (int i = 0; i < LB; ++i) {
-          int hi = hi0[i] + kr, wi = wi0[i] + ks;
-          Vec16 v = {{0u, 0u, 0u, 0u}};
-          if (kr < a.kh && (unsigned)hi < (unsigned)a.H && (unsigned)wi < (unsigned)a.W) {
-            const T* src = xg + ((size_t)(pixbase[i] + (long long)hi * a.W + wi)) * a.x_ld + a.x_coff + kc;
-            v = *(const Vec16*)src;
-          }
-          rb[i] = v;
-        }
-        kc += BK;
-        while (kc >= a.Cin) { kc -= a.Cin; if (++ks == a.kw) { ks = 0; ++kr; } }
-      } else {
-        const int kbase = kb * BK + ld_kv * VN;
-#pragma unroll
-        for (int i = 0; i < LB; ++i) {
-          alignas(16) T tmp[VN];
-#pragma unroll
-          for (int e = 0; e < VN; ++e) {
-            int k = kbase + e;
-            float val = 0.0f;
-            if (k < a.K) {
-              int tap = k / a.Cin, c = k - tap * a.Cin;
-              int r = tap / a.kw, s = tap - r * a.kw;
-              int hi = hi0[i] + r, wi = wi0[i] + s;
-              if ((unsigned)hi < (unsigned)a.H && (unsigned)wi < (unsigned)a.W)
-                val = E::to_f32(xg[((size_t)(pixbase[i] + (long long)hi * a.W + wi)) * a.x_ld + a.x_coff + c]);
-            }
-            tmp[e] = E::from_f32(val);
-          }
-          rb[i] = *(const Vec16*)tmp;
-        }
-      }
-    };
-    auto store_tiles = [&](int buf) {
-#pragma unroll
-      for (int i = 0; i < LA; ++i)
-        if (BC % 64 == 0 || ld_row + 64 * i < BC) sA[buf][ld_row + 64 * i][ld_kv] = ra[i];
-#pragma unroll
-      for (int i = 0; i < LB; ++i) sB[buf][ld_row + 64 * i][ld_kv] = rb[i];
-    };
+    u32x4 ra[LA], rb[LB];
+    bool rb_ok[LB];
 
-    __syncthreads();   // previous tile's LDS reads are done
-    load_tiles(0);
-    store_tiles(0);
-    __syncthreads();
+    // Operands of K step KB: global -> registers.  The loads are unconditional (an out-of-image tap reads a safe
+    // address and is zeroed when it is written to LDS) so that they stay in flight during the MFMA work.
+    // Element k = KB*BK + ld_kv*VN of the reduction is channel c of tap (r, s): k = (r*kw + s)*Cin + c; the two
+    // divisions use precomputed reciprocals (exact for k < 65536).
+#define OCTO_CONV_LOAD(KB)                                                                                          \
+    {                                                                                                               \
+      _Pragma("unroll") for (int i = 0; i < LA; ++i)                                                                \
+        if (BC % RP == 0 || ld_row + RP * i < BC) ra[i] = *(const u32x4*)(wrow[i] + (size_t)(KB) * BK);             \
+      if (VEC) {                                                                                                    \
+        const unsigned k = (unsigned)(KB) * BK + ld_kv * VN;                                                        \
+        const unsigned tap = __umulhi(k, a.magic_cin);                                                              \
+        const int c = (int)(k - tap * a.Cin);                                                                       \
+        const int r = a.kw == 1 ? (int)tap : (int)__umulhi(tap, a.magic_kw);                                        \
+        const int s2 = (int)tap - r * a.kw;                                                                         \
+        const int delta = (r * a.W + s2) * a.x_ld + c;                                                              \
+        const bool tap_ok = k < (unsigned)a.K;                                                                      \
+        _Pragma("unroll") for (int i = 0; i < LB; ++i) {                                                            \
+          const bool ok = tap_ok & ((unsigned)(hi0[i] + r) < (unsigned)a.H) & ((unsigned)(wi0[i] + s2) < (unsigned)a.W); \
+          const T* src = ok ? rowp[i] + delta : xg;                                                                 \
+          rb[i] = *(const u32x4*)src;                                                                               \
+          rb_ok[i] = ok;                                                                                            \
+        }                                                                                                           \
+      } else {                                                                                                      \
+        const int kbase = (KB) * BK + ld_kv * VN;                                                                   \
+        _Pragma("unroll") for (int i = 0; i < LB; ++i) {                                                            \
+          typedef T tv __attribute__((ext_vector_type(VN)));                                                        \
+          tv pk;                                                                                                    \
+          _Pragma("unroll") for (int e = 0; e < VN; ++e) {                                                          \
+            const int k = kbase + e;                                                                                \
+            T val = (T)0.0f;                                                                                        \
+            if (k < a.K) {                                                                                          \
+              const int tap = k / a.Cin, c = k - tap * a.Cin;                                                       \
+              const int r = tap / a.kw, s2 = tap - r * a.kw;                                                        \
+              if ((unsigned)(hi0[i] + r) < (unsigned)a.H && (unsigned)(wi0[i] + s2) < (unsigned)a.W)                \
+                val = rowp[i][(r * a.W + s2) * a.x_ld + c];                                                         \
+            }                                                                                                       \
+            pk[e] = val;                                                                                            \
+          }                                                                                                         \
+          rb[i] = __builtin_bit_cast(u32x4, pk);                                                                    \
+          rb_ok[i] = true;                                                                                          \
+        }                                                                                                           \
+      }                                                                                                             \
+    }
+
+    __syncthreads();   // the previous tile's LDS reads are done
+    if (tid < BC) sBias[tid] = a.bias[c0 + tid];     // bias is padded to a multiple of 128 channels
+    OCTO_CONV_LOAD(0)
     for (int kb = 0; kb < nk; ++kb) {
       const int buf = kb & 1;
-      if (kb + 1 < nk) load_tiles(kb + 1);
+      // operands of step kb: registers -> LDS
 #pragma unroll
-      for (int kk = 0; kk < KVEC / 2; ++kk) {
-        Vec16 fa[TC], fb[TP];
+      for (int i = 0; i < LA; ++i)
+        if (BC % RP == 0 || ld_row + RP * i < BC) sA[buf][ld_row + RP * i][ld_kv] = ra[i];
+#pragma unroll
+      for (int i = 0; i < LB; ++i) sB[buf][ld_row + RP * i][ld_kv] = rb_ok[i] ? rb[i] : u32x4{0u, 0u, 0u, 0u};
+      __syncthreads();
+      if (kb + 1 < nk) OCTO_CONV_LOAD(kb + 1)
+#pragma unroll
+      for (int kk = 0; kk < KV / 2; ++kk) {
+        u32x4 fa[TC], fb[TP];
 #pragma unroll
         for (int i = 0; i < TC; ++i) fa[i] = sA[buf][wc * (BC / WC) + i * 32 + l32][kk * 2 + g];
 #pragma unroll
@@ -198,56 +217,62 @@ __global__ __launch_bounds__(THREADS) void conv_mfma_kernel(const ConvArgs a) {
 #pragma unroll
         for (int i = 0; i < TC; ++i)
 #pragma unroll
-          for (int j = 0; j < TP; ++j) E::mfma(fa[i], fb[j], acc[i][j]);
+          for (int j = 0; j < TP; ++j) acc[i][j] = E::mfma(fa[i], fb[j], acc[i][j]);
       }
-      if (kb + 1 < nk) store_tiles(buf ^ 1);
-      __syncthreads();
     }
+#undef OCTO_CONV_LOAD
 
-    // epilogue: lane holds pixel column l32 of each 32x32 block and 4 groups of 4 consecutive channels
-    const bool vec_ok = ((a.y_ld | a.y_coff) & 3) == 0 && (!a.res || ((a.res_ld | a.res_coff) & 3) == 0);
+    // epilogue: a lane holds pixel column l32 of each 32x32 block and 4 groups of 4 consecutive channels
 #pragma unroll
     for (int j = 0; j < TP; ++j) {
       const long long p = p0 + wp * (BP / WP) + j * 32 + l32;
       if (p >= M) continue;
 #pragma unroll
       for (int i = 0; i < TC; ++i) {
+        const int cblk = wc * (BC / WC) + i * 32 + g * 4;     // channel (inside the tile) of this lane's group q = 0
+        if (vec_ok && c0 + cblk + 28 <= a.Cout) {
+          // fast path: all four 4-channel groups are inside the tensor and 8/16-byte accesses are aligned
+          floatx4 rv[4];
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
-          const int cb = c0 + wc * (BC / WC) + i * 32 + q * 8 + g * 4;
-          if (cb >= a.Cout) continue;
-          float v[4];
-#pragma unroll
-          for (int e = 0; e < 4; ++e) v[e] = acc[i][j][q * 4 + e];
-          const int nvalid = a.Cout - cb < 4 ? a.Cout - cb : 4;
-#pragma unroll
-          for (int e = 0; e < 4; ++e) if (e < nvalid) v[e] += a.bias[cb + e];
-          float rv[4] = {0.f, 0.f, 0.f, 0.f};
+          for (int q = 0; q < 4; ++q) rv[q] = floatx4{0.f, 0.f, 0.f, 0.f};
           if (a.res) {
-            const T* rp = (const T*)a.res + (size_t)p * a.res_ld + a.res_coff + cb;
+            const T* rp = (const T*)a.res + (size_t)p * a.res_ld + a.res_coff + c0 + cblk;
 #pragma unroll
-            for (int e = 0; e < 4; ++e) if (e < nvalid) rv[e] = E::to_f32(rp[e]);
+            for (int q = 0; q < 4; ++q) rv[q] = load4<T>(rp + q * 8);
           }
+          const size_t o = (size_t)p * a.y_ld + a.y_coff + c0 + cblk;
 #pragma unroll
-          for (int e = 0; e < 4; ++e) {
-            if (a.res_mode == OCTO_RES_BEFORE_ACT) v[e] = apply_act(v[e] + rv[e], a.act);
-            else if (a.res_mode == OCTO_RES_AFTER_ACT) v[e] = apply_act(v[e], a.act) + rv[e];
-            else v[e] = apply_act(v[e], a.act);
+          for (int q = 0; q < 4; ++q) {
+            const floatx4 b4 = *(const floatx4*)&sBias[cblk + q * 8];
+            floatx4 v;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) v[e] = fmaxf(acc[i][j][q * 4 + e] + b4[e] + res_pre * rv[q][e], act_lo);
+            if (is_silu) {
+#pragma unroll
+              for (int e = 0; e < 4; ++e) v[e] = silu(v[e]);
+            }
+#pragma unroll
+            for (int e = 0; e < 4; ++e) v[e] += res_post * rv[q][e];
+            if (a.out_f32) store4<float>((float*)a.y + o + q * 8, v);
+            else store4<T>((T*)a.y + o + q * 8, v);
           }
-          if (a.out_f32) {
-            float* yp = (float*)a.y + (size_t)p * a.y_ld + a.y_coff + cb;
-            if (vec_ok && nvalid == 4) *(floatx4*)yp = floatx4{v[0], v[1], v[2], v[3]};
-            else { for (int e = 0; e < nvalid; ++e) yp[e] = v[e]; }
-          } else {
-            T* yp = (T*)a.y + (size_t)p * a.y_ld + a.y_coff + cb;
-            if (vec_ok && nvalid == 4) {
-              alignas(16) T o[4];
+        } else {
+          // edge path: channel tail of the tensor or unaligned pitch - element by element
 #pragma unroll
-              for (int e = 0; e < 4; ++e) o[e] = E::from_f32(v[e]);
-              if (sizeof(T) == 2) *(uint2*)yp = *(const uint2*)o;
-              else *(floatx4*)yp = *(const floatx4*)o;
-            } else {
-              for (int e = 0; e < nvalid; ++e) yp[e] = E::from_f32(v[e]);
+          for (int q = 0; q < 4; ++q) {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+              const int cl = cblk + q * 8 + e;
+              const int c = c0 + cl;
+              if (c < a.Cout) {
+                float r = 0.f;
+                if (a.res) r = (float)((const T*)a.res)[(size_t)p * a.res_ld + a.res_coff + c];
+                float t = fmaxf(acc[i][j][q * 4 + e] + sBias[cl] + res_pre * r, act_lo);
+                if (is_silu) t = silu(t);
+                t += res_post * r;
+                const size_t o = (size_t)p * a.y_ld + a.y_coff + c;
+                if (a.out_f32) ((float*)a.y)[o] = t; else ((T*)a.y)[o] = (T)t;
+              }
             }
           }
         }
@@ -256,9 +281,12 @@ __global__ __launch_bounds__(THREADS) void conv_mfma_kernel(const ConvArgs a) {
   }
 }
 
+// kernel id of a conv tile configuration: 1000 + BC*10 ... kept readable: BC, BP and the gather flavour
+int conv_kernel_id(int bc, int bp, bool vec) { return 100000 + bc * 1000 + bp * 2 + (vec ? 1 : 0); }
+
 size_t conv_packed_weight_elems(int cout, int kh, int kw, int cin, int dtype, int* kp_out, int* cout_pad_out) {
   const int vn = dtype == OCTO_F32 ? 4 : 8;
-  const int bk = KVEC * vn;
+  const int bk = 8 * vn;   // largest K step of any tile configuration
   const int K = kh * kw * cin;
   const int kp = (K + bk - 1) / bk * bk;
   const int cp = (cout + 127) / 128 * 128;
@@ -267,40 +295,45 @@ size_t conv_packed_weight_elems(int cout, int kh, int kw, int cin, int dtype, in
   return (size_t)kp * cp;
 }
 
-template <typename T, int BC, int BP, int WC, int WP>
-static hipError_t launch_cfg(const ConvArgs& a, bool vec, int num_cu, hipStream_t s) {
+template <typename T, int BC, int BP, int WC, int WP, int KV = 4>
+static hipError_t launch_cfg(const ConvArgs& a, bool vec, int num_cu, hipStream_t s, int* kernel_id) {
+  if (kernel_id) *kernel_id = conv_kernel_id(BC, BP, vec);
   const long long M = (long long)a.n * a.Ho * a.Wo;
   const long long tiles = ((M + BP - 1) / BP) * ((a.Cout + BC - 1) / BC);
   if (tiles <= 0) return hipSuccess;
   long long grid = tiles;
   const long long cap = (long long)num_cu * 2;      // two resident workgroups per CU (LDS / register bound)
   if (grid > cap) grid = cap;
-  if (vec) hipLaunchKernelGGL((conv_mfma_kernel<T, BC, BP, WC, WP, true>), dim3((unsigned)grid), dim3(THREADS), 0, s, a);
-  else hipLaunchKernelGGL((conv_mfma_kernel<T, BC, BP, WC, WP, false>), dim3((unsigned)grid), dim3(THREADS), 0, s, a);
+  if (vec) hipLaunchKernelGGL((conv_mfma_kernel<T, BC, BP, WC, WP, KV, true>), dim3((unsigned)grid), dim3(THREADS), 0, s, a);
+  else hipLaunchKernelGGL((conv_mfma_kernel<T, BC, BP, WC, WP, KV, false>), dim3((unsigned)grid), dim3(THREADS), 0, s, a);
   return hipGetLastError();
 }
 
 template <typename T>
-static hipError_t launch_typed(const ConvArgs& a, int num_cu, hipStream_t s) {
+static hipError_t launch_typed(const ConvArgs& a, int num_cu, hipStream_t s, int* kernel_id) {
   constexpr int VN = Elem<T>::N;
   const bool vec = (a.Cin % VN == 0) && (a.x_ld % VN == 0) && (a.x_coff % VN == 0) && (((uintptr_t)a.x & 15) == 0);
   const long long M = (long long)a.n * a.Ho * a.Wo;
   // Tile choice: wide channel tiles only when there are enough channels; fall back to smaller pixel tiles when
   // the layer has too few tiles to occupy every CU.
-  if (a.Cout <= 32) return launch_cfg<T, 32, 128, 1, 4>(a, vec, num_cu, s);
+  if (a.Cout <= 32) return launch_cfg<T, 32, 128, 1, 4>(a, vec, num_cu, s, kernel_id);
   if (a.Cout <= 64) {
-    return launch_cfg<T, 64, 128, 2, 2>(a, vec, num_cu, s);
+    return launch_cfg<T, 64, 128, 2, 2>(a, vec, num_cu, s, kernel_id);
   }
   const long long t128 = ((M + 127) / 128) * ((a.Cout + 127) / 128);
-  if (t128 >= 2LL * num_cu) return launch_cfg<T, 128, 128, 2, 2>(a, vec, num_cu, s);
-  return launch_cfg<T, 64, 64, 2, 2>(a, vec, num_cu, s);
+  if (t128 >= 2LL * num_cu) return launch_cfg<T, 128, 128, 2, 2>(a, vec, num_cu, s, kernel_id);
+  return launch_cfg<T, 64, 64, 2, 2>(a, vec, num_cu, s, kernel_id);
 }
 
-hipError_t launch_conv(int dtype, const ConvArgs& a, int num_cu, hipStream_t s) {
+hipError_t launch_conv(int dtype, const ConvArgs& a0, int num_cu, hipStream_t s, int* kernel_id) {
+  ConvArgs a = a0;
+  if (a.Cin < 1 || a.kw < 1 || a.Kp >= 65536) return hipErrorInvalidValue;
+  a.magic_cin = a.Cin > 1 ? (unsigned)((1ull << 32) / (unsigned)a.Cin) + 1u : 0u;
+  a.magic_kw = a.kw > 1 ? (unsigned)((1ull << 32) / (unsigned)a.kw) + 1u : 0u;
   switch (dtype) {
-    case OCTO_F16: return launch_typed<_Float16>(a, num_cu, s);
-    case OCTO_BF16: return launch_typed<__bf16>(a, num_cu, s);
-    case OCTO_F32: return launch_typed<float>(a, num_cu, s);
+    case OCTO_F16: return launch_typed<_Float16>(a, num_cu, s, kernel_id);
+    case OCTO_BF16: return launch_typed<__bf16>(a, num_cu, s, kernel_id);
+    case OCTO_F32: return launch_typed<float>(a, num_cu, s, kernel_id);
   }
   return hipErrorInvalidValue;
 }

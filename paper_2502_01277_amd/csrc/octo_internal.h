@@ -31,6 +31,7 @@ struct ConvArgs {
   int res_ld, res_coff;
   int kh, kw, stride, pad;
   int K, Kp;
+  unsigned magic_cin, magic_kw;   // floor(2^32 / d) + 1 for d = Cin, kw (set by launch_conv)
   int act, res_mode;
   int out_f32;          // write fp32 instead of the storage type
 };
@@ -39,7 +40,9 @@ struct ConvArgs {
 inline __host__ __device__ int dtype_size(int dt) { return dt == OCTO_F32 ? 4 : 2; }
 
 // ---- launchers (each enqueues on `s`, never synchronises) -------------------
-hipError_t launch_conv(int dtype, const ConvArgs& a, int num_cu, hipStream_t s);
+hipError_t launch_conv(int dtype, const ConvArgs& a, int num_cu, hipStream_t s, int* kernel_id = nullptr);
+int conv_kernel_id(int bc, int bp, bool vec);
+enum { KID_NONE = 0, KID_MAXPOOL = 1, KID_UPSAMPLE = 2, KID_COPY = 3, KID_ADD = 4, KID_GAP = 5 };
 size_t conv_packed_weight_elems(int cout, int kh, int kw, int cin, int dtype, int* kp_out, int* cout_pad_out);
 
 struct PoolArgs {

@@ -41,6 +41,7 @@ struct LayerPlan {
   int K = 0, Kp = 0, cout_pad = 0;
   std::vector<int> copy_inputs;   // concat: inputs that could not be aliased into the output buffer
   double flops = 0, bytes = 0;    // per item
+  int kernel_id = KID_NONE;       // which kernel the last launch of this layer used
 };
 
 struct TensorPlan {
@@ -85,6 +86,7 @@ struct Batch {
   hipEvent_t done = nullptr;
   bool finalized = false;
   std::vector<hipEvent_t> stage_ev;
+  std::vector<std::vector<hipEvent_t>> layer_ev;   // per model: one event before the first layer and one after each
   std::vector<bool> model_ran;
 };
 
@@ -116,8 +118,9 @@ struct octo_pipeline {
   std::deque<Batch> inflight;
   std::vector<hipEvent_t> event_pool;
   int next_slot = 0;
-  bool stage_timing = false;
+  bool stage_timing = false, layer_timing = false;
   std::vector<float> last_stage_ms;
+  std::vector<std::vector<float>> last_layer_ms;
   hipEvent_t ev_det = nullptr;
   std::vector<hipEvent_t> ev_child;
   std::string err;
@@ -357,7 +360,7 @@ octo_status pack_weights(octo_pipeline* p, ModelPlan& m, Arena& ar) {
 
 // ---- one layer ----------------------------------------------------------------
 hipError_t run_layer(octo_pipeline* p, ModelPlan& m, int i, int n, const int* n_dyn, hipStream_t s) {
-  const LayerPlan& lp = m.layers[i];
+  LayerPlan& lp = m.layers[i];
   const octo_layer& L = lp.L;
   const TensorView x = view_of(m, L.in[0]);
   const TensorView y = view_of(m, i + 1);
@@ -370,14 +373,16 @@ hipError_t run_layer(octo_pipeline* p, ModelPlan& m, int i, int n, const int* n_
       a.kh = L.kh; a.kw = L.kw; a.stride = L.stride; a.pad = L.pad; a.K = lp.K; a.Kp = lp.Kp;
       a.act = L.act; a.res_mode = L.res_mode; a.out_f32 = m.tensors[i + 1].f32 ? 1 : 0;
       if (L.n_in == 2) { const TensorView r = view_of(m, L.in[1]); a.res = r.ptr; a.res_ld = r.ld; a.res_coff = r.coff; }
-      return launch_conv(m.d.dtype, a, p->num_cu, s);
+      return launch_conv(m.d.dtype, a, p->num_cu, s, &lp.kernel_id);
     }
     case OCTO_MAXPOOL: {
       PoolArgs a{x.ptr, y.ptr, n_dyn, n, x.h, x.w, x.c, x.ld, x.coff, y.h, y.w, y.ld, y.coff, L.kh, L.stride, L.pad};
+      lp.kernel_id = KID_MAXPOOL;
       return launch_maxpool(m.d.dtype, a, s);
     }
     case OCTO_UPSAMPLE2X: {
       PoolArgs a{x.ptr, y.ptr, n_dyn, n, x.h, x.w, x.c, x.ld, x.coff, y.h, y.w, y.ld, y.coff, 1, 1, 0};
+      lp.kernel_id = KID_UPSAMPLE;
       return launch_upsample2x(m.d.dtype, a, s);
     }
     case OCTO_CONCAT: {
@@ -386,6 +391,7 @@ hipError_t run_layer(octo_pipeline* p, ModelPlan& m, int i, int n, const int* n_
         const TensorView t = view_of(m, L.in[k]);
         if (std::find(lp.copy_inputs.begin(), lp.copy_inputs.end(), k) != lp.copy_inputs.end()) {
           PoolArgs a{t.ptr, y.ptr, n_dyn, n, t.h, t.w, t.c, t.ld, t.coff, y.h, y.w, y.ld, y.coff + off, 1, 1, 0};
+          lp.kernel_id = KID_COPY;
           hipError_t e = launch_copy_channels(m.d.dtype, a, s);
           if (e != hipSuccess) return e;
         }
@@ -396,20 +402,24 @@ hipError_t run_layer(octo_pipeline* p, ModelPlan& m, int i, int n, const int* n_
     case OCTO_ADD: {
       const TensorView b = view_of(m, L.in[1]);
       AddArgs a{x.ptr, b.ptr, y.ptr, n_dyn, n, x.h, x.w, x.c, x.ld, x.coff, b.ld, b.coff, y.ld, y.coff, L.act};
+      lp.kernel_id = KID_ADD;
       return launch_add(m.d.dtype, a, s);
     }
     case OCTO_GAP: {
       PoolArgs a{x.ptr, y.ptr, n_dyn, n, x.h, x.w, x.c, x.ld, x.coff, 1, 1, y.ld, y.coff, 1, 1, 0};
+      lp.kernel_id = KID_GAP;
       return launch_gap(m.d.dtype, a, s);
     }
   }
   return hipErrorInvalidValue;
 }
 
-hipError_t run_layers(octo_pipeline* p, ModelPlan& m, int n, const int* n_dyn, hipStream_t s) {
+hipError_t run_layers(octo_pipeline* p, ModelPlan& m, int n, const int* n_dyn, hipStream_t s, std::vector<hipEvent_t>* evs = nullptr) {
+  hipError_t e;
+  if (evs && (e = hipEventRecord((*evs)[0], s)) != hipSuccess) return e;
   for (int i = 0; i < (int)m.layers.size(); ++i) {
-    hipError_t e = run_layer(p, m, i, n, n_dyn, s);
-    if (e != hipSuccess) return e;
+    if ((e = run_layer(p, m, i, n, n_dyn, s)) != hipSuccess) return e;
+    if (evs && (e = hipEventRecord((*evs)[i + 1], s)) != hipSuccess) return e;
   }
   return hipSuccess;
 }
@@ -576,6 +586,12 @@ octo_status start_batch(octo_pipeline* p, hipStream_t s, int* launched) {
     const int ne = 1 + ST_FIXED + 3 * (int)p->edges.size();
     for (int i = 0; i < ne; ++i) { hipEvent_t e = get_event(p); if (!e) return fail(p, OCTO_EHIP, "hipEventCreate failed"); b.stage_ev.push_back(e); }
   }
+  b.layer_ev.resize(p->models.size());
+  if (p->layer_timing)
+    for (size_t k = 0; k < p->models.size(); ++k)
+      for (size_t i = 0; i <= p->models[k].layers.size(); ++i) {
+        hipEvent_t e = get_event(p); if (!e) return fail(p, OCTO_EHIP, "hipEventCreate failed"); b.layer_ev[k].push_back(e);
+      }
   p->inflight.push_back(std::move(b));
   Batch& B = p->inflight.back();
   hipEvent_t* ev = p->stage_timing ? B.stage_ev.data() : nullptr;
@@ -589,7 +605,7 @@ octo_status start_batch(octo_pipeline* p, hipStream_t s, int* launched) {
   ra.pad_value = root.d.pad_value; ra.n = n; ra.n_frames = n;
   HIPCHK(p, launch_letterbox(root.d.dtype, ra, s));
   if (ev) HIPCHK(p, hipEventRecord(ev[1 + ST_LETTERBOX], s));
-  HIPCHK(p, run_layers(p, root, n, nullptr, s));
+  HIPCHK(p, run_layers(p, root, n, nullptr, s, p->layer_timing ? &B.layer_ev[0] : nullptr));
   if (ev) HIPCHK(p, hipEventRecord(ev[1 + ST_DET_LAYERS], s));
   HIPCHK(p, launch_fill_i32((int*)p->d_result, 0, (int)((p->off_boxes) / sizeof(int)), s));   // n_keep, flags, n_roi
   HIPCHK(p, run_detect_tail(p, root, n, nullptr, s, ev ? ev + 1 + ST_DECODE : nullptr));
@@ -622,7 +638,7 @@ octo_status run_child(octo_pipeline* p, Batch& B, int e, hipStream_t s, bool wai
   ra.n = c.cap; ra.n_dyn = c.n_dyn; ra.rois = p->rois[e]; ra.n_frames = B.n;
   HIPCHK(p, launch_crop_resize(c.d.dtype, ra, s));
   if (ev) HIPCHK(p, hipEventRecord(ev[0], s));
-  HIPCHK(p, run_layers(p, c, c.cap, c.n_dyn, s));
+  HIPCHK(p, run_layers(p, c, c.cap, c.n_dyn, s, p->layer_timing ? &B.layer_ev[p->edges[e].child] : nullptr));
   if (ev) HIPCHK(p, hipEventRecord(ev[1], s));
   if (c.d.kind == OCTO_CLASSIFIER) {
     const TensorView lg = view_of(c, c.d.outputs[0]);
@@ -821,6 +837,16 @@ octo_status octo_collect(octo_pipeline* p, octo_frame_result* frames, int32_t fr
       }
       for (hipEvent_t e : B.stage_ev) p->event_pool.push_back(e);
     }
+    p->last_layer_ms.assign(p->models.size(), std::vector<float>());
+    for (size_t k = 0; k < B.layer_ev.size(); ++k) {
+      const std::vector<hipEvent_t>& le = B.layer_ev[k];
+      for (size_t i = 0; i + 1 < le.size(); ++i) {
+        float ms = 0.f;
+        if (!B.model_ran[k] || hipEventElapsedTime(&ms, le[i], le[i + 1]) != hipSuccess) ms = 0.f;
+        p->last_layer_ms[k].push_back(ms);
+      }
+      for (hipEvent_t e : le) p->event_pool.push_back(e);
+    }
     p->event_pool.push_back(B.done);
     p->inflight.pop_front();
   }
@@ -856,6 +882,27 @@ octo_status octo_get_stage_ms(octo_pipeline* p, float* ms, int32_t cap, int32_t*
   if (!p || !ms || !n) return OCTO_EINVAL;
   *n = (int)std::min<size_t>(p->last_stage_ms.size(), (size_t)std::max(cap, 0));
   for (int i = 0; i < *n; ++i) ms[i] = p->last_stage_ms[i];
+  return OCTO_OK;
+}
+
+octo_status octo_set_layer_timing(octo_pipeline* p, int32_t enable) {
+  if (!p) return OCTO_EINVAL;
+  p->layer_timing = enable != 0;
+  return OCTO_OK;
+}
+
+octo_status octo_get_layer_info(octo_pipeline* p, int32_t model, float* ms, int32_t* kernel_id, double* flops, double* bytes,
+                                int32_t cap, int32_t* n) {
+  if (!p) return OCTO_EINVAL;
+  if (model < 0 || model >= (int)p->models.size() || !n || cap < 0) return fail(p, OCTO_EINVAL, "bad arguments");
+  const ModelPlan& m = p->models[model];
+  *n = (int)std::min<size_t>(m.layers.size(), (size_t)cap);
+  for (int i = 0; i < *n; ++i) {
+    if (ms) ms[i] = (model < (int)p->last_layer_ms.size() && i < (int)p->last_layer_ms[model].size()) ? p->last_layer_ms[model][i] : 0.f;
+    if (kernel_id) kernel_id[i] = m.layers[i].kernel_id;
+    if (flops) flops[i] = m.layers[i].flops;
+    if (bytes) bytes[i] = m.layers[i].bytes;
+  }
   return OCTO_OK;
 }
 
