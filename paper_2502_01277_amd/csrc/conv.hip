@@ -5,11 +5,19 @@
 // GEMM view: rows = output channels (weights, [Cout][K] with K = kh*kw*Cin contiguous),
 // columns = output pixels (gathered on the fly from the NHWC input), reduction = K.
 // One workgroup = 4 wavefronts (256 lanes) computes a BC x BP tile with
-// v_mfma_f32_32x32x16 (fp16 / bf16) or v_mfma_f32_32x32x2 (fp32); both operands go
-// global -> registers -> LDS (double buffered, one barrier per K step) and every
-// lane feeds the MFMA with 16-byte LDS reads.  The grid is persistent: workgroups
-// stride over the tile list, whose length may depend on an item count that lives
-// in device memory (a variable number of ROIs), so no host round trip is needed.
+// v_mfma_f32_32x32x16 (fp16 / bf16) or v_mfma_f32_32x32x2 (fp32).  Both operands go
+// global -> registers -> LDS (double buffered, one barrier per K step); each lane
+// feeds the MFMA with 16-byte LDS reads from rows padded by 16 bytes (conflict free).
+//
+// The inner loop is kept nearly free of vector-ALU work, which would otherwise
+// starve the matrix cores: operands are fetched with buffer loads whose 32-bit
+// offsets are "row offset + tap offset", an out-of-image tap gets an offset beyond
+// the buffer range so the hardware returns zeros, and the weight offsets advance
+// through the scalar offset operand.  Loads run D K-steps ahead of the MFMA work.
+//
+// The grid is persistent: workgroups stride over the tile list, whose length may
+// depend on an item count that lives in device memory (a variable number of ROIs),
+// so no host round trip is needed.
 #include "octo_internal.h"
 
 namespace octo {
@@ -44,7 +52,6 @@ template <> struct Elem<float> {
   }
 };
 
-// four consecutive output values: residual, activation, conversion and one 8/16-byte store
 template <typename T>
 __device__ __forceinline__ floatx4 load4(const T* p) {
   if constexpr (sizeof(T) == 4) {
@@ -68,13 +75,18 @@ __device__ __forceinline__ void store4(T* p, floatx4 v) {
 __device__ __forceinline__ float silu(float v) { return v / (1.0f + __expf(-v)); }
 
 constexpr int THREADS = 256;
+constexpr unsigned BUF_FLAGS = 0x00020000u;      // raw buffer, 32-bit data format
+constexpr int OOB = (int)0x80000000;             // offset beyond any buffer range: the load returns zeros
+constexpr long long BUF_MAX = 0x7FFFFFFFLL;
 
 // BC: output channels per tile, BP: pixels per tile, WC x WP: wavefront grid (WC * WP == 4),
-// KV: 16-byte vectors per tile row and K step (one K step = KV*16 bytes of K per row).
-template <typename T, int BC, int BP, int WC, int WP, int KV, bool VEC>
-__global__ __launch_bounds__(THREADS) void conv_mfma_kernel(const ConvArgs a) {
+// KV: 16-byte vectors per tile row and K step (one K step = KV*16 bytes of K per row),
+// D: K steps whose global loads are in flight in registers (even), MINB: workgroups per CU to fit registers for.
+template <typename T, int BC, int BP, int WC, int WP, int KV, int D, int MINB, bool VEC>
+__global__ __launch_bounds__(THREADS, MINB) void conv_mfma_kernel(const ConvArgs a) {
   using E = Elem<T>;
   constexpr int VN = E::N;
+  constexpr int ES = (int)sizeof(T);
   constexpr int BK = KV * VN;            // elements per K step
   constexpr int ROWV = KV + 1;           // LDS row pitch in vectors: (16*KV + 16) bytes keeps 16-byte reads conflict-free
   constexpr int RP = THREADS / KV;       // tile rows covered by one pass of the 256 loader lanes
@@ -82,6 +94,7 @@ __global__ __launch_bounds__(THREADS) void conv_mfma_kernel(const ConvArgs a) {
   constexpr int TP = BP / WP / 32;
   constexpr int LA = (BC + RP - 1) / RP; // vectors per lane per K step (weights)
   constexpr int LB = BP / RP;            // (pixels)
+  static_assert(D % 2 == 0, "pipeline depth must be even");
   static_assert(WC * WP == 4 && TC >= 1 && TP >= 1 && LB >= 1 && BP % RP == 0 && BC % 32 == 0, "tile shape");
 
   __shared__ u32x4 sA[2][BC][ROWV];
@@ -100,10 +113,10 @@ __global__ __launch_bounds__(THREADS) void conv_mfma_kernel(const ConvArgs a) {
   const int tiles_c = (a.Cout + BC - 1) / BC;
   const long long tiles_p = (M + BP - 1) / BP;
   const long long n_tiles = tiles_p * tiles_c;
-  const int nk = a.Kp / BK;
+  const int nk = a.Kp / BK;              // a multiple of D: the host pads Kp to a multiple of 128 bytes
   const T* __restrict__ xg = (const T*)a.x + a.x_coff;
-  const T* __restrict__ wg = (const T*)a.w;
   const int HoWo = a.Ho * a.Wo;
+  const long long img_elems = (long long)a.H * a.W * a.x_ld;
 
   const int ld_row = tid / KV;
   const int ld_kv = tid % KV;
@@ -113,32 +126,48 @@ __global__ __launch_bounds__(THREADS) void conv_mfma_kernel(const ConvArgs a) {
   const float res_pre = a.res_mode == OCTO_RES_BEFORE_ACT ? 1.0f : 0.0f;
   const float res_post = a.res_mode == OCTO_RES_AFTER_ACT ? 1.0f : 0.0f;
 
+  // weights: one buffer for the whole packed matrix (padded, so never out of range)
+  const long long w_bytes = (long long)a.w_rows * a.Kp * ES;
+  const __amdgpu_buffer_rsrc_t rsrc_w = __builtin_amdgcn_make_buffer_rsrc((void*)a.w, 0, (int)(w_bytes < BUF_MAX ? w_bytes : BUF_MAX), BUF_FLAGS);
+
   for (long long tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
     const int tc = (int)(tile % tiles_c);
     const long long tp = tile / tiles_c;
     const int c0 = tc * BC;
     const long long p0 = tp * BP;
 
-    // per-lane pixel rows of the gather: pointer to the (possibly out-of-image) pixel of tap (0, 0)
-    int hi0[LB], wi0[LB];
-    const T* rowp[LB];
+    // activations: a buffer that starts at the first image this tile touches, so that 32-bit offsets suffice
+    const int img0 = (int)(p0 / HoWo);
+    const long long rem_bytes = ((long long)(a.n - img0) * img_elems - a.x_coff) * ES;
+    const __amdgpu_buffer_rsrc_t rsrc_x =
+        __builtin_amdgcn_make_buffer_rsrc((void*)(xg + (long long)img0 * img_elems), 0, (int)(rem_bytes < BUF_MAX ? rem_bytes : BUF_MAX), BUF_FLAGS);
+
+    // per-lane pixel rows of the gather: byte offset of the (possibly out-of-image) pixel of tap (0, 0) and the
+    // sets of kernel rows / columns that fall inside the image (bit r: row r ok; bit 16+s: column s ok)
+    int rowoff[LB];
+    unsigned hw_ok[LB];
+    int hi0[LB], wi0[LB];   // only used by the element-wise gather
 #pragma unroll
     for (int i = 0; i < LB; ++i) {
       const long long m = p0 + ld_row + RP * i;
+      rowoff[i] = 0; hw_ok[i] = 0u; hi0[i] = -1000000; wi0[i] = 0;
       if (m < M) {
         const int img = (int)(m / HoWo);
         const int rem = (int)(m - (long long)img * HoWo);
         const int ho = rem / a.Wo, wo = rem - ho * a.Wo;
-        hi0[i] = ho * a.stride - a.pad;
-        wi0[i] = wo * a.stride - a.pad;
-        rowp[i] = xg + (((long long)img * a.H + hi0[i]) * a.W + wi0[i]) * a.x_ld;
-      } else {
-        hi0[i] = -1000000; wi0[i] = 0; rowp[i] = xg;
+        const int h0 = ho * a.stride - a.pad, w0 = wo * a.stride - a.pad;
+        hi0[i] = h0; wi0[i] = w0;
+        rowoff[i] = (int)((((long long)(img - img0) * a.H + h0) * a.W + w0) * a.x_ld) * ES;
+        unsigned m2 = 0u;
+        for (int r = 0; r < a.kh; ++r) m2 |= ((unsigned)(h0 + r) < (unsigned)a.H ? 1u : 0u) << r;
+        for (int s2 = 0; s2 < a.kw; ++s2) m2 |= ((unsigned)(w0 + s2) < (unsigned)a.W ? 1u : 0u) << (16 + s2);
+        hw_ok[i] = m2;
       }
     }
-    const T* wrow[LA];
+    int woff[LA];
 #pragma unroll
-    for (int i = 0; i < LA; ++i) wrow[i] = wg + (size_t)(c0 + ld_row + RP * i) * a.Kp + ld_kv * VN;
+    for (int i = 0; i < LA; ++i) woff[i] = ((c0 + ld_row + RP * i) * a.Kp + ld_kv * VN) * ES;
+
     floatx16 acc[TC][TP];
 #pragma unroll
     for (int i = 0; i < TC; ++i)
@@ -147,36 +176,33 @@ __global__ __launch_bounds__(THREADS) void conv_mfma_kernel(const ConvArgs a) {
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
 
-    u32x4 ra[LA], rb[LB];
-    bool rb_ok[LB];
+    u32x4 ra[D][LA], rb[D][LB];
 
-    // Operands of K step KB: global -> registers.  The loads are unconditional (an out-of-image tap reads a safe
-    // address and is zeroed when it is written to LDS) so that they stay in flight during the MFMA work.
-    // Element k = KB*BK + ld_kv*VN of the reduction is channel c of tap (r, s): k = (r*kw + s)*Cin + c; the two
-    // divisions use precomputed reciprocals (exact for k < 65536).
-#define OCTO_CONV_LOAD(KB)                                                                                          \
+    // Operands of K step KB -> register slot SL.  Element k = KB*BK + ld_kv*VN of the reduction is channel c of tap
+    // (r, s): k = (r*kw + s)*Cin + c; the two divisions use precomputed reciprocals (exact for k < 65536).
+#define OCTO_CONV_LOAD(KB, SL)                                                                                      \
     {                                                                                                               \
       _Pragma("unroll") for (int i = 0; i < LA; ++i)                                                                \
-        if (BC % RP == 0 || ld_row + RP * i < BC) ra[i] = *(const u32x4*)(wrow[i] + (size_t)(KB) * BK);             \
+        if (BC % RP == 0 || ld_row + RP * i < BC)                                                                   \
+          ra[SL][i] = __builtin_amdgcn_raw_buffer_load_b128(rsrc_w, woff[i], (KB) * (BK * ES), 0);                  \
       if (VEC) {                                                                                                    \
         const unsigned k = (unsigned)(KB) * BK + ld_kv * VN;                                                        \
         const unsigned tap = __umulhi(k, a.magic_cin);                                                              \
         const int c = (int)(k - tap * a.Cin);                                                                       \
         const int r = a.kw == 1 ? (int)tap : (int)__umulhi(tap, a.magic_kw);                                        \
         const int s2 = (int)tap - r * a.kw;                                                                         \
-        const int delta = (r * a.W + s2) * a.x_ld + c;                                                              \
-        const bool tap_ok = k < (unsigned)a.K;                                                                      \
+        const int delta = ((r * a.W + s2) * a.x_ld + c) * ES;                                                       \
+        const unsigned need = k < (unsigned)a.K ? ((1u << r) | (0x10000u << s2)) : 0xFFFFFFFFu;                     \
         _Pragma("unroll") for (int i = 0; i < LB; ++i) {                                                            \
-          const bool ok = tap_ok & ((unsigned)(hi0[i] + r) < (unsigned)a.H) & ((unsigned)(wi0[i] + s2) < (unsigned)a.W); \
-          const T* src = ok ? rowp[i] + delta : xg;                                                                 \
-          rb[i] = *(const u32x4*)src;                                                                               \
-          rb_ok[i] = ok;                                                                                            \
+          const int off = (hw_ok[i] & need) == need ? rowoff[i] + delta : OOB;                                      \
+          rb[SL][i] = __builtin_amdgcn_raw_buffer_load_b128(rsrc_x, off, 0, 0);                                     \
         }                                                                                                           \
       } else {                                                                                                      \
         const int kbase = (KB) * BK + ld_kv * VN;                                                                   \
         _Pragma("unroll") for (int i = 0; i < LB; ++i) {                                                            \
           typedef T tv __attribute__((ext_vector_type(VN)));                                                        \
           tv pk;                                                                                                    \
+          const T* rowp = xg + (long long)img0 * img_elems + rowoff[i] / ES;                                        \
           _Pragma("unroll") for (int e = 0; e < VN; ++e) {                                                          \
             const int k = kbase + e;                                                                                \
             T val = (T)0.0f;                                                                                        \
@@ -184,40 +210,45 @@ __global__ __launch_bounds__(THREADS) void conv_mfma_kernel(const ConvArgs a) {
               const int tap = k / a.Cin, c = k - tap * a.Cin;                                                       \
               const int r = tap / a.kw, s2 = tap - r * a.kw;                                                        \
               if ((unsigned)(hi0[i] + r) < (unsigned)a.H && (unsigned)(wi0[i] + s2) < (unsigned)a.W)                \
-                val = rowp[i][(r * a.W + s2) * a.x_ld + c];                                                         \
+                val = rowp[(r * a.W + s2) * a.x_ld + c];                                                            \
             }                                                                                                       \
             pk[e] = val;                                                                                            \
           }                                                                                                         \
-          rb[i] = __builtin_bit_cast(u32x4, pk);                                                                    \
-          rb_ok[i] = true;                                                                                          \
+          rb[SL][i] = __builtin_bit_cast(u32x4, pk);                                                                \
         }                                                                                                           \
       }                                                                                                             \
     }
 
     __syncthreads();   // the previous tile's LDS reads are done
     if (tid < BC) sBias[tid] = a.bias[c0 + tid];     // bias is padded to a multiple of 128 channels
-    OCTO_CONV_LOAD(0)
-    for (int kb = 0; kb < nk; ++kb) {
-      const int buf = kb & 1;
-      // operands of step kb: registers -> LDS
+    // nk is a multiple of D (the packed K extent is padded accordingly); loads past the end return zeros
 #pragma unroll
-      for (int i = 0; i < LA; ++i)
-        if (BC % RP == 0 || ld_row + RP * i < BC) sA[buf][ld_row + RP * i][ld_kv] = ra[i];
+    for (int d = 0; d < D; ++d) OCTO_CONV_LOAD(d, d)
+    for (int kb0 = 0; kb0 < nk; kb0 += D) {
 #pragma unroll
-      for (int i = 0; i < LB; ++i) sB[buf][ld_row + RP * i][ld_kv] = rb_ok[i] ? rb[i] : u32x4{0u, 0u, 0u, 0u};
-      __syncthreads();
-      if (kb + 1 < nk) OCTO_CONV_LOAD(kb + 1)
+      for (int d = 0; d < D; ++d) {
+        const int kb = kb0 + d;
+        const int buf = d & 1;           // D is even, so kb & 1 == d & 1
+        // operands of step kb: registers -> LDS
 #pragma unroll
-      for (int kk = 0; kk < KV / 2; ++kk) {
-        u32x4 fa[TC], fb[TP];
+        for (int i = 0; i < LA; ++i)
+          if (BC % RP == 0 || ld_row + RP * i < BC) sA[buf][ld_row + RP * i][ld_kv] = ra[d][i];
 #pragma unroll
-        for (int i = 0; i < TC; ++i) fa[i] = sA[buf][wc * (BC / WC) + i * 32 + l32][kk * 2 + g];
+        for (int i = 0; i < LB; ++i) sB[buf][ld_row + RP * i][ld_kv] = rb[d][i];
+        __syncthreads();
+        OCTO_CONV_LOAD(kb + D, d)
 #pragma unroll
-        for (int j = 0; j < TP; ++j) fb[j] = sB[buf][wp * (BP / WP) + j * 32 + l32][kk * 2 + g];
+        for (int kk = 0; kk < KV / 2; ++kk) {
+          u32x4 fa[TC], fb[TP];
 #pragma unroll
-        for (int i = 0; i < TC; ++i)
+          for (int i = 0; i < TC; ++i) fa[i] = sA[buf][wc * (BC / WC) + i * 32 + l32][kk * 2 + g];
 #pragma unroll
-          for (int j = 0; j < TP; ++j) acc[i][j] = E::mfma(fa[i], fb[j], acc[i][j]);
+          for (int j = 0; j < TP; ++j) fb[j] = sB[buf][wp * (BP / WP) + j * 32 + l32][kk * 2 + g];
+#pragma unroll
+          for (int i = 0; i < TC; ++i)
+#pragma unroll
+            for (int j = 0; j < TP; ++j) acc[i][j] = E::mfma(fa[i], fb[j], acc[i][j]);
+        }
       }
     }
 #undef OCTO_CONV_LOAD
@@ -281,7 +312,7 @@ __global__ __launch_bounds__(THREADS) void conv_mfma_kernel(const ConvArgs a) {
   }
 }
 
-// kernel id of a conv tile configuration: 1000 + BC*10 ... kept readable: BC, BP and the gather flavour
+// kernel id of a conv tile configuration: channel tile, pixel tile and the gather flavour
 int conv_kernel_id(int bc, int bp, bool vec) { return 100000 + bc * 1000 + bp * 2 + (vec ? 1 : 0); }
 
 size_t conv_packed_weight_elems(int cout, int kh, int kw, int cin, int dtype, int* kp_out, int* cout_pad_out) {
@@ -295,39 +326,49 @@ size_t conv_packed_weight_elems(int cout, int kh, int kw, int cin, int dtype, in
   return (size_t)kp * cp;
 }
 
-template <typename T, int BC, int BP, int WC, int WP, int KV = 4>
-static hipError_t launch_cfg(const ConvArgs& a, bool vec, int num_cu, hipStream_t s, int* kernel_id) {
-  if (kernel_id) *kernel_id = conv_kernel_id(BC, BP, vec);
+#ifndef OCTO_CONV_NO_LAUNCHERS
+template <typename T, int BC, int BP, int WC, int WP, int KV, int D, int MINB, bool VEC>
+static hipError_t launch_cfg(const ConvArgs& a, int num_cu, hipStream_t s, int* kernel_id) {
+  if (kernel_id) *kernel_id = conv_kernel_id(BC, BP, VEC);
   const long long M = (long long)a.n * a.Ho * a.Wo;
   const long long tiles = ((M + BP - 1) / BP) * ((a.Cout + BC - 1) / BC);
   if (tiles <= 0) return hipSuccess;
   long long grid = tiles;
-  const long long cap = (long long)num_cu * 2;      // two resident workgroups per CU (LDS / register bound)
+  const long long cap = (long long)num_cu * MINB;
   if (grid > cap) grid = cap;
-  if (vec) hipLaunchKernelGGL((conv_mfma_kernel<T, BC, BP, WC, WP, KV, true>), dim3((unsigned)grid), dim3(THREADS), 0, s, a);
-  else hipLaunchKernelGGL((conv_mfma_kernel<T, BC, BP, WC, WP, KV, false>), dim3((unsigned)grid), dim3(THREADS), 0, s, a);
+  hipLaunchKernelGGL((conv_mfma_kernel<T, BC, BP, WC, WP, KV, D, MINB, VEC>), dim3((unsigned)grid), dim3(THREADS), 0, s, a);
   return hipGetLastError();
 }
 
 template <typename T>
 static hipError_t launch_typed(const ConvArgs& a, int num_cu, hipStream_t s, int* kernel_id) {
   constexpr int VN = Elem<T>::N;
-  const bool vec = (a.Cin % VN == 0) && (a.x_ld % VN == 0) && (a.x_coff % VN == 0) && (((uintptr_t)a.x & 15) == 0);
+  const bool vec = (a.Cin % VN == 0) && (a.x_ld % VN == 0) && (a.x_coff % VN == 0) && (((uintptr_t)a.x & 15) == 0) &&
+                   a.kh <= 15 && a.kw <= 15;
   const long long M = (long long)a.n * a.Ho * a.Wo;
-  // Tile choice: wide channel tiles only when there are enough channels; fall back to smaller pixel tiles when
-  // the layer has too few tiles to occupy every CU.
-  if (a.Cout <= 32) return launch_cfg<T, 32, 128, 1, 4>(a, vec, num_cu, s, kernel_id);
-  if (a.Cout <= 64) {
-    return launch_cfg<T, 64, 128, 2, 2>(a, vec, num_cu, s, kernel_id);
+  auto tiles = [&](int bc, int bp) { return ((M + bp - 1) / bp) * ((a.Cout + bc - 1) / bc); };
+  if (!vec) {
+    // element-wise gather (first layers with 3 input channels)
+    if (a.Cout <= 32) return launch_cfg<T, 32, 128, 1, 4, 4, 2, 2, false>(a, num_cu, s, kernel_id);
+    return launch_cfg<T, 64, 128, 2, 2, 4, 2, 2, false>(a, num_cu, s, kernel_id);
   }
-  const long long t128 = ((M + 127) / 128) * ((a.Cout + 127) / 128);
-  if (t128 >= 2LL * num_cu) return launch_cfg<T, 128, 128, 2, 2>(a, vec, num_cu, s, kernel_id);
-  return launch_cfg<T, 64, 64, 2, 2>(a, vec, num_cu, s, kernel_id);
+  // Tile choice (measured on MI355X): the widest tile whose tile count still covers the chip; K steps of 128 bytes
+  // when the padded reduction length allows it; small tiles at high occupancy for layers with few output pixels.
+  if (a.Cout <= 32) return launch_cfg<T, 32, 128, 1, 4, 4, 2, 3, true>(a, num_cu, s, kernel_id);
+  if (a.Cout >= 128 && tiles(128, 128) >= num_cu) return launch_cfg<T, 128, 128, 2, 2, 4, 2, 2, true>(a, num_cu, s, kernel_id);
+  if (tiles(64, 128) >= num_cu / 2) {
+    if (sizeof(T) == 2 && a.Kp % (16 * VN) == 0) return launch_cfg<T, 64, 128, 2, 2, 8, 2, 2, true>(a, num_cu, s, kernel_id);
+    return launch_cfg<T, 64, 128, 2, 2, 4, 2, 3, true>(a, num_cu, s, kernel_id);
+  }
+  return launch_cfg<T, 64, 64, 2, 2, 4, 2, 4, true>(a, num_cu, s, kernel_id);
 }
 
 hipError_t launch_conv(int dtype, const ConvArgs& a0, int num_cu, hipStream_t s, int* kernel_id) {
   ConvArgs a = a0;
-  if (a.Cin < 1 || a.kw < 1 || a.Kp >= 65536) return hipErrorInvalidValue;
+  if (a.Cin < 1 || a.kw < 1 || a.kh < 1 || a.stride < 1 || a.Kp >= 65536 || a.w_rows < 1) return hipErrorInvalidValue;
+  // a tile addresses its pixels with 32-bit byte offsets from the first image it touches: at most two images plus
+  // 256 output pixels' worth of further images
+  if ((2LL * a.H * a.W + 1024LL * a.stride * a.stride) * a.x_ld * dtype_size(dtype) > 0x7FFFFFF0LL) return hipErrorInvalidValue;
   a.magic_cin = a.Cin > 1 ? (unsigned)((1ull << 32) / (unsigned)a.Cin) + 1u : 0u;
   a.magic_kw = a.kw > 1 ? (unsigned)((1ull << 32) / (unsigned)a.kw) + 1u : 0u;
   switch (dtype) {
@@ -337,5 +378,6 @@ hipError_t launch_conv(int dtype, const ConvArgs& a0, int num_cu, hipStream_t s,
   }
   return hipErrorInvalidValue;
 }
+#endif
 
 }  // namespace octo

@@ -31,6 +31,7 @@ struct ConvArgs {
   int res_ld, res_coff;
   int kh, kw, stride, pad;
   int K, Kp;
+  int w_rows;                     // rows of the packed weight matrix (cout padded to a multiple of 128)
   unsigned magic_cin, magic_kw;   // floor(2^32 / d) + 1 for d = Cin, kw (set by launch_conv)
   int act, res_mode;
   int out_f32;          // write fp32 instead of the storage type

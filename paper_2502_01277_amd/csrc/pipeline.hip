@@ -342,7 +342,7 @@ octo_status pack_weights(octo_pipeline* p, ModelPlan& m, Arena& ar) {
     if (lp.L.op != OCTO_CONV && lp.L.op != OCTO_FC) continue;
     lp.K = lp.L.kh * lp.L.kw * lp.cin;
     const size_t elems = conv_packed_weight_elems(lp.L.cout, lp.L.kh, lp.L.kw, lp.cin, m.d.dtype, &lp.Kp, &lp.cout_pad);
-    lp.d_weight = ar.alloc(elems * es);
+    lp.d_weight = ar.alloc(elems * es + 512);   // slack: the conv prefetch may read a K step past the last row
     lp.d_bias = (float*)ar.alloc((size_t)lp.cout_pad * sizeof(float));
     if (!ar.base) continue;
     if (ar.failed) return OCTO_ENOMEM;
@@ -370,7 +370,7 @@ hipError_t run_layer(octo_pipeline* p, ModelPlan& m, int i, int n, const int* n_
       a.x = x.ptr; a.w = lp.d_weight; a.bias = lp.d_bias; a.y = y.ptr; a.n_dyn = n_dyn; a.n = n;
       a.H = x.h; a.W = x.w; a.Cin = x.c; a.x_ld = x.ld; a.x_coff = x.coff;
       a.Ho = y.h; a.Wo = y.w; a.Cout = y.c; a.y_ld = y.ld; a.y_coff = y.coff;
-      a.kh = L.kh; a.kw = L.kw; a.stride = L.stride; a.pad = L.pad; a.K = lp.K; a.Kp = lp.Kp;
+      a.kh = L.kh; a.kw = L.kw; a.stride = L.stride; a.pad = L.pad; a.K = lp.K; a.Kp = lp.Kp; a.w_rows = lp.cout_pad;
       a.act = L.act; a.res_mode = L.res_mode; a.out_f32 = m.tensors[i + 1].f32 ? 1 : 0;
       if (L.n_in == 2) { const TensorView r = view_of(m, L.in[1]); a.res = r.ptr; a.res_ld = r.ld; a.res_coff = r.coff; }
       return launch_conv(m.d.dtype, a, p->num_cu, s, &lp.kernel_id);
