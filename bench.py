@@ -150,7 +150,7 @@ def main():
                 "avg_launch_us": 1e3 * t_ms / launches, "launches_per_step": launches / ksteps,
                 "all_conv_tflops": sum(v[1] for v in conv.values()) / (sum(v[0] for v in conv.values()) * 1e-3) / 1e12,
                 "conv_ms_per_step": sum(v[0] for v in conv.values()) / ksteps}
-    names = ["upload", "letterbox", "detector_layers", "decode", "topk", "nms", "compact"]
+    names = ["letterbox", "detector_layers", "decode", "topk", "nms", "compact"]
     for e in range(len(spec.edges)):
         names += ["crop%d" % e, "child%d_layers" % e, "child%d_tail" % e]
     out = {

@@ -1,6 +1,8 @@
 // Convolution as an implicit GEMM on the CDNA4 matrix cores.
 //
 //   y[n,p,q,k] = act(bias[k] + sum_{r,s,c} x[n, p*stride + r - pad, q*stride + s - pad, c] * w[k,r,s,c]  (+ residual))
+// (vertical and horizontal stride / padding are separate arguments: a 3-channel first layer is run on the
+// pixel-pair view of a 4-channel-padded input, see pipeline.hip)
 //
 // GEMM view: rows = output channels (weights, [Cout][K] with K = kh*kw*Cin contiguous),
 // columns = output pixels (gathered on the fly from the NHWC input), reduction = K.
@@ -72,7 +74,10 @@ __device__ __forceinline__ void store4(T* p, floatx4 v) {
     *(u32x2*)p = __builtin_bit_cast(u32x2, o);
   }
 }
-__device__ __forceinline__ float silu(float v) { return v / (1.0f + __expf(-v)); }
+// x * sigmoid(x) with the hardware exp2 / reciprocal (about 1 ulp each: far below the storage precision)
+// floor(n / d) for n < 2^31 with magic = ceil(2^(32+shift) / d) (fits 32 bits for the shift chosen on the host)
+__device__ __forceinline__ unsigned udiv(unsigned n, unsigned magic, unsigned shift) { return __umulhi(n, magic) >> shift; }
+__device__ __forceinline__ float silu(float v) { return v * __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(v * -1.4426950408889634f)); }
 
 constexpr int THREADS = 256;
 constexpr unsigned BUF_FLAGS = 0x00020000u;      // raw buffer, 32-bit data format
@@ -97,9 +102,14 @@ __global__ __launch_bounds__(THREADS, MINB) void conv_mfma_kernel(const ConvArgs
   static_assert(D % 2 == 0, "pipeline depth must be even");
   static_assert(WC * WP == 4 && TC >= 1 && TP >= 1 && LB >= 1 && BP % RP == 0 && BC % 32 == 0, "tile shape");
 
-  __shared__ u32x4 sA[2][BC][ROWV];
-  __shared__ u32x4 sB[2][BP][ROWV];
+  // operand tiles; after the K loop the same memory stages the output tile as [pixel][channel] so that it can be
+  // written with 16-byte stores that cover whole cache lines
+  __shared__ u32x4 smem[2 * (BC + BP) * ROWV];
   __shared__ float sBias[BC];
+  u32x4 (*sA)[BC][ROWV] = (u32x4 (*)[BC][ROWV])smem;
+  u32x4 (*sB)[BP][ROWV] = (u32x4 (*)[BP][ROWV])(smem + 2 * BC * ROWV);
+  constexpr int OPITCH = BC * ES + 16;                                    // bytes per staged output row
+  constexpr bool STAGED = BP * OPITCH <= 2 * (BC + BP) * ROWV * 16;       // does the output tile fit?
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -152,16 +162,21 @@ __global__ __launch_bounds__(THREADS, MINB) void conv_mfma_kernel(const ConvArgs
       const long long m = p0 + ld_row + RP * i;
       rowoff[i] = 0; hw_ok[i] = 0u; hi0[i] = -1000000; wi0[i] = 0;
       if (m < M) {
-        const int img = (int)(m / HoWo);
-        const int rem = (int)(m - (long long)img * HoWo);
-        const int ho = rem / a.Wo, wo = rem - ho * a.Wo;
-        const int h0 = ho * a.stride - a.pad, w0 = wo * a.stride - a.pad;
+        // m < 2^31 (checked on the host): pixel -> (image, row, column) with precomputed reciprocals
+        const unsigned mu = (unsigned)m;
+        const unsigned img = a.HoWo_is_one ? mu : udiv(mu, a.magic_howo, a.shift_howo);
+        const unsigned rem = mu - img * (unsigned)HoWo;
+        const unsigned ho = a.Wo == 1 ? rem : udiv(rem, a.magic_wo, a.shift_wo);
+        const unsigned wo = rem - ho * (unsigned)a.Wo;
+        const int h0 = (int)ho * a.stride_h - a.pad_h, w0 = (int)wo * a.stride_w - a.pad_w;
         hi0[i] = h0; wi0[i] = w0;
-        rowoff[i] = (int)((((long long)(img - img0) * a.H + h0) * a.W + w0) * a.x_ld) * ES;
-        unsigned m2 = 0u;
-        for (int r = 0; r < a.kh; ++r) m2 |= ((unsigned)(h0 + r) < (unsigned)a.H ? 1u : 0u) << r;
-        for (int s2 = 0; s2 < a.kw; ++s2) m2 |= ((unsigned)(w0 + s2) < (unsigned)a.W ? 1u : 0u) << (16 + s2);
-        hw_ok[i] = m2;
+        rowoff[i] = (int)((((long long)((int)img - img0) * a.H + h0) * a.W + w0) * a.x_ld) * ES;
+        // kernel rows r with 0 <= h0 + r < H form the range [max(0, -h0), min(kh, H - h0)); same for columns
+        const int rlo = h0 < 0 ? -h0 : 0, rhi = a.H - h0 < a.kh ? a.H - h0 : a.kh;
+        const int slo = w0 < 0 ? -w0 : 0, shi = a.W - w0 < a.kw ? a.W - w0 : a.kw;
+        const unsigned rm = rhi > rlo ? ((1u << rhi) - 1u) & ~((1u << rlo) - 1u) : 0u;
+        const unsigned sm = shi > slo ? ((1u << shi) - 1u) & ~((1u << slo) - 1u) : 0u;
+        hw_ok[i] = rm | (sm << 16);
       }
     }
     int woff[LA];
@@ -254,22 +269,33 @@ __global__ __launch_bounds__(THREADS, MINB) void conv_mfma_kernel(const ConvArgs
 #undef OCTO_CONV_LOAD
 
     // epilogue: a lane holds pixel column l32 of each 32x32 block and 4 groups of 4 consecutive channels
+    const bool staged = STAGED && !a.out_f32 && ((a.y_ld | a.y_coff) & (VN - 1)) == 0 && (((uintptr_t)a.y & 15) == 0);
+    if (staged) __syncthreads();       // every wavefront is done reading the operand tiles
 #pragma unroll
     for (int j = 0; j < TP; ++j) {
-      const long long p = p0 + wp * (BP / WP) + j * 32 + l32;
+      const int pl = wp * (BP / WP) + j * 32 + l32;          // pixel inside the tile
+      const long long p = p0 + pl;
       if (p >= M) continue;
 #pragma unroll
       for (int i = 0; i < TC; ++i) {
         const int cblk = wc * (BC / WC) + i * 32 + g * 4;     // channel (inside the tile) of this lane's group q = 0
-        if (vec_ok && c0 + cblk + 28 <= a.Cout) {
-          // fast path: all four 4-channel groups are inside the tensor and 8/16-byte accesses are aligned
+        if (staged || (vec_ok && c0 + cblk + 28 <= a.Cout)) {
+          // all four 4-channel groups are inside the tensor and 8/16-byte accesses are aligned (a staged tile may
+          // carry channels past Cout; they are dropped when the tile is written out)
           floatx4 rv[4];
 #pragma unroll
           for (int q = 0; q < 4; ++q) rv[q] = floatx4{0.f, 0.f, 0.f, 0.f};
           if (a.res) {
             const T* rp = (const T*)a.res + (size_t)p * a.res_ld + a.res_coff + c0 + cblk;
+            if (vec_ok && c0 + cblk + 28 <= a.Cout) {
 #pragma unroll
-            for (int q = 0; q < 4; ++q) rv[q] = load4<T>(rp + q * 8);
+              for (int q = 0; q < 4; ++q) rv[q] = load4<T>(rp + q * 8);
+            } else {
+#pragma unroll
+              for (int q = 0; q < 4; ++q)
+#pragma unroll
+                for (int e = 0; e < 4; ++e) if (c0 + cblk + q * 8 + e < a.Cout) rv[q][e] = (float)rp[q * 8 + e];
+            }
           }
           const size_t o = (size_t)p * a.y_ld + a.y_coff + c0 + cblk;
 #pragma unroll
@@ -284,7 +310,8 @@ __global__ __launch_bounds__(THREADS, MINB) void conv_mfma_kernel(const ConvArgs
             }
 #pragma unroll
             for (int e = 0; e < 4; ++e) v[e] += res_post * rv[q][e];
-            if (a.out_f32) store4<float>((float*)a.y + o + q * 8, v);
+            if (staged) store4<T>((T*)((char*)smem + (size_t)pl * OPITCH) + cblk + q * 8, v);
+            else if (a.out_f32) store4<float>((float*)a.y + o + q * 8, v);
             else store4<T>((T*)a.y + o + q * 8, v);
           }
         } else {
@@ -305,6 +332,31 @@ __global__ __launch_bounds__(THREADS, MINB) void conv_mfma_kernel(const ConvArgs
                 if (a.out_f32) ((float*)a.y)[o] = t; else ((T*)a.y)[o] = (T)t;
               }
             }
+          }
+        }
+      }
+    }
+    if (staged) {
+      // staged tile -> global memory: consecutive lanes write consecutive 16-byte pieces of a pixel's channels
+      __syncthreads();
+      constexpr int VPR = BC / VN;                 // 16-byte vectors per pixel row of the tile
+      constexpr int PPP = THREADS / VPR;           // pixels per pass
+      const int v = tid % VPR, pr = tid / VPR;
+      const int c = c0 + v * VN;
+#pragma unroll
+      for (int ps = 0; ps < BP / PPP; ++ps) {
+        const int pl = ps * PPP + pr;
+        const long long p = p0 + pl;
+        if (p < M && c < a.Cout) {
+          const u32x4 val = *(const u32x4*)((const char*)smem + (size_t)pl * OPITCH + (size_t)v * 16);
+          T* yp = (T*)a.y + (size_t)p * a.y_ld + a.y_coff + c;
+          if (c + VN <= a.Cout) {
+            *(u32x4*)yp = val;
+          } else {
+            typedef T tv __attribute__((ext_vector_type(VN)));
+            const tv tvv = __builtin_bit_cast(tv, val);
+#pragma unroll
+            for (int e = 0; e < VN; ++e) if (c + e < a.Cout) yp[e] = tvv[e];
           }
         }
       }
@@ -354,7 +406,7 @@ static hipError_t launch_typed(const ConvArgs& a, int num_cu, hipStream_t s, int
   }
   // Tile choice (measured on MI355X): the widest tile whose tile count still covers the chip; K steps of 128 bytes
   // when the padded reduction length allows it; small tiles at high occupancy for layers with few output pixels.
-  if (a.Cout <= 32) return launch_cfg<T, 32, 128, 1, 4, 4, 2, 3, true>(a, num_cu, s, kernel_id);
+  if (a.Cout <= 32) return launch_cfg<T, 32, 128, 1, 4, 4, 2, 4, true>(a, num_cu, s, kernel_id);
   if (a.Cout >= 128 && tiles(128, 128) >= num_cu) return launch_cfg<T, 128, 128, 2, 2, 4, 2, 2, true>(a, num_cu, s, kernel_id);
   if (tiles(64, 128) >= num_cu / 2) {
     if (sizeof(T) == 2 && a.Kp % (16 * VN) == 0) return launch_cfg<T, 64, 128, 2, 2, 8, 2, 2, true>(a, num_cu, s, kernel_id);
@@ -363,14 +415,32 @@ static hipError_t launch_typed(const ConvArgs& a, int num_cu, hipStream_t s, int
   return launch_cfg<T, 64, 64, 2, 2, 4, 2, 4, true>(a, num_cu, s, kernel_id);
 }
 
-hipError_t launch_conv(int dtype, const ConvArgs& a0, int num_cu, hipStream_t s, int* kernel_id) {
-  ConvArgs a = a0;
-  if (a.Cin < 1 || a.kw < 1 || a.kh < 1 || a.stride < 1 || a.Kp >= 65536 || a.w_rows < 1) return hipErrorInvalidValue;
+// Checks the limits the kernel relies on and fills the precomputed reciprocals.
+bool conv_prepare(ConvArgs& a, int dtype) {
+  if (a.Cin < 1 || a.kw < 1 || a.kh < 1 || a.stride_h < 1 || a.stride_w < 1 || a.Kp >= 65536 || a.w_rows < 1) return false;
   // a tile addresses its pixels with 32-bit byte offsets from the first image it touches: at most two images plus
   // 256 output pixels' worth of further images
-  if ((2LL * a.H * a.W + 1024LL * a.stride * a.stride) * a.x_ld * dtype_size(dtype) > 0x7FFFFFF0LL) return hipErrorInvalidValue;
+  if ((2LL * a.H * a.W + 1024LL * a.stride_h * a.stride_w) * a.x_ld * dtype_size(dtype) > 0x7FFFFFF0LL) return false;
+  if ((long long)a.n * a.Ho * a.Wo >= 0x7FFFFFFFLL) return false;
+  // floor(n / d) = umulhi(n, magic) >> shift, exact for n < 2^31
+  auto magic = [](unsigned d, unsigned* mg, unsigned* sh) {
+    unsigned s = 0;
+    while ((1ull << s) < d) ++s;
+    const unsigned long long m = ((1ull << (32 + s)) + d - 1) / d;
+    if (m >> 32) { *mg = (unsigned)(((1ull << (31 + s)) + d - 1) / d); *sh = s - 1; }
+    else { *mg = (unsigned)m; *sh = s; }
+  };
+  a.HoWo_is_one = (a.Ho * a.Wo == 1) ? 1 : 0;
+  if (!a.HoWo_is_one) magic((unsigned)(a.Ho * a.Wo), &a.magic_howo, &a.shift_howo);
+  if (a.Wo > 1) magic((unsigned)a.Wo, &a.magic_wo, &a.shift_wo);
   a.magic_cin = a.Cin > 1 ? (unsigned)((1ull << 32) / (unsigned)a.Cin) + 1u : 0u;
   a.magic_kw = a.kw > 1 ? (unsigned)((1ull << 32) / (unsigned)a.kw) + 1u : 0u;
+  return true;
+}
+
+hipError_t launch_conv(int dtype, const ConvArgs& a0, int num_cu, hipStream_t s, int* kernel_id) {
+  ConvArgs a = a0;
+  if (!conv_prepare(a, dtype)) return hipErrorInvalidValue;
   switch (dtype) {
     case OCTO_F16: return launch_typed<_Float16>(a, num_cu, s, kernel_id);
     case OCTO_BF16: return launch_typed<__bf16>(a, num_cu, s, kernel_id);

@@ -29,9 +29,10 @@ struct ConvArgs {
   int H, W, Cin, x_ld, x_coff;
   int Ho, Wo, Cout, y_ld, y_coff;
   int res_ld, res_coff;
-  int kh, kw, stride, pad;
+  int kh, kw, stride_h, stride_w, pad_h, pad_w;
   int K, Kp;
   int w_rows;                     // rows of the packed weight matrix (cout padded to a multiple of 128)
+  unsigned magic_howo, shift_howo, magic_wo, shift_wo; int HoWo_is_one;   // pixel index -> (image, row, column)
   unsigned magic_cin, magic_kw;   // floor(2^32 / d) + 1 for d = Cin, kw (set by launch_conv)
   int act, res_mode;
   int out_f32;          // write fp32 instead of the storage type
@@ -67,6 +68,7 @@ struct ResizeArgs {
   const size_t* pitches;          // device table of row pitches in bytes
   int src_h, src_w;
   void* dst; int dst_h, dst_w;
+  int dst_c;                      // 3, or 4: a zero fourth channel so that two neighbouring pixels form one 16-byte vector
   float scale[3], bias[3];
   int pad_value;
   int n; const int* n_dyn;

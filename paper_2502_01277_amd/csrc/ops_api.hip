@@ -21,7 +21,7 @@ octo_status octo_op_letterbox(const void* d_frame_ptrs, const void* d_pitches, i
     return OCTO_EINVAL;
   ResizeArgs a{};
   a.frames = (const uint8_t* const*)d_frame_ptrs; a.pitches = (const size_t*)d_pitches; a.src_h = src_h; a.src_w = src_w;
-  a.dst = d_dst; a.dst_h = dst_h; a.dst_w = dst_w; a.pad_value = pad_value; a.n = n; a.n_frames = n;
+  a.dst = d_dst; a.dst_h = dst_h; a.dst_w = dst_w; a.dst_c = 3; a.pad_value = pad_value; a.n = n; a.n_frames = n;
   for (int c = 0; c < 3; ++c) { a.scale[c] = scale3[c]; a.bias[c] = bias3[c]; }
   return from_hip(launch_letterbox(dtype, a, (hipStream_t)hip_stream));
 }
@@ -35,7 +35,7 @@ octo_status octo_op_crop_resize(const void* d_frame_ptrs, const void* d_pitches,
     return OCTO_EINVAL;
   ResizeArgs a{};
   a.frames = (const uint8_t* const*)d_frame_ptrs; a.pitches = (const size_t*)d_pitches; a.src_h = src_h; a.src_w = src_w;
-  a.dst = d_dst; a.dst_h = out_h; a.dst_w = out_w; a.n = cap; a.n_dyn = d_n_rois; a.rois = d_rois;
+  a.dst = d_dst; a.dst_h = out_h; a.dst_w = out_w; a.dst_c = 3; a.n = cap; a.n_dyn = d_n_rois; a.rois = d_rois;
   a.n_frames = n_frames;
   for (int c = 0; c < 3; ++c) { a.scale[c] = scale3[c]; a.bias[c] = bias3[c]; }
   return from_hip(launch_crop_resize(dtype, a, (hipStream_t)hip_stream));

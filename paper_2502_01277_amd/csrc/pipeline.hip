@@ -42,6 +42,11 @@ struct LayerPlan {
   std::vector<int> copy_inputs;   // concat: inputs that could not be aliased into the output buffer
   double flops = 0, bytes = 0;    // per item
   int kernel_id = KID_NONE;       // which kernel the last launch of this layer used
+  // First layer on a 3-channel input: run on the pixel-pair view of the 4-channel-padded input (two neighbouring
+  // pixels = one 16-byte vector of 8 values), i.e. as a conv with 8 input channels, kernel width pair_kw, horizontal
+  // stride 1 and horizontal padding pair_pad, on an image of half the width.
+  bool pair_view = false;
+  int pair_kw = 0, pair_pad = 0, pair_shift = 0;
 };
 
 struct TensorPlan {
@@ -59,6 +64,7 @@ struct ModelPlan {
   std::string name;
   std::vector<LayerPlan> layers;
   std::vector<TensorPlan> tensors;
+  bool input_c4 = false;   // tensor 0 is stored with a zero fourth channel
   int cap = 0;             // item capacity
   int bz = 0;              // current batch size (root: frames per batch)
   const int* n_dyn = nullptr;
@@ -269,6 +275,29 @@ void plan_activations(ModelPlan& m, bool keep_all) {
     }
   }
   for (int t = 0; t < nt; ++t) m.tensors[t].ld = m.tensors[m.tensors[t].root].c;
+  // own buffers whose channel count is not a multiple of 8 (detector heads) get a padded pitch so that rows stay
+  // 16-byte aligned; the pad elements are never written or read
+  for (int t = 1; t < nt; ++t)
+    if (m.tensors[t].root == t && !m.tensors[t].f32 && (m.tensors[t].c & 7)) {
+      bool has_members = false;
+      for (int q = 0; q < nt; ++q) has_members |= (q != t && m.tensors[q].root == t);
+      if (!has_members) m.tensors[t].ld = (m.tensors[t].c + 7) & ~7;
+    }
+  // 3-channel input read only by stride-2 convolutions: store it with 4 channels and use the pixel-pair view
+  m.input_c4 = m.d.in_c == 3 && (m.d.in_w % 2) == 0 && !is_output[0] && m.tensors[0].root == 0;
+  for (int i = 0; i < (int)m.layers.size() && m.input_c4; ++i)
+    for (int k = 0; k < m.layers[i].L.n_in; ++k)
+      if (m.layers[i].L.in[k] == 0 && !(m.layers[i].L.op == OCTO_CONV && k == 0 && m.layers[i].L.stride == 2)) m.input_c4 = false;
+  if (m.input_c4) {
+    m.tensors[0].ld = 4;
+    for (LayerPlan& lp : m.layers)
+      if (lp.L.op == OCTO_CONV && lp.L.in[0] == 0) {
+        lp.pair_view = true;
+        lp.pair_shift = lp.L.pad & 1;                       // makes the leftmost tap column even
+        lp.pair_kw = (lp.L.kw + lp.pair_shift + 1) / 2;
+        lp.pair_pad = (lp.L.pad + lp.pair_shift) / 2;
+      }
+  }
   // lifetimes of root buffers in layer steps: tensor t is written at step t-1 (input: -1)
   std::vector<int> birth(nt, 1 << 30), death(nt, -2);
   for (int t = 0; t < nt; ++t) {
@@ -286,7 +315,7 @@ void plan_activations(ModelPlan& m, bool keep_all) {
   const int es = dtype_size(m.d.dtype);
   auto root_bytes = [&](int r) {
     const TensorPlan& t = m.tensors[r];
-    size_t b = (size_t)m.cap * t.h * t.w * t.c * (t.f32 ? 4 : es);
+    size_t b = (size_t)m.cap * t.h * t.w * t.ld * (t.f32 ? 4 : es);
     return (b + 255) & ~(size_t)255;
   };
   struct Block { size_t off, size; };
@@ -340,15 +369,30 @@ octo_status pack_weights(octo_pipeline* p, ModelPlan& m, Arena& ar) {
   const int es = dtype_size(m.d.dtype);
   for (LayerPlan& lp : m.layers) {
     if (lp.L.op != OCTO_CONV && lp.L.op != OCTO_FC) continue;
-    lp.K = lp.L.kh * lp.L.kw * lp.cin;
-    const size_t elems = conv_packed_weight_elems(lp.L.cout, lp.L.kh, lp.L.kw, lp.cin, m.d.dtype, &lp.Kp, &lp.cout_pad);
+    const int pk_kw = lp.pair_view ? lp.pair_kw : lp.L.kw, pk_cin = lp.pair_view ? 8 : lp.cin;
+    lp.K = lp.L.kh * pk_kw * pk_cin;
+    const size_t elems = conv_packed_weight_elems(lp.L.cout, lp.L.kh, pk_kw, pk_cin, m.d.dtype, &lp.Kp, &lp.cout_pad);
     lp.d_weight = ar.alloc(elems * es + 512);   // slack: the conv prefetch may read a K step past the last row
     lp.d_bias = (float*)ar.alloc((size_t)lp.cout_pad * sizeof(float));
     if (!ar.base) continue;
     if (ar.failed) return OCTO_ENOMEM;
     std::vector<char> host(elems * es, 0);
-    for (int k = 0; k < lp.L.cout; ++k)
-      memcpy(host.data() + (size_t)k * lp.Kp * es, (const char*)lp.L.weight + (size_t)k * lp.K * es, (size_t)lp.K * es);
+    if (lp.pair_view) {
+      // w'[k][r][j][e]: e = 4*(pixel of the pair) + channel; window column s = 2j + e/4 - shift
+      const int kw = lp.L.kw, cin = lp.cin;
+      for (int k = 0; k < lp.L.cout; ++k)
+        for (int r = 0; r < lp.L.kh; ++r)
+          for (int j = 0; j < pk_kw; ++j)
+            for (int e = 0; e < 8; ++e) {
+              const int sc = 2 * j + e / 4 - lp.pair_shift, c = e % 4;
+              if (sc < 0 || sc >= kw || c >= cin) continue;
+              memcpy(host.data() + ((size_t)k * lp.Kp + ((size_t)r * pk_kw + j) * 8 + e) * es,
+                     (const char*)lp.L.weight + ((((size_t)k * lp.L.kh + r) * kw + sc) * cin + c) * es, es);
+            }
+    } else {
+      for (int k = 0; k < lp.L.cout; ++k)
+        memcpy(host.data() + (size_t)k * lp.Kp * es, (const char*)lp.L.weight + (size_t)k * lp.K * es, (size_t)lp.K * es);
+    }
     HIPCHK(p, hipMemcpy(lp.d_weight, host.data(), host.size(), hipMemcpyHostToDevice));
     std::vector<float> hb(lp.cout_pad, 0.f);
     memcpy(hb.data(), lp.L.bias, (size_t)lp.L.cout * sizeof(float));
@@ -370,7 +414,8 @@ hipError_t run_layer(octo_pipeline* p, ModelPlan& m, int i, int n, const int* n_
       a.x = x.ptr; a.w = lp.d_weight; a.bias = lp.d_bias; a.y = y.ptr; a.n_dyn = n_dyn; a.n = n;
       a.H = x.h; a.W = x.w; a.Cin = x.c; a.x_ld = x.ld; a.x_coff = x.coff;
       a.Ho = y.h; a.Wo = y.w; a.Cout = y.c; a.y_ld = y.ld; a.y_coff = y.coff;
-      a.kh = L.kh; a.kw = L.kw; a.stride = L.stride; a.pad = L.pad; a.K = lp.K; a.Kp = lp.Kp; a.w_rows = lp.cout_pad;
+      a.kh = L.kh; a.kw = L.kw; a.stride_h = a.stride_w = L.stride; a.pad_h = a.pad_w = L.pad; a.K = lp.K; a.Kp = lp.Kp; a.w_rows = lp.cout_pad;
+      if (lp.pair_view) { a.W = x.w / 2; a.Cin = 8; a.x_ld = 8; a.kw = lp.pair_kw; a.stride_w = 1; a.pad_w = lp.pair_pad; }
       a.act = L.act; a.res_mode = L.res_mode; a.out_f32 = m.tensors[i + 1].f32 ? 1 : 0;
       if (L.n_in == 2) { const TensorView r = view_of(m, L.in[1]); a.res = r.ptr; a.res_ld = r.ld; a.res_coff = r.coff; }
       return launch_conv(m.d.dtype, a, p->num_cu, s, &lp.kernel_id);
@@ -600,7 +645,7 @@ octo_status start_batch(octo_pipeline* p, hipStream_t s, int* launched) {
   if (ev) HIPCHK(p, hipEventRecord(ev[0], s));
   ResizeArgs ra{};
   ra.frames = p->d_frames[B.slot]; ra.pitches = p->d_pitch[B.slot]; ra.src_h = p->d.src_h; ra.src_w = p->d.src_w;
-  ra.dst = view_of(root, 0).ptr; ra.dst_h = root.d.in_h; ra.dst_w = root.d.in_w;
+  ra.dst = view_of(root, 0).ptr; ra.dst_h = root.d.in_h; ra.dst_w = root.d.in_w; ra.dst_c = root.input_c4 ? 4 : 3;
   for (int c = 0; c < 3; ++c) { ra.scale[c] = root.d.norm_scale[c]; ra.bias[c] = root.d.norm_bias[c]; }
   ra.pad_value = root.d.pad_value; ra.n = n; ra.n_frames = n;
   HIPCHK(p, launch_letterbox(root.d.dtype, ra, s));
@@ -633,7 +678,7 @@ octo_status run_child(octo_pipeline* p, Batch& B, int e, hipStream_t s, bool wai
   if (wait_det) HIPCHK(p, hipStreamWaitEvent(s, p->ev_det, 0));
   ResizeArgs ra{};
   ra.frames = p->d_frames[B.slot]; ra.pitches = p->d_pitch[B.slot]; ra.src_h = p->d.src_h; ra.src_w = p->d.src_w;
-  ra.dst = view_of(c, 0).ptr; ra.dst_h = c.d.in_h; ra.dst_w = c.d.in_w;
+  ra.dst = view_of(c, 0).ptr; ra.dst_h = c.d.in_h; ra.dst_w = c.d.in_w; ra.dst_c = c.input_c4 ? 4 : 3;
   for (int k = 0; k < 3; ++k) { ra.scale[k] = c.d.norm_scale[k]; ra.bias[k] = c.d.norm_bias[k]; }
   ra.n = c.cap; ra.n_dyn = c.n_dyn; ra.rois = p->rois[e]; ra.n_frames = B.n;
   HIPCHK(p, launch_crop_resize(c.d.dtype, ra, s));
@@ -974,7 +1019,13 @@ octo_status octo_debug_run_model(octo_pipeline* p, int32_t model, const void* d_
   hipStream_t s = (hipStream_t)hip_stream;
   const TensorPlan& t0 = m.tensors[0];
   const size_t bytes = (size_t)n * t0.h * t0.w * t0.c * dtype_size(m.d.dtype);
-  HIPCHK(p, hipMemcpyAsync(view_of(m, 0).ptr, d_input, bytes, hipMemcpyDeviceToDevice, s));
+  if (m.input_c4) {
+    HIPCHK(p, hipMemsetAsync(view_of(m, 0).ptr, 0, (size_t)n * t0.h * t0.w * 4 * dtype_size(m.d.dtype), s));
+    PoolArgs ca{d_input, view_of(m, 0).ptr, nullptr, n, t0.h, t0.w, 3, 3, 0, t0.h, t0.w, 4, 0, 1, 1, 0};
+    HIPCHK(p, launch_copy_channels(m.d.dtype, ca, s));
+  } else {
+    HIPCHK(p, hipMemcpyAsync(view_of(m, 0).ptr, d_input, bytes, hipMemcpyDeviceToDevice, s));
+  }
   HIPCHK(p, run_layers(p, m, n, nullptr, s));
   if (m.d.kind == OCTO_DETECTOR) {
     if (m.flags) HIPCHK(p, launch_fill_i32(m.flags, 0, m.cap, s));

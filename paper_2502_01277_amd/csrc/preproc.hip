@@ -12,12 +12,17 @@ namespace octo {
 
 __device__ __forceinline__ int clampi(int v, int lo, int hi) { return v < lo ? lo : (v > hi ? hi : v); }
 
-template <typename T, int N> struct OutVec { alignas(sizeof(T) * 4) T v[N]; };
-
-template <typename T, int PX>
+// PX pixels, contiguous; C4: every pixel is written as 4 values (RGB + 0)
+template <typename T, int PX, bool C4>
 __device__ __forceinline__ void store_pixels(T* dst, const float* v) {
-  // PX pixels x 3 channels, contiguous
-  if (PX == 4) {
+  if (C4) {
+    typedef T t4 __attribute__((ext_vector_type(4)));
+#pragma unroll
+    for (int p = 0; p < PX; ++p) {
+      const t4 o = {(T)v[3 * p], (T)v[3 * p + 1], (T)v[3 * p + 2], (T)0.0f};
+      *(t4*)(dst + 4 * p) = o;
+    }
+  } else if (PX == 4) {
     alignas(16) T o[12];
 #pragma unroll
     for (int i = 0; i < 12; ++i) o[i] = (T)v[i];
@@ -48,7 +53,7 @@ __device__ __forceinline__ void bilinear_rgb(const uint8_t* row_a, const uint8_t
 
 struct LetterboxGeom { int nw, nh, left, top; };
 
-template <typename T, int PX>
+template <typename T, int PX, bool C4>
 __global__ void letterbox_kernel(const ResizeArgs a, const LetterboxGeom g) {
   const int wq = a.dst_w / PX;
   int n_items = a.n;
@@ -87,11 +92,11 @@ __global__ void letterbox_kernel(const ResizeArgs a, const LetterboxGeom g) {
         for (int c = 0; c < 3; ++c) v[3 * px + c] = (float)a.pad_value * a.scale[c] + a.bias[c];
       }
     }
-    store_pixels<T, PX>(dst + (((size_t)img * a.dst_h + y) * a.dst_w + (size_t)xq * PX) * 3, v);
+    store_pixels<T, PX, C4>(dst + (((size_t)img * a.dst_h + y) * a.dst_w + (size_t)xq * PX) * (C4 ? 4 : 3), v);
   }
 }
 
-template <typename T, int PX>
+template <typename T, int PX, bool C4>
 __global__ void crop_resize_kernel(const ResizeArgs a) {
   const int wq = a.dst_w / PX;
   int n_items = a.n;
@@ -121,7 +126,7 @@ __global__ void crop_resize_kernel(const ResizeArgs a) {
       const int xa = clampi((int)x0f, 0, a.src_w - 1), xb = clampi((int)x0f + 1, 0, a.src_w - 1);
       bilinear_rgb(base + (size_t)ya * pitch, base + (size_t)yb * pitch, xa, xb, fx, fy, a.scale, a.bias, v + 3 * px);
     }
-    store_pixels<T, PX>(dst + (((size_t)roi * a.dst_h + y) * a.dst_w + (size_t)xq * PX) * 3, v);
+    store_pixels<T, PX, C4>(dst + (((size_t)roi * a.dst_h + y) * a.dst_w + (size_t)xq * PX) * (C4 ? 4 : 3), v);
   }
 }
 
@@ -153,24 +158,33 @@ void letterbox_geometry(int src_h, int src_w, int dst_h, int dst_w, int* nw, int
 
 template <typename T> static hipError_t letterbox_t(const ResizeArgs& a, hipStream_t s) {
   LetterboxGeom g = letterbox_geom(a.src_h, a.src_w, a.dst_h, a.dst_w);
-  if (a.dst_w % 4 == 0 && ((uintptr_t)a.dst & 15) == 0) {
-    hipLaunchKernelGGL((letterbox_kernel<T, 4>), dim3(resize_grid((long long)a.n * a.dst_h * (a.dst_w / 4))), dim3(256), 0, s, a, g);
+  if (a.dst_c == 4 && ((uintptr_t)a.dst & 15) == 0 && a.dst_w % 4 == 0) {
+    hipLaunchKernelGGL((letterbox_kernel<T, 4, true>), dim3(resize_grid((long long)a.n * a.dst_h * (a.dst_w / 4))), dim3(256), 0, s, a, g);
+  } else if (a.dst_c == 4) {
+    hipLaunchKernelGGL((letterbox_kernel<T, 1, true>), dim3(resize_grid((long long)a.n * a.dst_h * a.dst_w)), dim3(256), 0, s, a, g);
+  } else if (a.dst_w % 4 == 0 && ((uintptr_t)a.dst & 15) == 0) {
+    hipLaunchKernelGGL((letterbox_kernel<T, 4, false>), dim3(resize_grid((long long)a.n * a.dst_h * (a.dst_w / 4))), dim3(256), 0, s, a, g);
   } else {
-    hipLaunchKernelGGL((letterbox_kernel<T, 1>), dim3(resize_grid((long long)a.n * a.dst_h * a.dst_w)), dim3(256), 0, s, a, g);
+    hipLaunchKernelGGL((letterbox_kernel<T, 1, false>), dim3(resize_grid((long long)a.n * a.dst_h * a.dst_w)), dim3(256), 0, s, a, g);
   }
   return hipGetLastError();
 }
 template <typename T> static hipError_t crop_t(const ResizeArgs& a, hipStream_t s) {
-  if (a.dst_w % 4 == 0 && ((uintptr_t)a.dst & 15) == 0) {
-    hipLaunchKernelGGL((crop_resize_kernel<T, 4>), dim3(resize_grid((long long)a.n * a.dst_h * (a.dst_w / 4))), dim3(256), 0, s, a);
+  if (a.dst_c == 4 && ((uintptr_t)a.dst & 15) == 0 && a.dst_w % 4 == 0) {
+    hipLaunchKernelGGL((crop_resize_kernel<T, 4, true>), dim3(resize_grid((long long)a.n * a.dst_h * (a.dst_w / 4))), dim3(256), 0, s, a);
+  } else if (a.dst_c == 4) {
+    hipLaunchKernelGGL((crop_resize_kernel<T, 1, true>), dim3(resize_grid((long long)a.n * a.dst_h * a.dst_w)), dim3(256), 0, s, a);
+  } else if (a.dst_w % 4 == 0 && ((uintptr_t)a.dst & 15) == 0) {
+    hipLaunchKernelGGL((crop_resize_kernel<T, 4, false>), dim3(resize_grid((long long)a.n * a.dst_h * (a.dst_w / 4))), dim3(256), 0, s, a);
   } else {
-    hipLaunchKernelGGL((crop_resize_kernel<T, 1>), dim3(resize_grid((long long)a.n * a.dst_h * a.dst_w)), dim3(256), 0, s, a);
+    hipLaunchKernelGGL((crop_resize_kernel<T, 1, false>), dim3(resize_grid((long long)a.n * a.dst_h * a.dst_w)), dim3(256), 0, s, a);
   }
   return hipGetLastError();
 }
 
 hipError_t launch_letterbox(int dtype, const ResizeArgs& a, hipStream_t s) {
   if (a.n <= 0) return hipSuccess;
+  if (a.dst_c != 3 && a.dst_c != 4) return hipErrorInvalidValue;
   switch (dtype) {
     case OCTO_F32: return letterbox_t<float>(a, s);
     case OCTO_F16: return letterbox_t<_Float16>(a, s);
@@ -180,6 +194,7 @@ hipError_t launch_letterbox(int dtype, const ResizeArgs& a, hipStream_t s) {
 }
 hipError_t launch_crop_resize(int dtype, const ResizeArgs& a, hipStream_t s) {
   if (a.n <= 0) return hipSuccess;
+  if (a.dst_c != 3 && a.dst_c != 4) return hipErrorInvalidValue;
   switch (dtype) {
     case OCTO_F32: return crop_t<float>(a, s);
     case OCTO_F16: return crop_t<_Float16>(a, s);
