@@ -37,7 +37,7 @@ def make_workload(name: str):
         rng = np.random.default_rng(zoo.SEED0 + 5)
         counts = synth.counts_pareto(rng, 32)
         scene = synth.make_scene(rng, 32, 2160, 3840, counts, 48, 720, log_uniform=True)
-        heads = synth.planted_heads(rng, spec.models[0], scene, 2160, 3840, n_clutter=1000)
+        heads = synth.planted_heads(rng, spec.models[0], scene, 2160, 3840, n_clutter=1100)
         desc = "high-resolution cascade: 32x3840x2160 frames, CSP-m detector 1280 bf16, planted heads Pareto(1.5), ResNet-18-shaped classifier"
     elif name == "tiny":
         spec = zoo.tiny_cascade()

@@ -266,11 +266,12 @@ octo_status octo_op_nms(const octo_cand* d_top, const int32_t* d_top_count, int3
 size_t octo_op_nms_scratch_bytes(int32_t n, int32_t k_cap);
 /* ROI compaction for one edge: kept boxes with class bit set, in (item, rank) order, converted to source pixels
  * (letterbox undone for a src_h x src_w frame letterboxed into in_h x in_w) and clamped.
- * d_n_rois[0] = count (clamped to cap); d_boxes [n][max_det] receives every kept box in source pixels. */
+ * d_n_rois[0] = count (clamped to cap); d_roi_of [n][max_det] = ROI id of each kept box or -1; d_item_counts [n] is
+ * scratch; d_boxes [n][max_det] (may be NULL) receives every kept box in source pixels; d_flags [n] may be NULL. */
 octo_status octo_op_compact(const octo_cand* d_top, int32_t k_cap, const int32_t* d_keep, const int32_t* d_n_keep, int32_t max_det,
                             int32_t n, int32_t src_h, int32_t src_w, int32_t in_h, int32_t in_w, const uint64_t* class_mask2,
-                            octo_roi* d_rois, int32_t* d_n_rois, int32_t cap, int32_t* d_roi_of, octo_box* d_boxes, int32_t* d_flags,
-                            void* hip_stream);
+                            octo_roi* d_rois, int32_t* d_n_rois, int32_t cap, int32_t* d_roi_of, int32_t* d_item_counts, octo_box* d_boxes,
+                            int32_t* d_flags, void* hip_stream);
 
 #ifdef __cplusplus
 }

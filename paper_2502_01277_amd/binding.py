@@ -140,7 +140,7 @@ def lib() -> C.CDLL:
         L.octo_op_topk.argtypes = [vp, vp, i32, i32, i32, vp, vp, i32, vp]
         L.octo_op_nms.argtypes = [vp, vp, i32, i32, f32, i32, vp, vp, vp, vp]
         L.octo_op_nms_scratch_bytes.argtypes = [i32, i32]
-        L.octo_op_compact.argtypes = [vp, i32, vp, vp, i32, i32, i32, i32, i32, i32, vp, vp, vp, i32, vp, vp, vp, vp]
+        L.octo_op_compact.argtypes = [vp, i32, vp, vp, i32, i32, i32, i32, i32, i32, vp, vp, vp, i32, vp, vp, vp, vp, vp]
         _lib = L
     return _lib
 
@@ -488,10 +488,11 @@ def op_compact(top, keep, n_keep, src_hw, in_hw, class_mask: int, cap: int, stre
     roi_of = t.full((n, max_det), -1, dtype=t.int32, device=dev)
     boxes = t.zeros((n, max_det, 32), dtype=t.uint8, device=dev)
     flags = t.zeros(n, dtype=t.int32, device=dev)
+    item_counts = t.zeros(n, dtype=t.int32, device=dev)
     cm = (C.c_uint64 * 2)(class_mask & ((1 << 64) - 1), (class_mask >> 64) & ((1 << 64) - 1))
     _st(lib().octo_op_compact(top.data_ptr(), k_cap, keep.data_ptr(), n_keep.data_ptr(), max_det, n, src_hw[0], src_hw[1],
                               in_hw[0], in_hw[1], cm, rois.data_ptr(), n_roi.data_ptr(), cap, roi_of.data_ptr(),
-                              boxes.data_ptr(), flags.data_ptr(), _stream_ptr(stream)))
+                              item_counts.data_ptr(), boxes.data_ptr(), flags.data_ptr(), _stream_ptr(stream)))
     nr = int(n_roi.cpu()[0])
     r = rois.cpu().numpy().reshape(-1).view(ROI_DTYPE)[:nr].copy()
     b = boxes.cpu().numpy().reshape(n, max_det * 32).view(BOX_DTYPE)

@@ -85,13 +85,15 @@ struct DecodeArgs {
   int n_levels; int gh[3], gw[3], stride[3]; float anchors[3][3][2];
   int n_anchors, n_classes; float score_thr;
   int n; const int* n_dyn;
-  octo_cand* cand; int* count; int cap;      // per item: cand[item*cap ...], count[item]
+  octo_cand* cand; int* count; int cap;      // per item: cand[item*cap ...], count[item*count_stride]
+  int count_stride;                          // >= 1; 32 puts every item's counter on its own 128-byte line
   int* overflow;
 };
 hipError_t launch_decode(int dtype, const DecodeArgs& a, hipStream_t s);
 
 struct TopkArgs {
   const octo_cand* in; const int* in_count; int in_cap;
+  int in_count_stride;
   octo_cand* out; int* out_count; int k;     // out stride = k_cap
   int k_cap;
   int n; const int* n_dyn;
@@ -116,7 +118,8 @@ struct CompactArgs {
   float left, top_pad, rx, ry, src_w, src_h;
   int n_edges; uint64_t class_mask[OCTO_MAX_EDGES][2];
   octo_roi* rois[OCTO_MAX_EDGES]; int* n_roi[OCTO_MAX_EDGES]; int roi_cap[OCTO_MAX_EDGES];
-  int* roi_of[OCTO_MAX_EDGES];             // [n][max_det] -> roi id or -1
+  int* roi_of[OCTO_MAX_EDGES];             // [n][max_det] -> roi id or -1 (required)
+  int* roi_cnt[OCTO_MAX_EDGES];            // [n] scratch: ROIs per item (required)
   octo_box* boxes;                         // [n][max_det] final boxes in source pixels
   int* flags;                              // [n]
 };

@@ -56,7 +56,7 @@ octo_status octo_op_decode(const octo_model_desc* model, const void* const* d_he
     memcpy(a.anchors[l], model->anchors[l], sizeof a.anchors[l]);
   }
   a.n_anchors = model->n_anchors; a.n_classes = model->n_classes; a.score_thr = model->score_thr;
-  a.n = n; a.cand = d_cand; a.count = d_count; a.cap = cap;
+  a.n = n; a.cand = d_cand; a.count = d_count; a.cap = cap; a.count_stride = 1;
   hipStream_t s = (hipStream_t)hip_stream;
   hipError_t e = launch_fill_i32(d_count, 0, n, s);
   if (e != hipSuccess) return from_hip(e);
@@ -66,7 +66,7 @@ octo_status octo_op_decode(const octo_model_desc* model, const void* const* d_he
 octo_status octo_op_topk(const octo_cand* d_in, const int32_t* d_in_count, int32_t in_cap, int32_t n, int32_t k,
                          octo_cand* d_out, int32_t* d_out_count, int32_t k_cap, void* hip_stream) {
   if (!d_in || !d_in_count || !d_out || !d_out_count || n < 0 || k < 1 || k > k_cap || in_cap < 1) return OCTO_EINVAL;
-  TopkArgs a{d_in, d_in_count, in_cap, d_out, d_out_count, k, k_cap, n, nullptr};
+  TopkArgs a{d_in, d_in_count, in_cap, 1, d_out, d_out_count, k, k_cap, n, nullptr};
   return from_hip(launch_topk(a, (hipStream_t)hip_stream));
 }
 
@@ -83,9 +83,9 @@ octo_status octo_op_nms(const octo_cand* d_top, const int32_t* d_top_count, int3
 
 octo_status octo_op_compact(const octo_cand* d_top, int32_t k_cap, const int32_t* d_keep, const int32_t* d_n_keep, int32_t max_det,
                             int32_t n, int32_t src_h, int32_t src_w, int32_t in_h, int32_t in_w, const uint64_t* class_mask2,
-                            octo_roi* d_rois, int32_t* d_n_rois, int32_t cap, int32_t* d_roi_of, octo_box* d_boxes, int32_t* d_flags,
+                            octo_roi* d_rois, int32_t* d_n_rois, int32_t cap, int32_t* d_roi_of, int32_t* d_item_counts, octo_box* d_boxes, int32_t* d_flags,
                             void* hip_stream) {
-  if (!d_top || !d_keep || !d_n_keep || !class_mask2 || !d_rois || !d_n_rois || n < 0 || cap < 0 || max_det < 1 || k_cap < 1 ||
+  if (!d_top || !d_keep || !d_n_keep || !class_mask2 || !d_rois || !d_n_rois || !d_roi_of || !d_item_counts || n < 0 || cap < 0 || max_det < 1 || k_cap < 1 ||
       src_h <= 0 || src_w <= 0 || in_h <= 0 || in_w <= 0)
     return OCTO_EINVAL;
   int nw, nh, left, top;
@@ -95,7 +95,7 @@ octo_status octo_op_compact(const octo_cand* d_top, int32_t k_cap, const int32_t
   a.left = (float)left; a.top_pad = (float)top; a.rx = (float)nw / (float)src_w; a.ry = (float)nh / (float)src_h;
   a.src_w = (float)src_w; a.src_h = (float)src_h;
   a.n_edges = 1; a.class_mask[0][0] = class_mask2[0]; a.class_mask[0][1] = class_mask2[1];
-  a.rois[0] = d_rois; a.n_roi[0] = d_n_rois; a.roi_cap[0] = cap; a.roi_of[0] = d_roi_of;
+  a.rois[0] = d_rois; a.n_roi[0] = d_n_rois; a.roi_cap[0] = cap; a.roi_of[0] = d_roi_of; a.roi_cnt[0] = d_item_counts;
   a.boxes = d_boxes; a.flags = d_flags;
   return from_hip(launch_compact(a, (hipStream_t)hip_stream));
 }

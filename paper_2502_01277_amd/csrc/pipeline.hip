@@ -99,6 +99,7 @@ struct Batch {
 struct QueuedFrame { const void* ptr; size_t pitch; double arrival; int64_t id; };
 
 constexpr int RING = 4;
+constexpr int CNT_STRIDE = 32;   // candidate counters sit 128 bytes apart: same-line atomics serialise in L2
 
 }  // namespace
 
@@ -111,6 +112,7 @@ struct octo_pipeline {
   int max_frames = 0, max_queue = 0;
   // per edge
   octo_roi* rois[OCTO_MAX_EDGES]{}; int* n_roi[OCTO_MAX_EDGES]{}; int roi_cap[OCTO_MAX_EDGES]{}; int* roi_of[OCTO_MAX_EDGES]{};
+  int* roi_cnt[OCTO_MAX_EDGES]{};
   // result block (device) and its pinned host mirrors
   char* d_result = nullptr; size_t result_bytes = 0;
   size_t off_nkeep = 0, off_flags = 0, off_nroi = 0, off_boxes = 0;
@@ -471,7 +473,7 @@ hipError_t run_layers(octo_pipeline* p, ModelPlan& m, int n, const int* n_dyn, h
 
 // decode -> top-k -> NMS of a detector (root or child) for n items
 hipError_t run_detect_tail(octo_pipeline* p, ModelPlan& m, int n, const int* n_dyn, hipStream_t s, hipEvent_t* evs) {
-  hipError_t e = launch_fill_i32(m.cand_count, 0, m.cap, s);
+  hipError_t e = launch_fill_i32(m.cand_count, 0, m.cap * CNT_STRIDE, s);
   if (e != hipSuccess) return e;
   DecodeArgs da{};
   da.n_levels = m.d.n_outputs;
@@ -483,10 +485,10 @@ hipError_t run_detect_tail(octo_pipeline* p, ModelPlan& m, int n, const int* n_d
     memcpy(da.anchors[l], m.d.anchors[l], sizeof da.anchors[l]);
   }
   da.n_anchors = m.d.n_anchors; da.n_classes = m.d.n_classes; da.score_thr = m.d.score_thr;
-  da.n = n; da.n_dyn = n_dyn; da.cand = m.cand; da.count = m.cand_count; da.cap = m.n_cand; da.overflow = m.flags;
+  da.n = n; da.n_dyn = n_dyn; da.cand = m.cand; da.count = m.cand_count; da.cap = m.n_cand; da.count_stride = CNT_STRIDE; da.overflow = m.flags;
   if ((e = launch_decode(m.d.dtype, da, s)) != hipSuccess) return e;
   if (evs) hipEventRecord(evs[0], s);
-  TopkArgs ta{m.cand, m.cand_count, m.n_cand, m.top, m.top_count, std::min(m.d.topk, m.n_cand), m.k_cap, n, n_dyn};
+  TopkArgs ta{m.cand, m.cand_count, m.n_cand, CNT_STRIDE, m.top, m.top_count, std::min(m.d.topk, m.n_cand), m.k_cap, n, n_dyn};
   if ((e = launch_topk(ta, s)) != hipSuccess) return e;
   if (evs) hipEventRecord(evs[1], s);
   NmsArgs na{m.top, m.top_count, m.k_cap, m.d.iou_thr, m.d.max_det, m.mask, m.keep, m.n_keep, n, n_dyn};
@@ -545,7 +547,7 @@ octo_status build(octo_pipeline* p, const octo_pipeline_desc* desc, Arena& ar) {
     m.act_base = (char*)ar.alloc(m.act_bytes);
     if (m.d.kind == OCTO_DETECTOR) {
       m.cand = (octo_cand*)ar.alloc((size_t)m.cap * m.n_cand * sizeof(octo_cand));
-      m.cand_count = (int*)ar.alloc((size_t)m.cap * sizeof(int));
+      m.cand_count = (int*)ar.alloc((size_t)m.cap * CNT_STRIDE * sizeof(int));
       m.top = (octo_cand*)ar.alloc((size_t)m.cap * m.k_cap * sizeof(octo_cand));
       m.top_count = (int*)ar.alloc((size_t)m.cap * sizeof(int));
       m.mask = (unsigned long long*)ar.alloc(nms_mask_bytes(m.cap, m.k_cap));
@@ -571,6 +573,7 @@ octo_status build(octo_pipeline* p, const octo_pipeline_desc* desc, Arena& ar) {
     p->roi_cap[e] = c.cap;
     p->rois[e] = (octo_roi*)ar.alloc((size_t)c.cap * sizeof(octo_roi));
     p->roi_of[e] = (int*)ar.alloc(mf * root.d.max_det * sizeof(int));
+    p->roi_cnt[e] = (int*)ar.alloc(mf * sizeof(int));
   }
   for (int r = 0; r < RING; ++r) {
     p->d_frames[r] = (const uint8_t**)ar.alloc(mf * sizeof(void*));
@@ -662,7 +665,7 @@ octo_status start_batch(octo_pipeline* p, hipStream_t s, int* launched) {
   ca.n_edges = (int)p->edges.size();
   for (int e = 0; e < ca.n_edges; ++e) {
     ca.class_mask[e][0] = p->edges[e].class_mask[0]; ca.class_mask[e][1] = p->edges[e].class_mask[1];
-    ca.rois[e] = p->rois[e]; ca.n_roi[e] = p->n_roi[e]; ca.roi_cap[e] = p->roi_cap[e]; ca.roi_of[e] = p->roi_of[e];
+    ca.rois[e] = p->rois[e]; ca.n_roi[e] = p->n_roi[e]; ca.roi_cap[e] = p->roi_cap[e]; ca.roi_of[e] = p->roi_of[e]; ca.roi_cnt[e] = p->roi_cnt[e];
   }
   ca.boxes = (octo_box*)(p->d_result + p->off_boxes); ca.flags = root.flags;
   HIPCHK(p, launch_compact(ca, s));
@@ -1045,7 +1048,7 @@ octo_status octo_debug_get_detections(octo_pipeline* p, int32_t model, int32_t i
   if (item < 0 || item >= m.cap) return fail(p, OCTO_EINVAL, "bad item");
   HIPCHK(p, hipDeviceSynchronize());
   int cc = 0, nt = 0, nk = 0;
-  HIPCHK(p, hipMemcpy(&cc, m.cand_count + item, sizeof(int), hipMemcpyDeviceToHost));
+  HIPCHK(p, hipMemcpy(&cc, m.cand_count + (size_t)item * CNT_STRIDE, sizeof(int), hipMemcpyDeviceToHost));
   HIPCHK(p, hipMemcpy(&nt, m.top_count + item, sizeof(int), hipMemcpyDeviceToHost));
   HIPCHK(p, hipMemcpy(&nk, m.n_keep + item, sizeof(int), hipMemcpyDeviceToHost));
   nk = std::min(nk, m.d.max_det);

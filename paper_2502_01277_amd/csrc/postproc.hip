@@ -72,7 +72,7 @@ __global__ void decode_kernel(const DecodeArgs a, int cand_per_item) {
     if (m) {
       int base = 0;
       const int leader = __ffsll((long long)m) - 1;
-      if (lane == leader) base = atomicAdd(&a.count[item], __popcll(m));
+      if (lane == leader) base = atomicAdd(&a.count[(size_t)item * a.count_stride], __popcll(m));
       base = __shfl(base, leader);
       if (keep) {
         const int slot = base + __popcll(m & ((1ull << lane) - 1ull));
@@ -83,19 +83,184 @@ __global__ void decode_kernel(const DecodeArgs a, int cand_per_item) {
   }
 }
 
-hipError_t launch_decode(int dtype, const DecodeArgs& a, hipStream_t s) {
-  if (a.n <= 0) return hipSuccess;
-  int cand = 0;
-  for (int l = 0; l < a.n_levels; ++l) cand += a.gh[l] * a.gw[l] * a.n_anchors;
-  int chunks = (cand + 255) / 256;
-  dim3 grid(chunks > 1024 ? 1024 : chunks, a.n);
-  switch (dtype) {
-    case OCTO_F32: hipLaunchKernelGGL(decode_kernel<float>, grid, dim3(256), 0, s, a, cand); break;
-    case OCTO_F16: hipLaunchKernelGGL(decode_kernel<_Float16>, grid, dim3(256), 0, s, a, cand); break;
-    case OCTO_BF16: hipLaunchKernelGGL(decode_kernel<__bf16>, grid, dim3(256), 0, s, a, cand); break;
-    default: return hipErrorInvalidValue;
+// Streaming variant: a persistent workgroup walks over chunks of CH consecutive candidates of one level.  The
+// contiguous head region of a chunk is fetched with 16-byte buffer loads (every byte of the head is read exactly
+// once, fully coalesced) into registers while the previous chunk is being decoded out of LDS, so the memory
+// pipeline never drains; each lane then decodes one candidate.  Same arithmetic as decode_kernel.
+constexpr int DEC_LDS_BYTES = 48 * 1024;
+
+struct DecChunk {
+  int l, level_off, c_first, c_last, cell_lo, item, shift, nvec;
+};
+
+template <typename T, int CH>
+__global__ __launch_bounds__(CH) void decode_stream_kernel(const DecodeArgs a, int blocks_per_item) {
+  typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+  __shared__ u32x4 lds[DEC_LDS_BYTES / 16];
+  __shared__ int s_cnt, s_base;
+  constexpr int ES = (int)sizeof(T);
+  constexpr int VPT = (DEC_LDS_BYTES / 16 + CH - 1) / CH;      // vectors per lane, upper bound
+  const int n_items = dyn_n(a.n_dyn, a.n);
+  const int total_work = n_items * blocks_per_item;
+  const int A = a.n_anchors, no = 5 + a.n_classes;
+  const int lane = threadIdx.x & 63;
+  const float z_min = a.score_thr <= 0.0f ? -INFINITY : (a.score_thr >= 1.0f ? INFINITY : __logf(a.score_thr / (1.0f - a.score_thr)) - 0.01f);
+  u32x4 regs[VPT];
+
+  // chunk geometry + issue of its loads.  The region is fetched through a buffer descriptor that ends where the
+  // tensor (or the region) ends: vectors past the end read as zeros, so the copy needs no per-vector bounds logic.
+  auto fetch = [&](int work, DecChunk& ck) {
+    ck.item = work / blocks_per_item;
+    int rem = work - ck.item * blocks_per_item;
+    ck.l = 0; ck.level_off = 0;
+    while (true) {
+      const int nb = (a.gh[ck.l] * a.gw[ck.l] * A + CH - 1) / CH;
+      if (rem < nb) break;
+      rem -= nb; ck.level_off += a.gh[ck.l] * a.gw[ck.l] * A; ++ck.l;
+    }
+    const int ld = a.head_ld[ck.l];
+    const int cells = a.gh[ck.l] * a.gw[ck.l];
+    const int cand_l = cells * A;
+    ck.c_first = rem * CH;
+    ck.c_last = (ck.c_first + CH < cand_l ? ck.c_first + CH : cand_l) - 1;
+    ck.cell_lo = ck.c_first / A;
+    const int cell_hi = ck.c_last / A;
+    const long long byte_lo = ((long long)ck.item * cells + ck.cell_lo) * ld * ES;
+    const long long byte_hi = (((long long)ck.item * cells + cell_hi) * ld + (long long)A * no) * ES;
+    const long long total = (long long)a.n * cells * ld * ES;
+    const long long al_lo = byte_lo & ~15LL;
+    ck.shift = (int)(byte_lo - al_lo);
+    ck.nvec = (int)((byte_hi - al_lo + 15) / 16);
+    const long long avail = total - al_lo < byte_hi - al_lo ? total - al_lo : byte_hi - al_lo;
+    const __amdgpu_buffer_rsrc_t rsrc =
+        __builtin_amdgcn_make_buffer_rsrc((void*)((const char*)a.head[ck.l] + al_lo), 0, (int)avail, 0x00020000);
+#pragma unroll
+    for (int q = 0; q < VPT; ++q) regs[q] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, (threadIdx.x + q * CH) * 16, 0, 0);
+  };
+
+  DecChunk nxt{};
+  int work = blockIdx.x;
+  if (work < total_work) fetch(work, nxt);
+  while (work < total_work) {
+    const DecChunk ck = nxt;
+#pragma unroll
+    for (int q = 0; q < VPT; ++q) {
+      const int v = threadIdx.x + q * CH;
+      if (v < ck.nvec) lds[v] = regs[q];
+    }
+    if (threadIdx.x == 0) s_cnt = 0;
+    __syncthreads();
+    const int next = work + gridDim.x;
+    if (next < total_work) fetch(next, nxt);           // in flight while this chunk is decoded
+
+    const int l = ck.l, ld = a.head_ld[l];
+    const int c = ck.c_first + threadIdx.x;
+    bool keep = false;
+    octo_cand out;
+    const int cell = c / A, an = c - cell * A;
+    const int t_off = ck.shift + ((cell - ck.cell_lo) * ld + an * no) * ES;    // this lane's logits in LDS
+    const T* t = (const T*)((const char*)lds + t_off);
+    // objectness logits far below logit(threshold) cannot pass; skipping their sigmoid keeps the common path to one
+    // LDS read and one compare (the margin covers fp32 rounding, so the kept set is unchanged)
+    float sobj = 0.0f;
+    if (c <= ck.c_last) { const float z = (float)t[4]; if (z > z_min) sobj = sigmoidf(z); }
+    // score = sobj * s(cls) <= sobj, so only lanes whose objectness passes need their class scanned.  Such lanes are
+    // rare; the wavefront scans the classes of each of them together (lane j looks at classes j and j + 64) instead
+    // of one lane walking all classes alone.
+    const bool pass_obj = c <= ck.c_last && sobj > a.score_thr;
+    unsigned long long pend = __ballot(pass_obj);
+    float best = 0.0f;
+    int cls = 0;
+    while (pend) {
+      const int src = __ffsll((long long)pend) - 1;
+      pend &= pend - 1;
+      const T* ts = (const T*)((const char*)lds + __shfl(t_off, src));
+      float v = lane < a.n_classes ? (float)ts[5 + lane] : -INFINITY;
+      int vi = lane;
+      if (lane + 64 < a.n_classes) { const float v2 = (float)ts[5 + lane + 64]; if (v2 > v) { v = v2; vi = lane + 64; } }
+#pragma unroll
+      for (int off = 32; off > 0; off >>= 1) {
+        const float ov = __shfl_xor(v, off);
+        const int oi = __shfl_xor(vi, off);
+        if (ov > v || (ov == v && oi < vi)) { v = ov; vi = oi; }
+      }
+      if (lane == src) { best = v; cls = vi; }
+    }
+    if (pass_obj) {
+      const float score = __fmul_rn(sobj, sigmoidf(best));
+      if (score > a.score_thr) {
+        const int gy = cell / a.gw[l], gx = cell - gy * a.gw[l];
+        const float st = (float)a.stride[l];
+        const float sx = sigmoidf((float)t[0]), sy = sigmoidf((float)t[1]);
+        const float sw = sigmoidf((float)t[2]), sh = sigmoidf((float)t[3]);
+        const float cx = __fmul_rn(__fadd_rn(__fsub_rn(__fmul_rn(2.0f, sx), 0.5f), (float)gx), st);
+        const float cy = __fmul_rn(__fadd_rn(__fsub_rn(__fmul_rn(2.0f, sy), 0.5f), (float)gy), st);
+        const float tw = __fmul_rn(2.0f, sw), th = __fmul_rn(2.0f, sh);
+        const float w = __fmul_rn(__fmul_rn(tw, tw), a.anchors[l][an][0]);
+        const float h = __fmul_rn(__fmul_rn(th, th), a.anchors[l][an][1]);
+        const float hw = __fmul_rn(w, 0.5f), hh = __fmul_rn(h, 0.5f);
+        out.x1 = __fsub_rn(cx, hw); out.y1 = __fsub_rn(cy, hh);
+        out.x2 = __fadd_rn(cx, hw); out.y2 = __fadd_rn(cy, hh);
+        out.score = score; out.cls = cls; out.idx = ck.level_off + c; out.pad_ = 0;
+        keep = true;
+      }
+    }
+    // kept candidates get consecutive slots: wavefront -> workgroup (LDS) -> one global atomic per chunk.  All kept
+    // candidates of a frame bump the same counter, and same-address atomics serialise in L2, so they must be few.
+    const unsigned long long m = __ballot(keep);
+    int wslot = 0;
+    if (m) {
+      const int leader = __ffsll((long long)m) - 1;
+      if (lane == leader) wslot = atomicAdd(&s_cnt, __popcll(m));
+      wslot = __shfl(wslot, leader);
+    }
+    __syncthreads();
+    if (threadIdx.x == 0 && s_cnt > 0) s_base = atomicAdd(&a.count[(size_t)ck.item * a.count_stride], s_cnt);
+    __syncthreads();          // every lane is done with this chunk's LDS contents; s_base is visible
+    if (keep) {
+      const int slot = s_base + wslot + __popcll(m & ((1ull << lane) - 1ull));
+      if (slot < a.cap) a.cand[(size_t)ck.item * a.cap + slot] = out;
+      else if (a.overflow) atomicOr(a.overflow + ck.item, OCTO_FLAG_CAND_OVERFLOW);
+    }
+    work = next;
+  }
+}
+
+template <typename T, int CH>
+static bool decode_stream_ok(const DecodeArgs& a) {
+  for (int l = 0; l < a.n_levels; ++l) {
+    const long long region = ((long long)(CH / a.n_anchors + 2) * a.head_ld[l] + a.n_anchors * (5 + a.n_classes)) * sizeof(T) + 32;
+    if (region > DEC_LDS_BYTES || ((uintptr_t)a.head[l] & 15)) return false;
+  }
+  return true;
+}
+
+template <typename T, int CH>
+static hipError_t decode_t(const DecodeArgs& a, hipStream_t s) {
+  int cand = 0, blocks = 0;
+  for (int l = 0; l < a.n_levels; ++l) {
+    cand += a.gh[l] * a.gw[l] * a.n_anchors;
+    blocks += (a.gh[l] * a.gw[l] * a.n_anchors + CH - 1) / CH;
+  }
+  if (decode_stream_ok<T, CH>(a) && (long long)blocks * a.n < 0x7FFFFFFFLL) {
+    const long long want = (long long)blocks * a.n;
+    const unsigned grid = (unsigned)(want < 256 * 3 * (256 / CH) ? want : 256 * 3 * (256 / CH));   // persistent: what fits the chip at once
+    hipLaunchKernelGGL((decode_stream_kernel<T, CH>), dim3(grid), dim3(CH), 0, s, a, blocks);
+  } else {
+    const int chunks = (cand + 255) / 256;
+    hipLaunchKernelGGL(decode_kernel<T>, dim3(chunks > 1024 ? 1024 : chunks, a.n), dim3(256), 0, s, a, cand);
   }
   return hipGetLastError();
+}
+
+hipError_t launch_decode(int dtype, const DecodeArgs& a, hipStream_t s) {
+  if (a.n <= 0) return hipSuccess;
+  switch (dtype) {
+    case OCTO_F32: return decode_t<float, 128>(a, s);
+    case OCTO_F16: return decode_t<_Float16, 256>(a, s);
+    case OCTO_BF16: return decode_t<__bf16, 256>(a, s);
+  }
+  return hipErrorInvalidValue;
 }
 
 // ---------------------------------------------------------------------------
@@ -132,7 +297,7 @@ __global__ __launch_bounds__(TOPK_THREADS) void topk_kernel(const TopkArgs a) {
   __shared__ unsigned val[TOPK_P];
   const int n_items = dyn_n(a.n_dyn, a.n);
   for (int item = blockIdx.x; item < n_items; item += gridDim.x) {
-    int count = a.in_count[item];
+    int count = a.in_count[(size_t)item * a.in_count_stride];
     if (count > a.in_cap) count = a.in_cap;
     if (count < 0) count = 0;
     const octo_cand* in = a.in + (size_t)item * a.in_cap;
@@ -287,84 +452,105 @@ __device__ __forceinline__ float to_src(float v, float off, float r, float hi) {
   return fminf(fmaxf(s, 0.0f), hi);
 }
 
-__global__ __launch_bounds__(256) void compact_kernel(const CompactArgs a) {
-  __shared__ int s_cnt[256];
-  __shared__ int s_base;
+// Step 1, one workgroup per (item, edge) [and one extra grid row for the final box table]: flag the kept boxes whose
+// class is routed along the edge, give each its rank among the item's flagged boxes (workgroup scan) and leave the
+// item's count in roi_cnt.  Step 2, same grid: the item's first ROI id is the sum of the counts of the items before
+// it; every flagged box is written to that id + its rank.  Both steps are a few microseconds; the order of the ROI
+// table is (item, rank), exactly that of a serial walk.
+__global__ __launch_bounds__(256) void compact_count_kernel(const CompactArgs a) {
+  __shared__ int s_wave[4];
+  __shared__ int s_run;
   const int n_items = dyn_n(a.n_dyn, a.n);
-  const int e = blockIdx.x;
-  const int t = threadIdx.x;
+  const int item = blockIdx.x, e = blockIdx.y;
+  if (item >= n_items) return;
+  const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+  int nk = a.n_keep[item]; if (nk > a.max_det) nk = a.max_det;
   if (e == a.n_edges) {
-    // final boxes of every item, in keep order, in source pixels
-    for (long long i = t; i < (long long)n_items * a.max_det; i += blockDim.x) {
-      const int item = (int)(i / a.max_det), r = (int)(i % a.max_det);
-      int nk = a.n_keep[item]; if (nk > a.max_det) nk = a.max_det;
-      if (r >= nk) continue;
+    // final boxes of the item, in keep order, in source pixels
+    for (int r = t; r < nk; r += blockDim.x) {
       const octo_cand c = a.top[(size_t)item * a.k_cap + a.keep[(size_t)item * a.max_det + r]];
       octo_box b;
       b.x1 = to_src(c.x1, a.left, a.rx, a.src_w); b.x2 = to_src(c.x2, a.left, a.rx, a.src_w);
       b.y1 = to_src(c.y1, a.top_pad, a.ry, a.src_h); b.y2 = to_src(c.y2, a.top_pad, a.ry, a.src_h);
       b.score = c.score; b.cls = c.cls;
       for (int k = 0; k < OCTO_MAX_CHILD_LABELS; ++k) b.child_label[k] = -1;
-      a.boxes[i] = b;
+      a.boxes[(size_t)item * a.max_det + r] = b;
     }
     return;
   }
   const uint64_t m0 = a.class_mask[e][0], m1 = a.class_mask[e][1];
-  if (t == 0) s_base = 0;
+  if (t == 0) s_run = 0;
   __syncthreads();
-  for (int chunk = 0; chunk < n_items; chunk += blockDim.x) {
-    const int item = chunk + t;
-    int cnt = 0, nk = 0;
-    if (item < n_items) {
-      nk = a.n_keep[item]; if (nk > a.max_det) nk = a.max_det;
-      for (int r = 0; r < nk; ++r) {
-        const int cls = a.top[(size_t)item * a.k_cap + a.keep[(size_t)item * a.max_det + r]].cls;
-        const bool hit = cls >= 0 && cls < 128 && (((cls < 64 ? m0 : m1) >> (cls & 63)) & 1ull);
-        cnt += hit ? 1 : 0;
-      }
+  for (int r0 = 0; r0 < nk; r0 += blockDim.x) {
+    const int r = r0 + t;
+    bool hit = false;
+    if (r < nk) {
+      const int cls = a.top[(size_t)item * a.k_cap + a.keep[(size_t)item * a.max_det + r]].cls;
+      hit = cls >= 0 && cls < 128 && (((cls < 64 ? m0 : m1) >> (cls & 63)) & 1ull);
     }
-    s_cnt[t] = cnt;
+    const unsigned long long bal = __ballot(hit);
+    if (lane == 0) s_wave[wave] = __popcll(bal);
     __syncthreads();
-    // inclusive scan (Hillis-Steele) over the chunk
-    for (int off = 1; off < blockDim.x; off <<= 1) {
-      int v = t >= off ? s_cnt[t - off] : 0;
-      __syncthreads();
-      s_cnt[t] += v;
-      __syncthreads();
-    }
-    const int base = s_base + s_cnt[t] - cnt;
-    if (item < n_items) {
-      int j = base;
-      for (int r = 0; r < nk; ++r) {
-        const octo_cand c = a.top[(size_t)item * a.k_cap + a.keep[(size_t)item * a.max_det + r]];
-        const bool hit = c.cls >= 0 && c.cls < 128 && (((c.cls < 64 ? m0 : m1) >> (c.cls & 63)) & 1ull);
-        int id = -1;
-        if (hit) {
-          if (j < a.roi_cap[e]) {
-            octo_roi o;
-            o.frame = item; o.rank = r; o.cls = c.cls; o.pad_ = 0;
-            o.x1 = to_src(c.x1, a.left, a.rx, a.src_w); o.x2 = to_src(c.x2, a.left, a.rx, a.src_w);
-            o.y1 = to_src(c.y1, a.top_pad, a.ry, a.src_h); o.y2 = to_src(c.y2, a.top_pad, a.ry, a.src_h);
-            a.rois[e][j] = o;
-            id = j;
-          } else if (a.flags) {
-            atomicOr(a.flags + item, OCTO_FLAG_ROI_OVERFLOW);
-          }
-          ++j;
-        }
-        if (a.roi_of[e]) a.roi_of[e][(size_t)item * a.max_det + r] = id;
-      }
-    }
+    int before = s_run;
+    for (int w = 0; w < wave; ++w) before += s_wave[w];
+    const int rank = before + __popcll(bal & ((1ull << lane) - 1ull));
+    if (r < nk) a.roi_of[e][(size_t)item * a.max_det + r] = hit ? rank : -1;      // rank inside the item for now
     __syncthreads();
-    if (t == blockDim.x - 1) s_base += s_cnt[t];
+    if (t == 0) s_run += s_wave[0] + s_wave[1] + s_wave[2] + s_wave[3];
     __syncthreads();
   }
-  if (t == 0) *a.n_roi[e] = s_base < a.roi_cap[e] ? s_base : a.roi_cap[e];
+  if (t == 0) a.roi_cnt[e][item] = s_run;
+}
+
+__global__ __launch_bounds__(256) void compact_write_kernel(const CompactArgs a) {
+  __shared__ int s_part[256];
+  const int n_items = dyn_n(a.n_dyn, a.n);
+  const int item = blockIdx.x, e = blockIdx.y;
+  if (item >= n_items) return;
+  const int t = threadIdx.x;
+  // ROIs of all earlier items (and, in the last workgroup, the total)
+  int part = 0, tot = 0;
+  for (int f = t; f < n_items; f += blockDim.x) { const int c = a.roi_cnt[e][f]; tot += c; if (f < item) part += c; }
+  s_part[t] = part;
+  __syncthreads();
+  for (int off = 128; off > 0; off >>= 1) { if (t < off) s_part[t] += s_part[t + off]; __syncthreads(); }
+  const int base = s_part[0];
+  __syncthreads();
+  if (item == n_items - 1) {
+    s_part[t] = tot;
+    __syncthreads();
+    for (int off = 128; off > 0; off >>= 1) { if (t < off) s_part[t] += s_part[t + off]; __syncthreads(); }
+    if (t == 0) *a.n_roi[e] = s_part[0] < a.roi_cap[e] ? s_part[0] : a.roi_cap[e];
+  }
+  int nk = a.n_keep[item]; if (nk > a.max_det) nk = a.max_det;
+  for (int r = t; r < nk; r += blockDim.x) {
+    const int local = a.roi_of[e][(size_t)item * a.max_det + r];
+    if (local < 0) continue;
+    const int j = base + local;
+    int id = -1;
+    if (j < a.roi_cap[e]) {
+      const octo_cand c = a.top[(size_t)item * a.k_cap + a.keep[(size_t)item * a.max_det + r]];
+      octo_roi o;
+      o.frame = item; o.rank = r; o.cls = c.cls; o.pad_ = 0;
+      o.x1 = to_src(c.x1, a.left, a.rx, a.src_w); o.x2 = to_src(c.x2, a.left, a.rx, a.src_w);
+      o.y1 = to_src(c.y1, a.top_pad, a.ry, a.src_h); o.y2 = to_src(c.y2, a.top_pad, a.ry, a.src_h);
+      a.rois[e][j] = o;
+      id = j;
+    } else if (a.flags) {
+      atomicOr(a.flags + item, OCTO_FLAG_ROI_OVERFLOW);
+    }
+    a.roi_of[e][(size_t)item * a.max_det + r] = id;
+  }
 }
 
 hipError_t launch_compact(const CompactArgs& a, hipStream_t s) {
   if (a.n <= 0) return hipSuccess;
-  hipLaunchKernelGGL(compact_kernel, dim3(a.n_edges + (a.boxes ? 1 : 0)), dim3(256), 0, s, a);
+  if (a.n > 65535) return hipErrorInvalidValue;
+  for (int e = 0; e < a.n_edges; ++e) if (!a.roi_of[e] || !a.roi_cnt[e]) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(compact_count_kernel, dim3(a.n, a.n_edges + (a.boxes ? 1 : 0)), dim3(256), 0, s, a);
+  hipError_t err = hipGetLastError();
+  if (err != hipSuccess || a.n_edges == 0) return err;
+  hipLaunchKernelGGL(compact_write_kernel, dim3(a.n, a.n_edges), dim3(256), 0, s, a);
   return hipGetLastError();
 }
 

@@ -39,27 +39,50 @@ __device__ __forceinline__ void store_pixels(T* dst, const float* v) {
   }
 }
 
-__device__ __forceinline__ void bilinear_rgb(const uint8_t* row_a, const uint8_t* row_b, int xa, int xb, float fx, float fy,
+// 12 source bytes (4 RGB pixels) starting at pixel ws of a row, fetched with one unaligned 3-dword load
+struct __attribute__((packed)) Win12 { uint32_t d0, d1, d2; };
+__device__ __forceinline__ Win12 load_window(const uint8_t* row, int ws) {
+  Win12 w;
+  __builtin_memcpy(&w, row + 3 * ws, 12);
+  return w;
+}
+// the three channels of the pixel that starts at byte `off` (0, 3, 6 or 9) of the window
+__device__ __forceinline__ void window_pixel(const Win12& w, int off, float* rgb) {
+  const unsigned long long lo = (unsigned long long)w.d0 | ((unsigned long long)w.d1 << 32);
+  const unsigned long long hi = (unsigned long long)w.d1 | ((unsigned long long)w.d2 << 32);
+  const unsigned v = off < 4 ? (unsigned)(lo >> (8 * off)) : (unsigned)(hi >> (8 * (off - 4)));
+  rgb[0] = (float)(v & 0xFFu); rgb[1] = (float)((v >> 8) & 0xFFu); rgb[2] = (float)((v >> 16) & 0xFFu);
+}
+
+// Bilinear sample of taps (xa, xb) x (row_a, row_b); xb is xa or xa + 1 (clamping), so both taps of a row come from
+// one window.  Needs src_w >= 4.
+__device__ __forceinline__ void bilinear_rgb(const uint8_t* row_a, const uint8_t* row_b, int xa, int xb, int src_w, float fx, float fy,
                                              const float* scale, const float* bias, float* out) {
-  const uint8_t* p00 = row_a + 3 * xa; const uint8_t* p01 = row_a + 3 * xb;
-  const uint8_t* p10 = row_b + 3 * xa; const uint8_t* p11 = row_b + 3 * xb;
+  const int ws = xa < src_w - 4 ? xa : src_w - 4;
+  const Win12 wa = load_window(row_a, ws), wb = load_window(row_b, ws);
+  float p00[3], p01[3], p10[3], p11[3];
+  window_pixel(wa, 3 * (xa - ws), p00); window_pixel(wa, 3 * (xb - ws), p01);
+  window_pixel(wb, 3 * (xa - ws), p10); window_pixel(wb, 3 * (xb - ws), p11);
 #pragma unroll
   for (int c = 0; c < 3; ++c) {
-    float top = (1.0f - fx) * (float)p00[c] + fx * (float)p01[c];
-    float bot = (1.0f - fx) * (float)p10[c] + fx * (float)p11[c];
+    float top = (1.0f - fx) * p00[c] + fx * p01[c];
+    float bot = (1.0f - fx) * p10[c] + fx * p11[c];
     out[c] = ((1.0f - fy) * top + fy * bot) * scale[c] + bias[c];
   }
 }
 
 struct LetterboxGeom { int nw, nh, left, top; };
 
-template <typename T, int PX, bool C4>
+// EXACT: the source / resized size ratio is an odd integer in both directions, so every output pixel is exactly one
+// source pixel (1080p -> 640x360 and 2160p -> 1280x720 are ratio 3): one window load per pixel, no interpolation.
+template <typename T, int PX, bool C4, bool EXACT>
 __global__ void letterbox_kernel(const ResizeArgs a, const LetterboxGeom g) {
   const int wq = a.dst_w / PX;
   int n_items = a.n;
   if (a.n_dyn) { int d = *a.n_dyn; n_items = d < a.n ? d : a.n; }
   const long long total = (long long)n_items * a.dst_h * wq;
   T* dst = (T*)a.dst;
+  const int rx = a.src_w / g.nw, ry = a.src_h / g.nh;      // only meaningful when EXACT
   for (long long i = blockIdx.x * (long long)blockDim.x + threadIdx.x; i < total; i += (long long)gridDim.x * blockDim.x) {
     const int xq = (int)(i % wq);
     const long long t = i / wq;
@@ -72,21 +95,34 @@ __global__ void letterbox_kernel(const ResizeArgs a, const LetterboxGeom g) {
     const size_t pitch = a.pitches[img];
     int ya = 0, yb = 0; float fy = 0.f;
     if (row_in) {
-      // source y = (yi + 0.5) * Hs / nh - 0.5 = ((2 yi + 1) Hs - nh) / (2 nh), split exactly into floor and fraction
-      const int num = (2 * yi + 1) * a.src_h - g.nh, den = 2 * g.nh;
-      int y0 = num >= 0 ? num / den : -((-num + den - 1) / den);
-      fy = (float)(num - y0 * den) / (float)den;
-      ya = clampi(y0, 0, a.src_h - 1); yb = clampi(y0 + 1, 0, a.src_h - 1);
+      if (EXACT) {
+        ya = yb = ry * yi + (ry - 1) / 2;
+      } else {
+        // source y = (yi + 0.5) * Hs / nh - 0.5 = ((2 yi + 1) Hs - nh) / (2 nh), split exactly into floor and fraction
+        const int num = (2 * yi + 1) * a.src_h - g.nh, den = 2 * g.nh;
+        int y0 = num >= 0 ? num / den : -((-num + den - 1) / den);
+        fy = (float)(num - y0 * den) / (float)den;
+        ya = clampi(y0, 0, a.src_h - 1); yb = clampi(y0 + 1, 0, a.src_h - 1);
+      }
     }
 #pragma unroll
     for (int px = 0; px < PX; ++px) {
       const int xi = xq * PX + px - g.left;
       if (row_in && (unsigned)xi < (unsigned)g.nw) {
-        const int num = (2 * xi + 1) * a.src_w - g.nw, den = 2 * g.nw;
-        int x0 = num >= 0 ? num / den : -((-num + den - 1) / den);
-        const float fx = (float)(num - x0 * den) / (float)den;
-        const int xa = clampi(x0, 0, a.src_w - 1), xb = clampi(x0 + 1, 0, a.src_w - 1);
-        bilinear_rgb(base + (size_t)ya * pitch, base + (size_t)yb * pitch, xa, xb, fx, fy, a.scale, a.bias, v + 3 * px);
+        if (EXACT) {
+          const int xs = rx * xi + (rx - 1) / 2;
+          const int ws = xs < a.src_w - 4 ? xs : a.src_w - 4;
+          float rgb[3];
+          window_pixel(load_window(base + (size_t)ya * pitch, ws), 3 * (xs - ws), rgb);
+#pragma unroll
+          for (int c = 0; c < 3; ++c) v[3 * px + c] = rgb[c] * a.scale[c] + a.bias[c];
+        } else {
+          const int num = (2 * xi + 1) * a.src_w - g.nw, den = 2 * g.nw;
+          int x0 = num >= 0 ? num / den : -((-num + den - 1) / den);
+          const float fx = (float)(num - x0 * den) / (float)den;
+          const int xa = clampi(x0, 0, a.src_w - 1), xb = clampi(x0 + 1, 0, a.src_w - 1);
+          bilinear_rgb(base + (size_t)ya * pitch, base + (size_t)yb * pitch, xa, xb, a.src_w, fx, fy, a.scale, a.bias, v + 3 * px);
+        }
       } else {
 #pragma unroll
         for (int c = 0; c < 3; ++c) v[3 * px + c] = (float)a.pad_value * a.scale[c] + a.bias[c];
@@ -124,7 +160,7 @@ __global__ void crop_resize_kernel(const ResizeArgs a) {
       const float x0f = floorf(sx);
       const float fx = sx - x0f;
       const int xa = clampi((int)x0f, 0, a.src_w - 1), xb = clampi((int)x0f + 1, 0, a.src_w - 1);
-      bilinear_rgb(base + (size_t)ya * pitch, base + (size_t)yb * pitch, xa, xb, fx, fy, a.scale, a.bias, v + 3 * px);
+      bilinear_rgb(base + (size_t)ya * pitch, base + (size_t)yb * pitch, xa, xb, a.src_w, fx, fy, a.scale, a.bias, v + 3 * px);
     }
     store_pixels<T, PX, C4>(dst + (((size_t)roi * a.dst_h + y) * a.dst_w + (size_t)xq * PX) * (C4 ? 4 : 3), v);
   }
@@ -156,18 +192,22 @@ void letterbox_geometry(int src_h, int src_w, int dst_h, int dst_w, int* nw, int
   *nw = g.nw; *nh = g.nh; *left = g.left; *top = g.top;
 }
 
-template <typename T> static hipError_t letterbox_t(const ResizeArgs& a, hipStream_t s) {
-  LetterboxGeom g = letterbox_geom(a.src_h, a.src_w, a.dst_h, a.dst_w);
+template <typename T, bool EXACT> static hipError_t letterbox_e(const ResizeArgs& a, const LetterboxGeom& g, hipStream_t s) {
   if (a.dst_c == 4 && ((uintptr_t)a.dst & 15) == 0 && a.dst_w % 4 == 0) {
-    hipLaunchKernelGGL((letterbox_kernel<T, 4, true>), dim3(resize_grid((long long)a.n * a.dst_h * (a.dst_w / 4))), dim3(256), 0, s, a, g);
+    hipLaunchKernelGGL((letterbox_kernel<T, 4, true, EXACT>), dim3(resize_grid((long long)a.n * a.dst_h * (a.dst_w / 4))), dim3(256), 0, s, a, g);
   } else if (a.dst_c == 4) {
-    hipLaunchKernelGGL((letterbox_kernel<T, 1, true>), dim3(resize_grid((long long)a.n * a.dst_h * a.dst_w)), dim3(256), 0, s, a, g);
+    hipLaunchKernelGGL((letterbox_kernel<T, 1, true, EXACT>), dim3(resize_grid((long long)a.n * a.dst_h * a.dst_w)), dim3(256), 0, s, a, g);
   } else if (a.dst_w % 4 == 0 && ((uintptr_t)a.dst & 15) == 0) {
-    hipLaunchKernelGGL((letterbox_kernel<T, 4, false>), dim3(resize_grid((long long)a.n * a.dst_h * (a.dst_w / 4))), dim3(256), 0, s, a, g);
+    hipLaunchKernelGGL((letterbox_kernel<T, 4, false, EXACT>), dim3(resize_grid((long long)a.n * a.dst_h * (a.dst_w / 4))), dim3(256), 0, s, a, g);
   } else {
-    hipLaunchKernelGGL((letterbox_kernel<T, 1, false>), dim3(resize_grid((long long)a.n * a.dst_h * a.dst_w)), dim3(256), 0, s, a, g);
+    hipLaunchKernelGGL((letterbox_kernel<T, 1, false, EXACT>), dim3(resize_grid((long long)a.n * a.dst_h * a.dst_w)), dim3(256), 0, s, a, g);
   }
   return hipGetLastError();
+}
+template <typename T> static hipError_t letterbox_t(const ResizeArgs& a, hipStream_t s) {
+  const LetterboxGeom g = letterbox_geom(a.src_h, a.src_w, a.dst_h, a.dst_w);
+  const bool exact = a.src_w % g.nw == 0 && a.src_h % g.nh == 0 && ((a.src_w / g.nw) & 1) && ((a.src_h / g.nh) & 1);
+  return exact ? letterbox_e<T, true>(a, g, s) : letterbox_e<T, false>(a, g, s);
 }
 template <typename T> static hipError_t crop_t(const ResizeArgs& a, hipStream_t s) {
   if (a.dst_c == 4 && ((uintptr_t)a.dst & 15) == 0 && a.dst_w % 4 == 0) {
@@ -184,7 +224,7 @@ template <typename T> static hipError_t crop_t(const ResizeArgs& a, hipStream_t 
 
 hipError_t launch_letterbox(int dtype, const ResizeArgs& a, hipStream_t s) {
   if (a.n <= 0) return hipSuccess;
-  if (a.dst_c != 3 && a.dst_c != 4) return hipErrorInvalidValue;
+  if ((a.dst_c != 3 && a.dst_c != 4) || a.src_w < 4) return hipErrorInvalidValue;
   switch (dtype) {
     case OCTO_F32: return letterbox_t<float>(a, s);
     case OCTO_F16: return letterbox_t<_Float16>(a, s);
@@ -194,7 +234,7 @@ hipError_t launch_letterbox(int dtype, const ResizeArgs& a, hipStream_t s) {
 }
 hipError_t launch_crop_resize(int dtype, const ResizeArgs& a, hipStream_t s) {
   if (a.n <= 0) return hipSuccess;
-  if (a.dst_c != 3 && a.dst_c != 4) return hipErrorInvalidValue;
+  if ((a.dst_c != 3 && a.dst_c != 4) || a.src_w < 4) return hipErrorInvalidValue;
   switch (dtype) {
     case OCTO_F32: return crop_t<float>(a, s);
     case OCTO_F16: return crop_t<_Float16>(a, s);

@@ -196,15 +196,25 @@ def planted_heads(rng, det: ModelSpec, scene: Scene, src_h, src_w, max_dups=4, n
                         plant(f, lvl, a, gy, gx + dx, cx, cy, jw, jh, o2, cls)
                     else:
                         plant(f, lvl, a, gy + dy, gx, cx, cy, jw, jh, o2, cls)
-        for _ in range(n_clutter):
+        # low-score clutter so that top-k really truncates: candidates crowd around a few hot spots (same class,
+        # similar size, jittered centres), so NMS has dense overlaps to resolve and removes most of them again
+        n_spots = 40 if n_clutter else 0
+        size = det.in_w
+        spots = [(rng.uniform(0.1, 0.9) * size, rng.uniform(0.25, 0.75) * size, rng.uniform(0.05, 0.18) * size,
+                  rng.uniform(0.05, 0.18) * size, int(rng.integers(0, C))) for _ in range(n_spots)]
+        placed, tries = 0, 0
+        while placed < n_clutter and tries < 20 * n_clutter:
+            tries += 1
+            sx, sy, sw, sh, scls = spots[int(rng.integers(0, n_spots))]
+            cx, cy = sx + rng.uniform(-0.25, 0.25) * sw, sy + rng.uniform(-0.25, 0.25) * sh
+            bw, bh = sw * rng.uniform(0.85, 1.15), sh * rng.uniform(0.85, 1.15)
             lvl = int(rng.integers(0, len(det.grids)))
-            g, s = det.grids[lvl], det.strides[lvl]
-            gx, gy, a = int(rng.integers(0, g)), int(rng.integers(0, g)), int(rng.integers(0, A))
-            aw, ah = det.anchors[lvl, a]
+            s_ = det.strides[lvl]
+            a = int(rng.integers(0, A))
+            gx, gy = int(cx // s_) + int(rng.integers(-1, 2)) * int(rng.random() < 0.3), int(cy // s_)
             # score = sigmoid(obj) * sigmoid(4) in (0.26, 0.30)
             target = rng.uniform(0.262, 0.298) / (1.0 / (1.0 + math.exp(-4.0)))
-            plant(f, lvl, a, gy, gx, (gx + rng.uniform(0.1, 0.9)) * s, (gy + rng.uniform(0.1, 0.9)) * s,
-                  aw * rng.uniform(0.5, 1.5), ah * rng.uniform(0.5, 1.5), _logit(target), int(rng.integers(0, C)))
+            placed += bool(plant(f, lvl, a, gy, gx, cx, cy, bw, bh, _logit(target), scls))
     return [round_to_dtype(h.reshape(n, g, g, A * no), det.dtype) for h, g in zip(heads, det.grids)]
 
 

@@ -178,3 +178,71 @@ def test_run_model_by_model_on_two_streams_matches_octo_run(octo):
     f1, b1, _ = P.collect()
     assert b0.tobytes() == b1.tobytes() and f0["n_boxes"].tolist() == f1["n_boxes"].tolist()
     P.close()
+
+
+def test_hires_cascade_planted_heavy_tail(octo):
+    """High-resolution workload at its real per-frame shape (one 3840x2160 frame, m-shaped detector at 1280, top-k 1000
+    truncating, dense clutter for NMS), bf16; the classifier is checked on the first ROIs only (oracle time)."""
+    spec = zoo.hires_cascade(det_batch=1, max_rois_per_frame=300)
+    det = spec.models[0]
+    rng = np.random.default_rng(zoo.SEED0 + 5)
+    counts = np.array([37])
+    scene = synth.make_scene(rng, 1, 2160, 3840, counts, 48, 720, log_uniform=True)
+    planted = synth.planted_heads(rng, det, scene, 2160, 3840, n_clutter=1100)
+    ref = cascade.run_cascade(spec, scene.frames, planted_heads=planted, max_child_rois=6)
+    assert ref.dets[0].cand_count > 1000 and len(ref.dets[0].top) == 1000 and 40 < len(ref.dets[0].keep) <= 300
+    P = octo.Pipeline(spec)
+    for l, h in enumerate(planted):
+        P.set_head(0, l, octo.to_device(h, "bf16"))
+    P.submit(_frames_dev(scene.frames))
+    assert P.run() == 1
+    frames, boxes, st = P.collect()
+    assert st == octo.OK
+    for l, t in enumerate(det.outputs):
+        assert rel_err(P.get_tensor(0, t, 1), ref.heads[l]) <= TOL["bf16"], l
+    cc, top, keep = P.get_detections(0, 0)
+    d = ref.dets[0]
+    assert cc == d.cand_count and top["idx"].tolist() == d.top.idx.tolist() and keep.tolist() == d.keep.tolist()
+    rois = P.get_rois(0)
+    r = ref.children[0].rois
+    assert rois["frame"].tolist() == r.frame.tolist() and rois["rank"].tolist() == r.rank.tolist()
+    assert np.abs(np.stack([rois["x1"], rois["y1"], rois["x2"], rois["y2"]], 1) - r.box).max() < 2e-2
+    m = 6
+    assert rel_err(P.get_tensor(1, 0, m), ref.children[0].crops) <= 8e-3
+    logits = P.get_tensor(1, spec.models[1].outputs[0], m).reshape(m, -1)
+    assert rel_err(logits, ref.children[0].logits) <= TOL["bf16"]
+    assert frames["n_boxes"][0] == len(d.keep) and len(boxes) == len(d.keep)
+    P.close()
+
+
+@pytest.mark.parametrize("bz", [1, 4])
+def test_sweep_cascade_bursty_counts(octo, bz):
+    """Batch-size sweep workload (bf16, negative-binomial object counts, cap 200): post-processing and ROI routing are
+    exact for every batch size; a frame with zero objects and a very crowded frame sit in one batch."""
+    spec = zoo.sweep_cascade(bz)
+    det = spec.models[0]
+    rng = np.random.default_rng(zoo.SEED0 + 3)
+    counts = synth.counts_negbin(rng, bz)
+    counts[0] = 0
+    if bz > 1:
+        counts[1] = 90
+    scene = synth.make_scene(rng, bz, 1080, 1920, counts, 24, 200, log_uniform=True)
+    planted = synth.planted_heads(rng, det, scene, 1080, 1920)
+    dets = cascade.postprocess_heads(planted, det)
+    P = octo.Pipeline(spec)
+    for l, h in enumerate(planted):
+        P.set_head(0, l, octo.to_device(h, "bf16"))
+    P.submit(_frames_dev(scene.frames))
+    assert P.run() == bz
+    frames, boxes, st = P.collect()
+    assert st == octo.OK and frames["n_boxes"].tolist() == [len(d.keep) for d in dets]
+    for f, d in enumerate(dets):
+        cc, top, keep = P.get_detections(0, f)
+        assert cc == d.cand_count and top["idx"].tolist() == d.top.idx.tolist() and keep.tolist() == d.keep.tolist()
+    rois = P.get_rois(0)
+    exp = [(f, r) for f, d in enumerate(dets) for r in range(len(d.keep))]
+    assert list(zip(rois["frame"].tolist(), rois["rank"].tolist())) == exp
+    assert frames["n_boxes"][0] == 0
+    lab = P.get_labels(0)
+    assert len(lab) == len(exp) and np.array_equal(boxes["child_label"][:, 0], lab) and np.all((lab >= 0) & (lab < 1000))
+    P.close()
