@@ -191,9 +191,10 @@ def test_hires_cascade_planted_heavy_tail(octo):
     planted = synth.planted_heads(rng, det, scene, 2160, 3840, n_clutter=1100)
     ref = cascade.run_cascade(spec, scene.frames, planted_heads=planted, max_child_rois=6)
     assert ref.dets[0].cand_count > 1000 and len(ref.dets[0].top) == 1000 and 40 < len(ref.dets[0].keep) <= 300
-    P = octo.Pipeline(spec)
-    for l, h in enumerate(planted):
-        P.set_head(0, l, octo.to_device(h, "bf16"))
+    P = octo.Pipeline(spec, keep_all_tensors=True)          # the crops (child tensor 0) are read back below
+    d_heads = [octo.to_device(h, "bf16") for h in planted]        # must stay alive while the pipeline reads them
+    for l, h in enumerate(d_heads):
+        P.set_head(0, l, h)
     P.submit(_frames_dev(scene.frames))
     assert P.run() == 1
     frames, boxes, st = P.collect()
@@ -230,8 +231,9 @@ def test_sweep_cascade_bursty_counts(octo, bz):
     planted = synth.planted_heads(rng, det, scene, 1080, 1920)
     dets = cascade.postprocess_heads(planted, det)
     P = octo.Pipeline(spec)
-    for l, h in enumerate(planted):
-        P.set_head(0, l, octo.to_device(h, "bf16"))
+    d_heads = [octo.to_device(h, "bf16") for h in planted]
+    for l, h in enumerate(d_heads):
+        P.set_head(0, l, h)
     P.submit(_frames_dev(scene.frames))
     assert P.run() == bz
     frames, boxes, st = P.collect()
