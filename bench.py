@@ -50,6 +50,15 @@ def make_workload(name: str):
     return spec, scene, heads, desc
 
 
+def conv_name(kid: int, dtype: str) -> str:
+    """Template instance behind a conv kernel id (digits 1 BBB PPP K M V), as rocprofv3 prints it."""
+    d = kid - 1000000000
+    bc, bp, kv, minb, vec = d // 1000000, (d // 1000) % 1000, (d // 100) % 10, (d // 10) % 10, d % 10
+    wc, wp = (1, 4) if bc == 32 else (2, 2)
+    ctype = {"f16": "_Float16", "bf16": "__bf16", "f32": "float"}[dtype]
+    return "octo::conv_mfma_kernel<%s, %d, %d, %d, %d, %d, 2, %d, %s>" % (ctype, bc, bp, wc, wp, kv, minb, "true" if vec else "false")
+
+
 def cpu_baseline(spec, scene, heads):
     """The oracle, as it stands, on the same batch (bounded to about 10-30 s of CPU work)."""
     import torch
@@ -71,6 +80,9 @@ def main():
     ap.add_argument("--workload", default="traffic")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--layers", action="store_true", help="print the per-layer table to stderr")
+    ap.add_argument("--calib-copy-mib", type=int, default=0,
+                    help="also run one plain device copy of this many MiB before the timed region (a known-size kernel "
+                         "against which hardware traffic counters are scaled)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU only (frames are independent: more GPUs = more copies of this run); --gpus %d refused" % args.gpus,
@@ -100,21 +112,33 @@ def main():
     for _ in range(args.warmup):
         step_submit()
         P.collect()
+    if args.calib_copy_mib:
+        src = torch.full((args.calib_copy_mib << 18,), 1.0, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        torch.add(src, 1.0, out=dst)           # one elementwise kernel: reads and writes calib_copy_mib MiB each
+        torch.cuda.synchronize()
+        del src, dst
     # ---- timed region: K steps, two batches in flight, inputs resident in HBM ----
     lat, met, total_boxes = [], 0, 0
+    submitted = collected = 0
+
+    def drain(max_in_flight):
+        nonlocal collected, met, total_boxes
+        while submitted - collected > max_in_flight * n:
+            fr, bx, st = P.collect()            # blocking: returns at least the oldest batch
+            collected += len(fr)
+            lat.extend(fr["latency_ms"].tolist())
+            met += int(fr["slo_met"].sum())
+            total_boxes += int(fr["n_boxes"].sum())
+
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    step_submit()
     for i in range(args.steps):
-        if i + 1 < args.steps:
-            step_submit()
-        fr, bx, st = P.collect()
-        while len(fr) < n:                      # a collect may return one batch at a time
-            f2, b2, st = P.collect()
-            fr = np.concatenate([fr, f2]); bx = np.concatenate([bx, b2])
-        lat.append(float(fr["latency_ms"].max()))
-        met += int(fr["slo_met"].sum())
-        total_boxes += int(fr["n_boxes"].sum())
+        step_submit()
+        submitted += n
+        drain(1)                                # one batch stays in flight while the next is prepared
+    drain(0)
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     # ---- same region again with an event between layers: per-kernel durations ----
@@ -131,20 +155,19 @@ def main():
         P.collect()
         stage.append(P.stage_ms())
         for mi, m in enumerate(spec.models):
-            ms, kid, fl, by = P.layer_info(mi)
+            ms, kid, fl, by, wb = P.layer_info(mi)
             for j in range(len(ms)):
                 if kid[j] == 0:
                     continue
                 a = agg.setdefault(int(kid[j]), [0.0, 0.0, 0.0, 0])
-                a[0] += float(ms[j]); a[1] += fl[j] * items[mi]; a[2] += by[j] * items[mi]; a[3] += 1
+                a[0] += float(ms[j]); a[1] += fl[j] * items[mi]; a[2] += by[j] * items[mi] + wb[j]; a[3] += 1
     P.set_layer_timing(False)
     P.set_stage_timing(False)
     stage = np.mean(np.stack(stage), axis=0)
-    conv = {k: v for k, v in agg.items() if k >= 100000}
+    conv = {k: v for k, v in agg.items() if k >= 1000000000}
     dom = max(conv, key=lambda k: conv[k][0])
     t_ms, fl, by, launches = conv[dom]
-    bc, rest = (dom - 100000) // 1000, (dom - 100000) % 1000
-    kname = "conv_mfma_kernel<%s, %d, %d, vec=%d>" % (det.dtype, bc, rest // 2, rest % 2)
+    kname = conv_name(dom, det.dtype)
     roofline = {"bound": "mfma", "kernel": kname, "achieved": fl / (t_ms * 1e-3) / 1e12, "peak": PEAK[det.dtype], "unit": "TFLOP/s",
                 "frac": fl / (t_ms * 1e-3) / 1e12 / PEAK[det.dtype], "traffic": None,
                 "avg_launch_us": 1e3 * t_ms / launches, "launches_per_step": launches / ksteps,
@@ -166,8 +189,9 @@ def main():
     }
     if args.layers:
         for k, v in sorted(agg.items()):
-            print("kernel %7d  %8.3f ms/step  %7.1f TFLOP/s  %7.1f GB/s  %5.1f launches/step" %
-                  (k, v[0] / ksteps, v[1] / max(v[0], 1e-9) / 1e9, v[2] / max(v[0], 1e-9) / 1e6, v[3] / ksteps), file=sys.stderr)
+            nm = conv_name(k, det.dtype) if k >= 1000000000 else {1: "maxpool", 2: "upsample2x", 3: "copy", 4: "add", 5: "gap"}.get(k, str(k))
+            print("%-80s %8.3f ms/step  %7.1f TFLOP/s  %7.1f GB/s  %5.1f launches/step  %7.1f us/launch" %
+                  (nm, v[0] / ksteps, v[1] / max(v[0], 1e-9) / 1e9, v[2] / max(v[0], 1e-9) / 1e6, v[3] / ksteps, 1e3 * v[0] / max(v[3], 1)), file=sys.stderr)
     if not args.no_cpu_baseline:
         out["cpu_baseline"], _ = cpu_baseline(spec, scene, heads)
     P.close()

@@ -203,17 +203,21 @@ octo_status octo_run_model(octo_pipeline* p, int32_t model, void* hip_stream, in
 
 /* Time every layer of a model: each layer is launched `iters` times back to back between two HIP events on
  * `hip_stream` for `n` items; ms[i] = mean duration of layer i, flops[i] / bytes[i] its dense FLOPs and the
- * element bytes of its external tensors for n items.  Synchronises the stream. */
+ * element bytes of its external tensors (activations of n items plus weights once).  Synchronises the stream. */
 octo_status octo_profile_layers(octo_pipeline* p, int32_t model, int32_t n, int32_t iters, void* hip_stream,
                                 float* ms, double* flops, double* bytes, int32_t cap);
 /* Per-layer GPU time inside the serving path: after octo_set_layer_timing(p, 1) every run records a HIP event
  * between the layers of each model (on the stream the layers run on); octo_get_layer_info then returns, for the most
- * recently collected batch, ms[i] = time from the end of layer i-1 to the end of layer i, kernel_id[i] = which
- * kernel ran it (conv: 100000 + 1000*channel-tile + 2*pixel-tile + vectorised-gather bit; 1 max-pool, 2 upsample,
- * 3 channel copy, 4 add, 5 global average pool, 0 none), and per ITEM dense FLOPs and external tensor bytes. */
+ * recently collected batch, ms[i] = run time of layer i (convolution and fully connected layers: the kernel's own
+ * duration, from events attached to its dispatch; other layers: end of layer i-1 to end of layer i on the stream,
+ * which includes the launch gap), kernel_id[i] = which
+ * kernel ran it (conv: decimal digits 1 BBB PPP K M V = channel tile, pixel tile, 16-byte vectors per K step,
+ * workgroups per CU, vectorised-gather bit; 1 max-pool, 2 upsample,
+ * 3 channel copy, 4 add, 5 global average pool, 0 none), per ITEM dense FLOPs and activation bytes (input, output
+ * and residual elements), and per LAUNCH weight and bias bytes. */
 octo_status octo_set_layer_timing(octo_pipeline* p, int32_t enable);
 octo_status octo_get_layer_info(octo_pipeline* p, int32_t model, float* ms, int32_t* kernel_id, double* flops, double* bytes,
-                                int32_t cap, int32_t* n);
+                                double* weight_bytes, int32_t cap, int32_t* n);
 /* Per-stage GPU time of the most recently collected batch, ms: letterbox, detector layers, decode, top-k, NMS,
  * compaction, then per edge (crop, child layers, child post-processing).  Only measured after
  * octo_set_stage_timing(p, 1), which adds event records between stages. */

@@ -125,7 +125,7 @@ def lib() -> C.CDLL:
         L.octo_profile_layers.argtypes = [vp, i32, i32, i32, vp, vp, vp, vp, i32]
         L.octo_set_stage_timing.argtypes = [vp, i32]
         L.octo_set_layer_timing.argtypes = [vp, i32]
-        L.octo_get_layer_info.argtypes = [vp, i32, vp, vp, vp, vp, i32, vp]
+        L.octo_get_layer_info.argtypes = [vp, i32, vp, vp, vp, vp, vp, i32, vp]
         L.octo_get_stage_ms.argtypes = [vp, vp, i32, vp]
         L.octo_debug_get_tensor.argtypes = [vp, i32, i32, i32, vp, C.c_size_t]
         L.octo_debug_tensor_shape.argtypes = [vp, i32, i32, vp, vp, vp]
@@ -367,9 +367,11 @@ class Pipeline:
         """(ms, kernel_id, flops per item, bytes per item) per layer for the most recently collected batch."""
         nl = len(self.spec.models[model].layers)
         ms = np.zeros(nl, np.float32); kid = np.zeros(nl, np.int32); fl = np.zeros(nl, np.float64); by = np.zeros(nl, np.float64)
+        wb = np.zeros(nl, np.float64)
         n = C.c_int32()
-        self._check(self.L.octo_get_layer_info(self.h, model, ms.ctypes.data, kid.ctypes.data, fl.ctypes.data, by.ctypes.data, nl, C.byref(n)))
-        return ms, kid, fl, by
+        self._check(self.L.octo_get_layer_info(self.h, model, ms.ctypes.data, kid.ctypes.data, fl.ctypes.data, by.ctypes.data,
+                                               wb.ctypes.data, nl, C.byref(n)))
+        return ms, kid, fl, by, wb
 
     def set_stage_timing(self, on: bool):
         self._check(self.L.octo_set_stage_timing(self.h, 1 if on else 0))

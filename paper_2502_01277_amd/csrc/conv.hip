@@ -21,6 +21,7 @@
 // depend on an item count that lives in device memory (a variable number of ROIs),
 // so no host round trip is needed.
 #include "octo_internal.h"
+#include <hip/hip_ext.h>
 
 namespace octo {
 
@@ -364,8 +365,9 @@ __global__ __launch_bounds__(THREADS, MINB) void conv_mfma_kernel(const ConvArgs
   }
 }
 
-// kernel id of a conv tile configuration: channel tile, pixel tile and the gather flavour
-int conv_kernel_id(int bc, int bp, bool vec) { return 100000 + bc * 1000 + bp * 2 + (vec ? 1 : 0); }
+// kernel id of a conv tile configuration, decimal digits 1 BBB PPP K M V: channel tile, pixel tile, 16-byte vectors per
+// K step, workgroups per CU the registers are sized for, vectorised gather
+int conv_kernel_id(int bc, int bp, int kv, int minb, bool vec) { return 1000000000 + bc * 1000000 + bp * 1000 + kv * 100 + minb * 10 + (vec ? 1 : 0); }
 
 size_t conv_packed_weight_elems(int cout, int kh, int kw, int cin, int dtype, int* kp_out, int* cout_pad_out) {
   const int vn = dtype == OCTO_F32 ? 4 : 8;
@@ -380,20 +382,24 @@ size_t conv_packed_weight_elems(int cout, int kh, int kw, int cin, int dtype, in
 
 #ifndef OCTO_CONV_NO_LAUNCHERS
 template <typename T, int BC, int BP, int WC, int WP, int KV, int D, int MINB, bool VEC>
-static hipError_t launch_cfg(const ConvArgs& a, int num_cu, hipStream_t s, int* kernel_id) {
-  if (kernel_id) *kernel_id = conv_kernel_id(BC, BP, VEC);
+static hipError_t launch_cfg(const ConvArgs& a, int num_cu, hipStream_t s, int* kernel_id, const ConvTiming& tm) {
+  if (kernel_id) *kernel_id = conv_kernel_id(BC, BP, KV, MINB, VEC);
   const long long M = (long long)a.n * a.Ho * a.Wo;
   const long long tiles = ((M + BP - 1) / BP) * ((a.Cout + BC - 1) / BC);
   if (tiles <= 0) return hipSuccess;
   long long grid = tiles;
   const long long cap = (long long)num_cu * MINB;
   if (grid > cap) grid = cap;
-  hipLaunchKernelGGL((conv_mfma_kernel<T, BC, BP, WC, WP, KV, D, MINB, VEC>), dim3((unsigned)grid), dim3(THREADS), 0, s, a);
+  // with timing events the dispatch itself carries them, so their difference is the kernel's own run time
+  if (tm.start && tm.stop)
+    hipExtLaunchKernelGGL((conv_mfma_kernel<T, BC, BP, WC, WP, KV, D, MINB, VEC>), dim3((unsigned)grid), dim3(THREADS), 0, s, tm.start, tm.stop, 0, a);
+  else
+    hipLaunchKernelGGL((conv_mfma_kernel<T, BC, BP, WC, WP, KV, D, MINB, VEC>), dim3((unsigned)grid), dim3(THREADS), 0, s, a);
   return hipGetLastError();
 }
 
 template <typename T>
-static hipError_t launch_typed(const ConvArgs& a, int num_cu, hipStream_t s, int* kernel_id) {
+static hipError_t launch_typed(const ConvArgs& a, int num_cu, hipStream_t s, int* kernel_id, const ConvTiming& tm) {
   constexpr int VN = Elem<T>::N;
   const bool vec = (a.Cin % VN == 0) && (a.x_ld % VN == 0) && (a.x_coff % VN == 0) && (((uintptr_t)a.x & 15) == 0) &&
                    a.kh <= 15 && a.kw <= 15;
@@ -401,18 +407,18 @@ static hipError_t launch_typed(const ConvArgs& a, int num_cu, hipStream_t s, int
   auto tiles = [&](int bc, int bp) { return ((M + bp - 1) / bp) * ((a.Cout + bc - 1) / bc); };
   if (!vec) {
     // element-wise gather (first layers with 3 input channels)
-    if (a.Cout <= 32) return launch_cfg<T, 32, 128, 1, 4, 4, 2, 2, false>(a, num_cu, s, kernel_id);
-    return launch_cfg<T, 64, 128, 2, 2, 4, 2, 2, false>(a, num_cu, s, kernel_id);
+    if (a.Cout <= 32) return launch_cfg<T, 32, 128, 1, 4, 4, 2, 2, false>(a, num_cu, s, kernel_id, tm);
+    return launch_cfg<T, 64, 128, 2, 2, 4, 2, 2, false>(a, num_cu, s, kernel_id, tm);
   }
   // Tile choice (measured on MI355X): the widest tile whose tile count still covers the chip; K steps of 128 bytes
   // when the padded reduction length allows it; small tiles at high occupancy for layers with few output pixels.
-  if (a.Cout <= 32) return launch_cfg<T, 32, 128, 1, 4, 4, 2, 4, true>(a, num_cu, s, kernel_id);
-  if (a.Cout >= 128 && tiles(128, 128) >= num_cu) return launch_cfg<T, 128, 128, 2, 2, 4, 2, 2, true>(a, num_cu, s, kernel_id);
+  if (a.Cout <= 32) return launch_cfg<T, 32, 128, 1, 4, 4, 2, 4, true>(a, num_cu, s, kernel_id, tm);
+  if (a.Cout >= 128 && tiles(128, 128) >= num_cu) return launch_cfg<T, 128, 128, 2, 2, 4, 2, 2, true>(a, num_cu, s, kernel_id, tm);
   if (tiles(64, 128) >= num_cu / 2) {
-    if (sizeof(T) == 2 && a.Kp % (16 * VN) == 0) return launch_cfg<T, 64, 128, 2, 2, 8, 2, 2, true>(a, num_cu, s, kernel_id);
-    return launch_cfg<T, 64, 128, 2, 2, 4, 2, 3, true>(a, num_cu, s, kernel_id);
+    if (sizeof(T) == 2 && a.Kp % (16 * VN) == 0) return launch_cfg<T, 64, 128, 2, 2, 8, 2, 2, true>(a, num_cu, s, kernel_id, tm);
+    return launch_cfg<T, 64, 128, 2, 2, 4, 2, 3, true>(a, num_cu, s, kernel_id, tm);
   }
-  return launch_cfg<T, 64, 64, 2, 2, 4, 2, 4, true>(a, num_cu, s, kernel_id);
+  return launch_cfg<T, 64, 64, 2, 2, 4, 2, 4, true>(a, num_cu, s, kernel_id, tm);
 }
 
 // Checks the limits the kernel relies on and fills the precomputed reciprocals.
@@ -438,13 +444,13 @@ bool conv_prepare(ConvArgs& a, int dtype) {
   return true;
 }
 
-hipError_t launch_conv(int dtype, const ConvArgs& a0, int num_cu, hipStream_t s, int* kernel_id) {
+hipError_t launch_conv(int dtype, const ConvArgs& a0, int num_cu, hipStream_t s, int* kernel_id, ConvTiming tm) {
   ConvArgs a = a0;
   if (!conv_prepare(a, dtype)) return hipErrorInvalidValue;
   switch (dtype) {
-    case OCTO_F16: return launch_typed<_Float16>(a, num_cu, s, kernel_id);
-    case OCTO_BF16: return launch_typed<__bf16>(a, num_cu, s, kernel_id);
-    case OCTO_F32: return launch_typed<float>(a, num_cu, s, kernel_id);
+    case OCTO_F16: return launch_typed<_Float16>(a, num_cu, s, kernel_id, tm);
+    case OCTO_BF16: return launch_typed<__bf16>(a, num_cu, s, kernel_id, tm);
+    case OCTO_F32: return launch_typed<float>(a, num_cu, s, kernel_id, tm);
   }
   return hipErrorInvalidValue;
 }

@@ -41,6 +41,7 @@ struct LayerPlan {
   int K = 0, Kp = 0, cout_pad = 0;
   std::vector<int> copy_inputs;   // concat: inputs that could not be aliased into the output buffer
   double flops = 0, bytes = 0;    // per item
+  double weight_bytes = 0;        // per launch
   int kernel_id = KID_NONE;       // which kernel the last launch of this layer used
   // First layer on a 3-channel input: run on the pixel-pair view of the 4-channel-padded input (two neighbouring
   // pixels = one 16-byte vector of 8 values), i.e. as a conv with 8 input channels, kernel width pair_kw, horizontal
@@ -182,8 +183,9 @@ octo_status plan_shapes(ModelPlan& m, std::string& why) {
         } else if (L.n_in != 1 || L.res_mode != OCTO_RES_NONE) { why = "conv inputs"; return OCTO_EINVAL; }
         lp.flops = 2.0 * y.h * y.w * L.cout * x.c * kh * kw;
         const int es = dtype_size(d.dtype);
-        lp.bytes = (double)es * ((double)x.h * x.w * x.c + (double)L.cout * kh * kw * x.c) + (double)(y.f32 ? 4 : es) * y.h * y.w * y.c +
+        lp.bytes = (double)es * x.h * x.w * x.c + (double)(y.f32 ? 4 : es) * y.h * y.w * y.c +
                    (L.n_in == 2 ? (double)es * y.h * y.w * y.c : 0.0);
+        lp.weight_bytes = (double)es * L.cout * kh * kw * x.c + 4.0 * L.cout;
         break;
       }
       case OCTO_MAXPOOL:
@@ -405,7 +407,7 @@ octo_status pack_weights(octo_pipeline* p, ModelPlan& m, Arena& ar) {
 }
 
 // ---- one layer ----------------------------------------------------------------
-hipError_t run_layer(octo_pipeline* p, ModelPlan& m, int i, int n, const int* n_dyn, hipStream_t s) {
+hipError_t run_layer(octo_pipeline* p, ModelPlan& m, int i, int n, const int* n_dyn, hipStream_t s, ConvTiming tm = ConvTiming()) {
   LayerPlan& lp = m.layers[i];
   const octo_layer& L = lp.L;
   const TensorView x = view_of(m, L.in[0]);
@@ -420,7 +422,7 @@ hipError_t run_layer(octo_pipeline* p, ModelPlan& m, int i, int n, const int* n_
       if (lp.pair_view) { a.W = x.w / 2; a.Cin = 8; a.x_ld = 8; a.kw = lp.pair_kw; a.stride_w = 1; a.pad_w = lp.pair_pad; }
       a.act = L.act; a.res_mode = L.res_mode; a.out_f32 = m.tensors[i + 1].f32 ? 1 : 0;
       if (L.n_in == 2) { const TensorView r = view_of(m, L.in[1]); a.res = r.ptr; a.res_ld = r.ld; a.res_coff = r.coff; }
-      return launch_conv(m.d.dtype, a, p->num_cu, s, &lp.kernel_id);
+      return launch_conv(m.d.dtype, a, p->num_cu, s, &lp.kernel_id, tm);
     }
     case OCTO_MAXPOOL: {
       PoolArgs a{x.ptr, y.ptr, n_dyn, n, x.h, x.w, x.c, x.ld, x.coff, y.h, y.w, y.ld, y.coff, L.kh, L.stride, L.pad};
@@ -463,9 +465,13 @@ hipError_t run_layer(octo_pipeline* p, ModelPlan& m, int i, int n, const int* n_
 
 hipError_t run_layers(octo_pipeline* p, ModelPlan& m, int n, const int* n_dyn, hipStream_t s, std::vector<hipEvent_t>* evs = nullptr) {
   hipError_t e;
+  // timing events: [0..L] bracket the layers on the stream; [L+1+2i], [L+2+2i] ride on layer i's convolution dispatch
+  const int L = (int)m.layers.size();
   if (evs && (e = hipEventRecord((*evs)[0], s)) != hipSuccess) return e;
-  for (int i = 0; i < (int)m.layers.size(); ++i) {
-    if ((e = run_layer(p, m, i, n, n_dyn, s)) != hipSuccess) return e;
+  for (int i = 0; i < L; ++i) {
+    ConvTiming tm;
+    if (evs) { tm.start = (*evs)[L + 1 + 2 * i]; tm.stop = (*evs)[L + 2 + 2 * i]; }
+    if ((e = run_layer(p, m, i, n, n_dyn, s, tm)) != hipSuccess) return e;
     if (evs && (e = hipEventRecord((*evs)[i + 1], s)) != hipSuccess) return e;
   }
   return hipSuccess;
@@ -637,7 +643,7 @@ octo_status start_batch(octo_pipeline* p, hipStream_t s, int* launched) {
   b.layer_ev.resize(p->models.size());
   if (p->layer_timing)
     for (size_t k = 0; k < p->models.size(); ++k)
-      for (size_t i = 0; i <= p->models[k].layers.size(); ++i) {
+      for (size_t i = 0; i < 3 * p->models[k].layers.size() + 1; ++i) {
         hipEvent_t e = get_event(p); if (!e) return fail(p, OCTO_EHIP, "hipEventCreate failed"); b.layer_ev[k].push_back(e);
       }
   p->inflight.push_back(std::move(b));
@@ -888,9 +894,14 @@ octo_status octo_collect(octo_pipeline* p, octo_frame_result* frames, int32_t fr
     p->last_layer_ms.assign(p->models.size(), std::vector<float>());
     for (size_t k = 0; k < B.layer_ev.size(); ++k) {
       const std::vector<hipEvent_t>& le = B.layer_ev[k];
-      for (size_t i = 0; i + 1 < le.size(); ++i) {
+      const size_t L = p->models[k].layers.size();
+      for (size_t i = 0; i < L && le.size() == 3 * L + 1; ++i) {
+        // convolutions: the kernel's own run time from the events on its dispatch; other layers: stream bracket
+        const bool conv = p->models[k].layers[i].L.op == OCTO_CONV || p->models[k].layers[i].L.op == OCTO_FC;
         float ms = 0.f;
-        if (!B.model_ran[k] || hipEventElapsedTime(&ms, le[i], le[i + 1]) != hipSuccess) ms = 0.f;
+        if (!B.model_ran[k]) ms = 0.f;
+        else if (conv && hipEventElapsedTime(&ms, le[L + 1 + 2 * i], le[L + 2 + 2 * i]) == hipSuccess) {}
+        else if (hipEventElapsedTime(&ms, le[i], le[i + 1]) != hipSuccess) ms = 0.f;
         p->last_layer_ms[k].push_back(ms);
       }
       for (hipEvent_t e : le) p->event_pool.push_back(e);
@@ -940,7 +951,7 @@ octo_status octo_set_layer_timing(octo_pipeline* p, int32_t enable) {
 }
 
 octo_status octo_get_layer_info(octo_pipeline* p, int32_t model, float* ms, int32_t* kernel_id, double* flops, double* bytes,
-                                int32_t cap, int32_t* n) {
+                                double* weight_bytes, int32_t cap, int32_t* n) {
   if (!p) return OCTO_EINVAL;
   if (model < 0 || model >= (int)p->models.size() || !n || cap < 0) return fail(p, OCTO_EINVAL, "bad arguments");
   const ModelPlan& m = p->models[model];
@@ -950,6 +961,7 @@ octo_status octo_get_layer_info(octo_pipeline* p, int32_t model, float* ms, int3
     if (kernel_id) kernel_id[i] = m.layers[i].kernel_id;
     if (flops) flops[i] = m.layers[i].flops;
     if (bytes) bytes[i] = m.layers[i].bytes;
+    if (weight_bytes) weight_bytes[i] = m.layers[i].weight_bytes;
   }
   return OCTO_OK;
 }
@@ -974,7 +986,7 @@ octo_status octo_profile_layers(octo_pipeline* p, int32_t model, int32_t n, int3
     HIPCHK(p, hipEventElapsedTime(&t, e0, e1));
     ms[i] = t / iters;
     if (flops) flops[i] = m.layers[i].flops * n;
-    if (bytes) bytes[i] = m.layers[i].bytes * n;
+    if (bytes) bytes[i] = m.layers[i].bytes * n + m.layers[i].weight_bytes;
   }
   hipEventDestroy(e0); hipEventDestroy(e1);
   return OCTO_OK;
