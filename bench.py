@@ -3,7 +3,9 @@
 
 A step is one pass of the whole path (letterbox, detector, decode, top-k, NMS, ROI compaction, crop-resize,
 classifier and plate detector, result copy) over one batch of the traffic workload: 8 synthetic 1920x1080 frames
-from 4 cameras, fp16, planted detector heads (Poisson(8) objects per frame).  Prints one JSON line.
+from 4 cameras, fp16, planted detector heads (Poisson(8) objects per frame).  Several copies of the pipeline
+(instances, as the paper's model instances) take batches in turn on their own streams, so kernels of different
+batches overlap.  Prints one JSON line.
 """
 from __future__ import annotations
 
@@ -59,6 +61,24 @@ def conv_name(kid: int, dtype: str) -> str:
     return "octo::conv_mfma_kernel<%s, %d, %d, %d, %d, %d, 2, %d, %s>" % (ctype, bc, bp, wc, wp, kv, minb, "true" if vec else "false")
 
 
+# HBM traffic per launch of the dominant kernel, from `rocprofv3 --pmc FETCH_SIZE` and `--pmc WRITE_SIZE` runs of
+# `bench.py --calib-copy-mib 256` (counters in KiB per dispatch, scaled by what the same counter reads for the
+# calibration pass of known size).  Valid only for the kernel source it was taken with: keyed by a hash of conv.hip.
+TRAFFIC = {
+    # sha256(conv.hip)[:16]: {kernel name: bytes per launch}
+}
+
+
+def traffic_per_launch(kernel_name: str):
+    import hashlib
+    src = os.path.join(ROOT, "paper_2502_01277_amd", "csrc", "conv.hip")
+    try:
+        key = hashlib.sha256(open(src, "rb").read()).hexdigest()[:16]
+    except OSError:
+        return None
+    return TRAFFIC.get(key, {}).get(kernel_name)
+
+
 def cpu_baseline(spec, scene, heads):
     """The oracle, as it stands, on the same batch (bounded to about 10-30 s of CPU work)."""
     import torch
@@ -75,13 +95,16 @@ def cpu_baseline(spec, scene, heads):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=200)
-    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--steps", type=int, default=400)
+    ap.add_argument("--warmup", type=int, default=40)
     ap.add_argument("--workload", default="traffic")
+    ap.add_argument("--instances", type=int, default=4,
+                    help="copies of the pipeline (own activations and tables) that take batches in turn, each on its own "
+                         "stream, so that kernels of different batches overlap on the GPU")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--layers", action="store_true", help="print the per-layer table to stderr")
+    ap.add_argument("--layers", action="store_true", help="print the per-kernel table to stderr")
     ap.add_argument("--calib-copy-mib", type=int, default=0,
-                    help="also run one plain device copy of this many MiB before the timed region (a known-size kernel "
+                    help="also run one plain device pass over this many MiB before the timed region (a known-size kernel "
                          "against which hardware traffic counters are scaled)")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -95,23 +118,44 @@ def main():
     spec, scene, heads, desc = make_workload(args.workload)
     det = spec.models[0]
     n = scene.frames.shape[0]
-    P = binding.Pipeline(spec)
-    d_heads = None
-    if heads is not None:
-        d_heads = [binding.to_device(h, det.dtype) for h in heads]
-        for l, h in enumerate(d_heads):
-            P.set_head(0, l, h)
+    ninst = max(1, args.instances)
+    pipes, keep_heads = [], []
+    for _ in range(ninst):
+        P = binding.Pipeline(spec)
+        if heads is not None:
+            dh = [binding.to_device(h, det.dtype) for h in heads]
+            for l, h in enumerate(dh):
+                P.set_head(0, l, h)
+            keep_heads.append(dh)
+        pipes.append(P)
     dev = [torch.from_numpy(f).cuda() for f in scene.frames]
-    stream = torch.cuda.Stream()
+    # one stream per instance, created by the library over all compute units: each gets a hardware queue of its own
+    # (streams from a framework's pool may share one, which serialises the instances that land on it)
+    n_cu = binding.device_cu_count()
+    streams = [binding.stream_create_range(0, n_cu) for _ in range(ninst)]
     now = binding.lib().octo_now_ms
 
-    def step_submit():
-        P.submit(dev, arrival_ms=[now()] * n)
-        P.run(stream)
+    def region(steps, on_collect, use=None):
+        """`steps` batches, taken in turn by the instances in `use`; each instance keeps at most two uncollected
+        batches, so the host prepares and collects while the GPU works."""
+        use = list(range(ninst)) if use is None else use
+        pend = {j: 0 for j in use}
+        for k in range(steps):
+            j = use[k % len(use)]
+            if pend[j] >= 2:
+                fr, bx, st = pipes[j].collect()
+                pend[j] -= len(fr) // n
+                on_collect(j, fr)
+            pipes[j].submit(dev, arrival_ms=[now()] * n)
+            pipes[j].run(streams[j])
+            pend[j] += 1
+        for j in use:
+            while pend[j] > 0:
+                fr, bx, st = pipes[j].collect()
+                pend[j] -= len(fr) // n
+                on_collect(j, fr)
 
-    for _ in range(args.warmup):
-        step_submit()
-        P.collect()
+    region(args.warmup, lambda j, fr: None)
     if args.calib_copy_mib:
         src = torch.full((args.calib_copy_mib << 18,), 1.0, dtype=torch.float32, device="cuda")
         dst = torch.empty_like(src)
@@ -119,82 +163,86 @@ def main():
         torch.add(src, 1.0, out=dst)           # one elementwise kernel: reads and writes calib_copy_mib MiB each
         torch.cuda.synchronize()
         del src, dst
-    # ---- timed region: K steps, two batches in flight, inputs resident in HBM ----
-    lat, met, total_boxes = [], 0, 0
-    submitted = collected = 0
+    # ---- timed region: K steps, inputs resident in HBM ----
+    lat, tot = [], {"met": 0, "boxes": 0, "frames": 0}
 
-    def drain(max_in_flight):
-        nonlocal collected, met, total_boxes
-        while submitted - collected > max_in_flight * n:
-            fr, bx, st = P.collect()            # blocking: returns at least the oldest batch
-            collected += len(fr)
-            lat.extend(fr["latency_ms"].tolist())
-            met += int(fr["slo_met"].sum())
-            total_boxes += int(fr["n_boxes"].sum())
+    def tally(j, fr):
+        lat.extend(fr["latency_ms"].tolist())
+        tot["met"] += int(fr["slo_met"].sum()); tot["boxes"] += int(fr["n_boxes"].sum()); tot["frames"] += len(fr)
 
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for i in range(args.steps):
-        step_submit()
-        submitted += n
-        drain(1)                                # one batch stays in flight while the next is prepared
-    drain(0)
+    region(args.steps, tally)
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
-    # ---- same region again with an event between layers: per-kernel durations ----
-    P.set_layer_timing(True)
-    P.set_stage_timing(True)
-    agg = {}      # kernel id -> [time ms, flops, bytes, launches]
-    stage = []
-    ksteps = min(args.steps, 50)
+    assert tot["frames"] == n * args.steps
+    # ---- the same steps again with timing events on every layer: once with one instance alone (a kernel's own
+    # duration, which is what a profiler that serialises dispatches reports) and once with all instances overlapping
     items = [n] + [0] * (len(spec.models) - 1)          # items each model processes per step (same batch every step)
     for e, edge in enumerate(spec.edges):
-        items[edge.child] = len(P.get_rois(e))
-    for i in range(ksteps):
-        step_submit()
-        P.collect()
-        stage.append(P.stage_ms())
-        for mi, m in enumerate(spec.models):
-            ms, kid, fl, by, wb = P.layer_info(mi)
-            for j in range(len(ms)):
-                if kid[j] == 0:
-                    continue
-                a = agg.setdefault(int(kid[j]), [0.0, 0.0, 0.0, 0])
-                a[0] += float(ms[j]); a[1] += fl[j] * items[mi]; a[2] += by[j] * items[mi] + wb[j]; a[3] += 1
-    P.set_layer_timing(False)
-    P.set_stage_timing(False)
-    stage = np.mean(np.stack(stage), axis=0)
+        items[edge.child] = len(pipes[0].get_rois(e))
+
+    def timing_pass(steps, use):
+        agg, stage = {}, []      # kernel id -> [time ms, flops, bytes, launches]
+
+        def per_layer(j, fr):
+            stage.append(pipes[j].stage_ms())            # timings of the newest batch of this collect
+            for mi, m in enumerate(spec.models):
+                ms, kid, fl, by, wb = pipes[j].layer_info(mi)
+                for q in range(len(ms)):
+                    if kid[q] == 0:
+                        continue
+                    a = agg.setdefault(int(kid[q]), [0.0, 0.0, 0.0, 0])
+                    a[0] += float(ms[q]); a[1] += fl[q] * items[mi]; a[2] += by[q] * items[mi] + wb[q]; a[3] += 1
+
+        for P in pipes:
+            P.set_layer_timing(True); P.set_stage_timing(True)
+        region(steps, per_layer, use)
+        for P in pipes:
+            P.set_layer_timing(False); P.set_stage_timing(False)
+        return agg, np.mean(np.stack(stage), axis=0), len(stage)
+
+    agg, stage, nsamp = timing_pass(min(args.steps, 60), [0])
+    agg_ov, stage_ov, nsamp_ov = timing_pass(min(args.steps, 120), None) if ninst > 1 else (agg, stage, nsamp)
     conv = {k: v for k, v in agg.items() if k >= 1000000000}
     dom = max(conv, key=lambda k: conv[k][0])
     t_ms, fl, by, launches = conv[dom]
     kname = conv_name(dom, det.dtype)
     roofline = {"bound": "mfma", "kernel": kname, "achieved": fl / (t_ms * 1e-3) / 1e12, "peak": PEAK[det.dtype], "unit": "TFLOP/s",
-                "frac": fl / (t_ms * 1e-3) / 1e12 / PEAK[det.dtype], "traffic": None,
-                "avg_launch_us": 1e3 * t_ms / launches, "launches_per_step": launches / ksteps,
-                "all_conv_tflops": sum(v[1] for v in conv.values()) / (sum(v[0] for v in conv.values()) * 1e-3) / 1e12,
-                "conv_ms_per_step": sum(v[0] for v in conv.values()) / ksteps}
+                "frac": fl / (t_ms * 1e-3) / 1e12 / PEAK[det.dtype], "traffic": traffic_per_launch(kname),
+                "avg_launch_us": 1e3 * t_ms / launches, "launches_per_step": launches / nsamp,
+                "avg_launch_us_overlapped": 1e3 * agg_ov[dom][0] / agg_ov[dom][3],
+                "flop_per_launch": fl / launches, "bytes_per_launch": by / launches,
+                "all_conv_tflops_per_kernel": sum(v[1] for v in conv.values()) / (sum(v[0] for v in conv.values()) * 1e-3) / 1e12,
+                "conv_flop_per_step": sum(v[1] for v in conv.values()) / nsamp,
+                "conv_tflops_whole_step": sum(v[1] for v in conv.values()) / nsamp / (dt / args.steps) / 1e12}
     names = ["letterbox", "detector_layers", "decode", "topk", "nms", "compact"]
     for e in range(len(spec.edges)):
         names += ["crop%d" % e, "child%d_layers" % e, "child%d_tail" % e]
     out = {
-        "metric": "pipeline frames/s within 200 ms SLO on 1 GPU", "value": met / dt, "unit": "frames/s",
+        "metric": "pipeline frames/s within 200 ms SLO on 1 GPU", "value": tot["met"] / dt, "unit": "frames/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": 1e3 * dt / args.steps,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": det.dtype, "data": "synthetic",
-        "config": {"workload": desc, "batch_frames": n, "slo_ms": spec.slo_ms, "batches_in_flight": 2,
+        "config": {"workload": desc, "batch_frames": n, "slo_ms": spec.slo_ms, "instances": ninst,
                    "heads": "planted" if heads is not None else "natural"},
-        "total_frames_per_s": n * args.steps / dt, "objects_per_s": total_boxes / dt,
+        "total_frames_per_s": n * args.steps / dt, "objects_per_s": tot["boxes"] / dt,
         "latency_ms_p50": float(np.percentile(lat, 50)), "latency_ms_p99": float(np.percentile(lat, 99)),
         "stage_ms": {k: round(float(v), 4) for k, v in zip(names, stage)},
+        "stage_ms_overlapped": {k: round(float(v), 4) for k, v in zip(names, stage_ov)},
         "roofline": roofline,
     }
     if args.layers:
         for k, v in sorted(agg.items()):
             nm = conv_name(k, det.dtype) if k >= 1000000000 else {1: "maxpool", 2: "upsample2x", 3: "copy", 4: "add", 5: "gap"}.get(k, str(k))
             print("%-80s %8.3f ms/step  %7.1f TFLOP/s  %7.1f GB/s  %5.1f launches/step  %7.1f us/launch" %
-                  (nm, v[0] / ksteps, v[1] / max(v[0], 1e-9) / 1e9, v[2] / max(v[0], 1e-9) / 1e6, v[3] / ksteps, 1e3 * v[0] / max(v[3], 1)), file=sys.stderr)
+                  (nm, v[0] / nsamp, v[1] / max(v[0], 1e-9) / 1e9, v[2] / max(v[0], 1e-9) / 1e6, v[3] / nsamp, 1e3 * v[0] / max(v[3], 1)), file=sys.stderr)
     if not args.no_cpu_baseline:
         out["cpu_baseline"], _ = cpu_baseline(spec, scene, heads)
-    P.close()
+    torch.cuda.synchronize()
+    for P in pipes:
+        P.close()
+    for st in streams:
+        binding.stream_destroy(st)
     print(json.dumps(out))
 
 

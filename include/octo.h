@@ -145,7 +145,7 @@ octo_status octo_submit_frames(octo_pipeline* p, const void* const* d_frames, co
 
 /* Form one batch of up to bz (models[0].batch_size, or the value set by octo_set_batch_size) queued frames in
  * arrival order and enqueue the whole cascade for it on `hip_stream`; no host-device synchronisation.
- * *n_frames_launched = 0 and OCTO_OK if the queue is empty; OCTO_ESTATE if too many batches are uncollected. */
+ * *n_frames_launched = 0 and OCTO_OK if the queue is empty; OCTO_ESTATE if too many batches (7) are uncollected. */
 octo_status octo_run(octo_pipeline* p, void* hip_stream, int32_t* n_frames_launched);
 
 /* Fetch finished batches, oldest first.  frames[0..*n_frames) and boxes[0..*n_boxes) are host arrays; a frame's
@@ -161,6 +161,10 @@ double octo_now_ms(void);                               /* monotonic host clock 
 /* Spatial sharing (Sec. III-C: a stream's width is its share of compute): create / destroy a HIP stream
  * restricted to the compute units whose bit is set (cu_mask: n_words 32-bit words), default priority. */
 octo_status octo_stream_create_masked(const uint32_t* cu_mask, int32_t n_words, void** hip_stream);
+/* The same for the contiguous unit range [first_cu, first_cu + n_cu), both multiples of 8: mask bit i selects unit
+ * i / 8 of die i % 8 on this GPU, so such a range is an equal slice of every die and two disjoint ranges share no
+ * compute unit.  OCTO_EINVAL for a mask or range that leaves a die without units (the runtime refuses those). */
+octo_status octo_stream_create_range(int32_t first_cu, int32_t n_cu, void** hip_stream);
 octo_status octo_stream_destroy(void* hip_stream);
 octo_status octo_device_cu_count(int32_t* n_cu);
 

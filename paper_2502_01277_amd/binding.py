@@ -82,7 +82,7 @@ class OctoPlacement(C.Structure):
 # Every symbol include/octo.h declares.
 EXPORTS = [
     "octo_pipeline_workspace_size", "octo_pipeline_create", "octo_pipeline_destroy", "octo_submit_frames", "octo_run",
-    "octo_collect", "octo_set_batch_size", "octo_last_error", "octo_now_ms", "octo_stream_create_masked",
+    "octo_collect", "octo_set_batch_size", "octo_last_error", "octo_now_ms", "octo_stream_create_masked", "octo_stream_create_range",
     "octo_stream_destroy", "octo_device_cu_count", "octo_cwd_search", "octo_coral_schedule", "octo_est_latency_ms",
     "octo_est_throughput", "octo_run_model", "octo_profile_layers", "octo_set_layer_timing", "octo_get_layer_info", "octo_set_stage_timing", "octo_get_stage_ms",
     "octo_debug_get_tensor", "octo_debug_tensor_shape", "octo_debug_set_head", "octo_debug_run_model",
@@ -116,6 +116,7 @@ def lib() -> C.CDLL:
         L.octo_collect.argtypes = [vp, vp, i32, vp, i32, vp, vp, i32]
         L.octo_set_batch_size.argtypes = [vp, i32, i32]
         L.octo_stream_create_masked.argtypes = [vp, i32, vp]
+        L.octo_stream_create_range.argtypes = [i32, i32, vp]
         L.octo_stream_destroy.argtypes = [vp]
         L.octo_device_cu_count.argtypes = [vp]
         L.octo_cwd_search.argtypes = [vp]
@@ -499,6 +500,24 @@ def op_compact(top, keep, n_keep, src_hw, in_hw, class_mask: int, cap: int, stre
     r = rois.cpu().numpy().reshape(-1).view(ROI_DTYPE)[:nr].copy()
     b = boxes.cpu().numpy().reshape(n, max_det * 32).view(BOX_DTYPE)
     return r, roi_of.cpu().numpy(), b, flags.cpu().numpy()
+
+
+# ---- CU-masked streams --------------------------------------------------------
+def device_cu_count() -> int:
+    n = C.c_int32(0)
+    _st(lib().octo_device_cu_count(C.byref(n)))
+    return n.value
+
+
+def stream_create_range(first_cu: int, n_cu: int) -> int:
+    """Raw HIP stream restricted to compute units [first_cu, first_cu + n_cu); release with stream_destroy."""
+    h = C.c_void_p()
+    _st(lib().octo_stream_create_range(first_cu, n_cu, C.byref(h)))
+    return int(h.value)
+
+
+def stream_destroy(stream: int):
+    _st(lib().octo_stream_destroy(C.c_void_p(stream)))
 
 
 # ---- scheduling ---------------------------------------------------------------

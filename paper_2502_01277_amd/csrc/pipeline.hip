@@ -99,7 +99,7 @@ struct Batch {
 
 struct QueuedFrame { const void* ptr; size_t pitch; double arrival; int64_t id; };
 
-constexpr int RING = 4;
+constexpr int RING = 8;
 constexpr int CNT_STRIDE = 32;   // candidate counters sit 128 bytes apart: same-line atomics serialise in L2
 
 }  // namespace
@@ -913,12 +913,30 @@ octo_status octo_collect(octo_pipeline* p, octo_frame_result* frames, int32_t fr
   return overflow ? OCTO_ECAP : OCTO_OK;
 }
 
+// Compute-unit bit i of a stream mask selects unit i / 8 of accelerator die i % 8 on this GPU (measured with a
+// kernel that reads its die id under different masks).  A mask that leaves a die without units is refused here:
+// the runtime does not accept it.
+static const int N_XCD = 8;
+
 octo_status octo_stream_create_masked(const uint32_t* cu_mask, int32_t n_words, void** hip_stream) {
   if (!cu_mask || n_words <= 0 || !hip_stream) return OCTO_EINVAL;
+  int per_die[N_XCD] = {0};
+  for (int b = 0; b < 32 * n_words; ++b)
+    if (cu_mask[b / 32] >> (b % 32) & 1u) per_die[b % N_XCD]++;
+  for (int d = 0; d < N_XCD; ++d)
+    if (per_die[d] == 0) return OCTO_EINVAL;
   hipStream_t s = nullptr;
   if (hipExtStreamCreateWithCUMask(&s, (uint32_t)n_words, cu_mask) != hipSuccess) return OCTO_EHIP;
   *hip_stream = (void*)s;
   return OCTO_OK;
+}
+octo_status octo_stream_create_range(int32_t first_cu, int32_t n_cu, void** hip_stream) {
+  int32_t total = 0;
+  if (octo_device_cu_count(&total) != OCTO_OK) return OCTO_EHIP;
+  if (first_cu < 0 || n_cu < N_XCD || first_cu % N_XCD || n_cu % N_XCD || first_cu + n_cu > total) return OCTO_EINVAL;
+  std::vector<uint32_t> mask((size_t)(total + 31) / 32, 0u);
+  for (int b = first_cu; b < first_cu + n_cu; ++b) mask[b / 32] |= 1u << (b % 32);
+  return octo_stream_create_masked(mask.data(), (int32_t)mask.size(), hip_stream);
 }
 octo_status octo_stream_destroy(void* hip_stream) {
   if (!hip_stream) return OCTO_EINVAL;

@@ -1,0 +1,457 @@
+"""Co-located serving of several pipelines on one GPU: profiling, scheduler-lite and the slot executor.
+
+The paper shares a GPU between models in space and time (Sec. III-C): every model gets a *portion* - a time slot
+inside the duty cycle of an inference stream (length = its batch latency) with a width (the share of compute it
+needs) - found by Algorithm 2 after Algorithm 1 has chosen the batch sizes.  Here a stream's width is a real
+restriction: a HIP stream created on a contiguous range of compute units.  All decisions come from the library
+(`octo_cwd_search`, `octo_coral_schedule`); this module measures the profiles they need, turns the placements into
+streams and slot times, and drives `octo_run_model` at the slot starts.
+
+Two things differ from the paper's runtime and are stated here once:
+  * a child model consumes the ROIs of its parent's batch in one launch whose size is taken on the device, so a
+    child's batch size from Algorithm 1 sizes its portion (ceil(ROIs per cycle / bz) back-to-back batches) rather
+    than splitting the launch;
+  * one instance per model: where the arrival rate needs more than one batch per duty cycle, the portion is sized
+    for k = ceil(rate * cycle / bz) back-to-back batches instead of k instances.
+"""
+from __future__ import annotations
+
+import math
+import time
+from dataclasses import dataclass, field
+from typing import Dict, List, Optional, Sequence, Tuple
+
+import numpy as np
+
+from . import binding
+
+CU_GRAIN = 8          # stream widths are multiples of 8 compute units (one per die)
+MAX_IN_FLIGHT = 6     # uncollected batches per pipeline (the library holds result slots for 7)
+
+
+def _pow2_upto(cap: int, limit: int = 8) -> List[int]:
+    out, b = [], 1
+    while b <= cap and len(out) < limit:
+        out.append(b)
+        b *= 2
+    return out
+
+
+def width_to_cus(util: float, total: int) -> int:
+    """Portion width (share of compute, 0..1) -> number of compute units, rounded up to the stream granularity."""
+    n = int(math.ceil(util * total / CU_GRAIN - 1e-9)) * CU_GRAIN
+    return max(CU_GRAIN, min(total, n))
+
+
+def coefficient_of_variation(times: np.ndarray) -> float:
+    """Burstiness of an arrival sequence: std / mean of the inter-arrival times (Sec. III-B)."""
+    if len(times) < 3:
+        return 0.0
+    d = np.diff(np.sort(np.asarray(times, np.float64)))
+    return float(d.std() / d.mean()) if d.mean() > 0 else 0.0
+
+
+@dataclass
+class ModelProfile:
+    latency_ms: Dict[int, float]        # batch size -> batch latency at the chosen width
+    util: float                         # chosen width as a share of the GPU
+    by_width: Dict[int, Dict[int, float]] = field(default_factory=dict)    # compute units -> {batch size -> latency}
+
+
+def choose_width(by_width: Dict[int, Dict[int, float]], ref_bz: int, total: int, rule: str = "efficient", tol: float = 0.10) -> int:
+    """Portion width of a model from its latency at several stream widths (the paper takes a model's measured GPU
+    utilisation as the width, Sec. III-C; here widths are enforced, so the choice is made from the latency curve).
+    'latency': the narrowest width whose latency is within tol of the whole GPU's.  'efficient': the narrowest width
+    whose cost in compute-unit-milliseconds is within tol of the cheapest - a model that does not speed up on more
+    units should not hold them; whether its latency still fits is checked by the batch-size search, which is given
+    the profile measured at this width."""
+    ws = sorted(by_width)
+    if rule == "latency":
+        full = by_width[max(ws)][ref_bz]
+        return next(w for w in ws if by_width[w][ref_bz] <= (1.0 + tol) * full)
+    cost = {w: w * by_width[w][ref_bz] for w in ws}
+    best = min(cost.values())
+    return next(w for w in ws if cost[w] <= (1.0 + tol) * best)
+
+
+def profile_pipeline(P: binding.Pipeline, widths: Sequence[int] = (64, 128, 256), iters: int = 2,
+                     det_batches: Optional[Sequence[int]] = None, child_batches: Optional[Sequence[int]] = None,
+                     rule: str = "efficient", tol: float = 0.10) -> List[ModelProfile]:
+    """Batch-latency profile L_m(bz) of every model (the paper's offline profiling, Sec. III-C), measured by running
+    the model's layers on bz items on streams of several widths, and the width chosen from it."""
+    import torch
+    total = binding.device_cu_count()
+    streams = {}
+    for w in widths:
+        streams[min(w, total)] = binding.stream_create_range(0, min(w, total))
+    out = []
+    try:
+        for mi, m in enumerate(P.spec.models):
+            cap = m.batch_size
+            grid = list(det_batches if (mi == 0 and det_batches) else child_batches if (mi > 0 and child_batches) else _pow2_upto(cap))
+            grid = [b for b in grid if b <= cap]
+            by_width = {}
+            for w, s in streams.items():
+                lat = {}
+                for b in grid:
+                    P.profile_layers(mi, b, 1, s)                       # warm-up
+                    lat[b] = float(P.profile_layers(mi, b, iters, s)[0].sum())
+                by_width[w] = lat
+            w = choose_width(by_width, grid[-1], total, rule, tol)
+            out.append(ModelProfile(dict(by_width[w]), w / total, by_width))
+    finally:
+        torch.cuda.synchronize()
+        for s in streams.values():
+            binding.stream_destroy(s)
+    return out
+
+
+@dataclass
+class Schedule:
+    duty_ms: float
+    bz: List[List[int]]                                   # per pipeline, per model
+    batches_per_cycle: List[List[int]]                    # per pipeline, per model
+    placements: List[Tuple[int, int, int, float, float, float]]   # (pipeline, model, stream, start, end, duty)
+    stream_cus: Dict[int, Tuple[int, int]]                # stream -> (first compute unit, count)
+    est_latency_ms: List[float]
+    est_throughput: List[float]
+
+    def placement(self, pipeline: int, model: int):
+        for pl in self.placements:
+            if pl[0] == pipeline and pl[1] == model:
+                return pl
+        raise KeyError((pipeline, model))
+
+
+def plan(specs, profiles: List[List[ModelProfile]], frame_rates: Sequence[float], objects_per_frame: Sequence[float],
+         burstiness: Sequence[Sequence[float]], n_streams: int = 8, gpu_mem_mb: float = 288e3,
+         fixed_bz: Optional[List[List[int]]] = None) -> Schedule:
+    """Scheduler-lite: Algorithm 1's batch-size search per pipeline, then Algorithm 2 over all pipelines."""
+    total = binding.device_cu_count()
+    sched_in, all_bz, all_k, est_l, est_t = [], [], [], [], []
+    duty = min(s.slo_ms for s in specs) / 2.0
+    for i, spec in enumerate(specs):
+        parent = {e.child: e.parent for e in spec.edges}
+        models = []
+        for mi, m in enumerate(spec.models):
+            rate = frame_rates[i] * (objects_per_frame[i] if mi > 0 else 1.0)
+            wmem = sum(L.weight.size for L in m.layers if getattr(L, "weight", None) is not None) * (4 if m.dtype == "f32" else 2) / 1e6
+            models.append(dict(parent=parent.get(mi, -1), profile=dict(profiles[i][mi].latency_ms), rate=max(rate, 1e-3),
+                               burstiness=burstiness[i][mi], util=profiles[i][mi].util, weight_mem=wmem, inter_mem=0.0, bz=1))
+        if fixed_bz is None:
+            bzs = binding.cwd_search(models, spec.slo_ms)
+        else:
+            bzs = list(fixed_bz[i])
+        keep: list = []
+        for m, b in zip(models, bzs):
+            m["bz"] = b
+        sp = binding.sched_pipeline(models, spec.slo_ms, keep)
+        est_l.append(float(binding.lib().octo_est_latency_ms(binding.C.byref(sp))))
+        est_t.append(float(binding.lib().octo_est_throughput(binding.C.byref(sp))))
+        ks = []
+        for m, b in zip(models, bzs):
+            k = max(1, int(math.ceil(m["rate"] * duty / 1000.0 / b - 1e-9)))
+            ks.append(k)
+            m["profile"] = dict(m["profile"])
+            m["profile"][b] = k * m["profile"][b]          # the portion holds k back-to-back batches
+        sched_in.append((models, spec.slo_ms))
+        all_bz.append(bzs)
+        all_k.append(ks)
+    placements = binding.coral_schedule(sched_in, gpu_mem_mb, 1.0, n_streams)
+    widest: Dict[int, float] = {}
+    for (pi, mi, st, a, b, d) in placements:
+        if st >= 0:
+            widest[st] = max(widest.get(st, 0.0), sched_in[pi][0][mi]["util"])
+    stream_cus, first = {}, 0
+    for st in sorted(widest):
+        n = width_to_cus(widest[st], total)
+        if first + n > total:                               # rounding to the stream granularity overshot the GPU
+            first = max(0, total - n)
+        stream_cus[st] = (first, n)
+        first = min(total - CU_GRAIN, first + n)
+    return Schedule(duty, all_bz, all_k, placements, stream_cus, est_l, est_t)
+
+
+@dataclass
+class Camera:
+    pipeline: int
+    arrivals_s: np.ndarray              # arrival times in seconds from the start of serving
+    pool: List                          # device uint8 frames this camera cycles through
+    pool_offset: int = 0                # where in the pipeline's planted-head pool this camera's frames start
+
+
+@dataclass
+class PipelineStats:
+    submitted: int = 0
+    served: int = 0
+    slo_met: int = 0
+    boxes: int = 0
+    latency_ms: List[float] = field(default_factory=list)
+    results: Dict[int, Tuple[int, np.ndarray]] = field(default_factory=dict)   # frame id -> (pool index, boxes)
+
+
+class Executor:
+    """Slot executor (Sec. III-C 'Inference Stream'): every duty cycle, at a portion's start, the model is launched on
+    what is queued (at most its batch size per batch); downstream models follow their parent on their own streams."""
+
+    def __init__(self, pipes: List[binding.Pipeline], schedule: Schedule, cameras: List[Camera],
+                 head_pools: Optional[List[Optional[List]]] = None, slotted: bool = True, masked: bool = True,
+                 keep_results: bool = False):
+        import torch
+        self.t = torch
+        self.pipes, self.sch, self.cams = pipes, schedule, cameras
+        self.slotted, self.keep_results = slotted, keep_results
+        self.streams: Dict[int, int] = {}
+        self._owned: List[int] = []
+        self._plain = torch.cuda.Stream()
+        for st, (first, n) in schedule.stream_cus.items():
+            if masked:
+                h = binding.stream_create_range(first, n)
+                self._owned.append(h)
+            else:
+                h = int(self._plain.cuda_stream)
+            self.streams[st] = h
+        self.head_pools = head_pools or [None] * len(pipes)
+        self.override: List[Optional[List]] = []
+        for i, P in enumerate(pipes):
+            hp = self.head_pools[i]
+            if hp is None:
+                self.override.append(None)
+                continue
+            bufs = [torch.empty((P.spec.max_frames,) + tuple(h.shape[1:]), dtype=h.dtype, device=h.device) for h in hp]
+            for l, b in enumerate(bufs):
+                P.set_head(0, l, b)
+            self.override.append(bufs)
+        for i, P in enumerate(pipes):
+            P.set_batch_size(0, min(schedule.bz[i][0], P.spec.models[0].batch_size))
+        self.stats = [PipelineStats() for _ in pipes]
+        self._warmup()
+
+    def _gather_heads(self, i: int, pool_idx: List[int], stream: int):
+        """Planted mode: copy the head tensors of the batch's frames from the pool into the buffers decode reads."""
+        if self.override[i] is None:
+            return
+        t = self.t
+        idx = t.tensor(pool_idx, dtype=t.int64)
+        with t.cuda.stream(t.cuda.ExternalStream(stream)):
+            idx = idx.cuda()
+            for l, pool in enumerate(self.head_pools[i]):
+                t.index_select(pool, 0, idx, out=self.override[i][l][:len(pool_idx)])
+
+    def _warmup(self):
+        """One frame through every pipeline on the streams it will use, so that the first served batch does not pay
+        for stream and code-object set-up."""
+        for i, P in enumerate(self.pipes):
+            cam = next((c for c in self.cams if c.pipeline == i), None)
+            if cam is None:
+                continue
+            self._gather_heads(i, [cam.pool_offset], self._stream_of(i, 0))
+            P.submit([cam.pool[0]], frame_ids=[-1])
+            P.run_model(0, self._stream_of(i, 0))
+            for mi in range(1, len(P.spec.models)):
+                P.run_model(mi, self._stream_of(i, mi))
+            P.collect(blocking=True)
+
+    def close(self):
+        self.t.cuda.synchronize()
+        for h in self._owned:
+            binding.stream_destroy(h)
+        self._owned = []
+        for i, P in enumerate(self.pipes):
+            if self.override[i] is not None:
+                for l in range(len(self.override[i])):
+                    P.set_head(0, l, None)
+
+    def _stream_of(self, pipeline: int, model: int) -> int:
+        """Stream of a model's portion; a model Algorithm 2 could not place follows its parent on the parent's stream
+        (a root: on the first stream), i.e. it is served best-effort without a slot of its own."""
+        st = self.sch.placement(pipeline, model)[2]
+        if st >= 0:
+            return self.streams[st]
+        parent = {e.child: e.parent for e in self.pipes[pipeline].spec.edges}.get(model, -1)
+        if parent >= 0:
+            return self._stream_of(pipeline, parent)
+        return self.streams[min(self.streams)] if self.streams else int(self._plain.cuda_stream)
+
+    def _poll(self):
+        for i, P in enumerate(self.pipes):
+            if self.inflight[i] == 0:
+                continue
+            fr, bx, st = P.collect(blocking=False)
+            if st == binding.ENOTREADY or len(fr) == 0:
+                continue
+            S = self.stats[i]
+            S.served += len(fr)
+            S.slo_met += int(fr["slo_met"].sum())
+            S.boxes += int(fr["n_boxes"].sum())
+            S.latency_ms.extend(fr["latency_ms"].tolist())
+            batches_done = 0
+            for f in fr:
+                fid = int(f["frame_id"])
+                if fid in self.batch_last[i]:
+                    batches_done += 1
+                    self.batch_last[i].discard(fid)
+                if self.keep_results:
+                    S.results[fid] = (self.pool_of[i].pop(fid), bx[f["box_offset"]: f["box_offset"] + f["n_boxes"]].copy())
+            self.inflight[i] -= batches_done
+
+    def _admit(self, i: int, now_s: float):
+        """Move frames that have arrived by now from the camera streams into the pipeline's queue."""
+        arr, ptr = self.merged[i], self.next_arrival[i]
+        frames, stamps, ids = [], [], []
+        while ptr < len(arr) and arr[ptr][0] <= now_s:
+            t_s, cam, seq = arr[ptr]
+            c = self.cams[cam]
+            k = seq % len(c.pool)
+            fid = self.next_id[i]
+            self.next_id[i] += 1
+            frames.append(c.pool[k]); stamps.append(self.t0_ms + 1e3 * t_s); ids.append(fid)
+            self.mirror[i].append((fid, c.pool_offset + k))
+            ptr += 1
+        self.next_arrival[i] = ptr
+        if frames:
+            self.pipes[i].submit(frames, arrival_ms=stamps, frame_ids=ids)
+            self.stats[i].submitted += len(frames)
+
+    def _launch_batch(self, i: int) -> int:
+        P = self.pipes[i]
+        bz = self.sch.bz[i][0]
+        n = min(bz, len(self.mirror[i]))
+        if n == 0 or self.inflight[i] >= MAX_IN_FLIGHT:
+            return 0
+        batch = [self.mirror[i].pop(0) for _ in range(n)]
+        s0 = self._stream_of(i, 0)
+        self._gather_heads(i, [b[1] for b in batch], s0)
+        got = P.run_model(0, s0)
+        assert got == n, (got, n)
+        for mi in range(1, len(P.spec.models)):
+            P.run_model(mi, self._stream_of(i, mi))
+        self.inflight[i] += 1
+        self.batch_last[i].add(batch[-1][0])
+        if self.keep_results:
+            for fid, k in batch:
+                self.pool_of[i][fid] = k
+        return n
+
+    def _fire(self, i: int, now_s: float):
+        self._admit(i, now_s)
+        for _ in range(self.sch.batches_per_cycle[i][0] + 1):
+            if self._launch_batch(i) == 0:
+                break
+
+    def serve(self, duration_s: float, drain_s: float = 2.0) -> dict:
+        npipe = len(self.pipes)
+        self.merged = [[] for _ in range(npipe)]
+        for ci, c in enumerate(self.cams):
+            self.merged[c.pipeline] += [(float(t_), ci, k) for k, t_ in enumerate(c.arrivals_s) if t_ < duration_s]
+        for m in self.merged:
+            m.sort()
+        self.next_arrival = [0] * npipe
+        self.next_id = [0] * npipe
+        self.mirror = [[] for _ in range(npipe)]
+        self.inflight = [0] * npipe
+        self.batch_last = [set() for _ in range(npipe)]
+        self.pool_of = [dict() for _ in range(npipe)]
+        now = binding.lib().octo_now_ms
+        duty = self.sch.duty_ms
+        slots = sorted((self.sch.placement(i, 0)[3], i) for i in range(npipe))
+        self.t0_ms = now() + 2.0
+        t_end_ms = self.t0_ms + 1e3 * (duration_s + drain_s)
+        if self.slotted:
+            c = 0
+            while True:
+                for off, i in slots:
+                    target = self.t0_ms + c * duty + off
+                    while now() < target:
+                        self._poll()
+                        time.sleep(0.0002)
+                    self._fire(i, (now() - self.t0_ms) / 1e3)
+                c += 1
+                done = all(self.next_arrival[i] == len(self.merged[i]) and not self.mirror[i] and self.inflight[i] == 0
+                           for i in range(npipe))
+                if (done and c * duty >= 1e3 * duration_s) or now() > t_end_ms:
+                    break
+        else:
+            while True:
+                for i in range(npipe):
+                    self._admit(i, (now() - self.t0_ms) / 1e3)
+                    self._launch_batch(i)
+                self._poll()
+                time.sleep(0.0002)
+                done = all(self.next_arrival[i] == len(self.merged[i]) and not self.mirror[i] and self.inflight[i] == 0
+                           for i in range(npipe))
+                if (done and now() - self.t0_ms >= 1e3 * duration_s) or now() > t_end_ms:
+                    break
+        wall_s = (now() - self.t0_ms) / 1e3
+        for _ in range(1000):
+            if all(v == 0 for v in self.inflight):
+                break
+            self._poll()
+            time.sleep(0.001)
+        per = []
+        for i, S in enumerate(self.stats):
+            lat = np.asarray(S.latency_ms) if S.latency_ms else np.zeros(1)
+            per.append(dict(pipeline=self.pipes[i].spec.name, submitted=S.submitted, served=S.served, slo_met=S.slo_met,
+                            objects=S.boxes, latency_ms_p50=float(np.percentile(lat, 50)),
+                            latency_ms_p99=float(np.percentile(lat, 99)), latency_ms_max=float(lat.max())))
+        span = max(duration_s, 1e-9)
+        return dict(duration_s=duration_s, wall_s=wall_s, per_pipeline=per,
+                    effective_frames_per_s=sum(S.slo_met for S in self.stats) / span,
+                    total_frames_per_s=sum(S.served for S in self.stats) / span,
+                    objects_per_s=sum(S.boxes for S in self.stats) / span,
+                    slo_attainment=sum(S.slo_met for S in self.stats) / max(1, sum(S.submitted for S in self.stats)))
+
+
+# ---------------------------------------------------------------------------
+# the co-location workload: three pipelines, sixteen cameras
+# ---------------------------------------------------------------------------
+@dataclass
+class Colocation:
+    specs: List
+    cameras: List[Camera]
+    head_pools: List[Optional[List]]
+    scenes: List
+    heads_host: List[Optional[List[np.ndarray]]]
+    frame_rates: List[float]
+    objects_per_frame: List[float]
+    burstiness: List[List[float]]
+
+
+def make_colocation(duration_s: float, n_cameras=(6, 6, 4), pool_frames: int = 8, det_batch: int = 16, dtype: str = "bf16",
+                    seed: int = 20250201 + 4, mean_objects: float = 8.0, base_fps: float = 15.0,
+                    src_hw=(1080, 1920)) -> Colocation:
+    """Traffic cascade, surveillance cascade and a detector-only pipeline fed by cameras whose frame rate swings
+    sinusoidally around 15 fps (inhomogeneous Poisson arrivals); frames cycle through a small pool per pipeline and
+    the detector heads are planted per pool frame with Poisson object counts."""
+    import torch
+    from . import synth, zoo
+    rng = np.random.default_rng(seed)
+    specs = [zoo.traffic_cascade(dtype=dtype, det_batch=det_batch), zoo.surveillance_cascade(dtype=dtype, det_batch=det_batch),
+             zoo.detector_only(dtype=dtype, det_batch=det_batch)]
+    h, w = src_hw
+    arrivals = synth.sinusoid_arrivals(rng, sum(n_cameras), duration_s, base_fps=base_fps)
+    cams, pools, scenes, heads_host = [], [], [], []
+    ci = 0
+    for i, spec in enumerate(specs):
+        counts = synth.counts_poisson(rng, pool_frames, mean=mean_objects, cap=spec.max_rois_per_frame)
+        scene = synth.make_scene(rng, pool_frames, h, w, counts, 24, 360, log_uniform=True)
+        scenes.append(scene)
+        dev = [torch.from_numpy(f).cuda() for f in scene.frames]
+        hh = synth.planted_heads(rng, spec.models[0], scene, h, w)
+        heads_host.append(hh)
+        pools.append([binding.to_device(x, spec.models[0].dtype) for x in hh])
+        for _ in range(n_cameras[i]):
+            cams.append(Camera(i, arrivals[ci], dev, 0))
+            ci += 1
+    rates, objs, burst = [], [], []
+    for i, spec in enumerate(specs):
+        mine = np.sort(np.concatenate([c.arrivals_s for c in cams if c.pipeline == i])) if n_cameras[i] else np.zeros(0)
+        rates.append(len(mine) / max(duration_s, 1e-9))
+        per_frame = np.array([len(r) for r in scenes[i].rects], np.float64)
+        objs.append(float(per_frame.mean()))
+        # objects of one frame reach the child together, so its inter-arrival times are mostly zero: a much
+        # burstier sequence than the frames themselves
+        k = rng.choice(per_frame.astype(np.int64), size=len(mine)) if len(mine) else np.zeros(0, np.int64)
+        child_times = np.repeat(mine, k)
+        burst.append([coefficient_of_variation(mine)] + [coefficient_of_variation(child_times)] * (len(spec.models) - 1))
+    return Colocation(specs, cams, pools, scenes, heads_host, rates, objs, burst)
