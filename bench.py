@@ -92,6 +92,113 @@ def cpu_baseline(spec, scene, heads):
                       (n, len(ref.children[0].rois) if ref.children else 0, dt)}, ref
 
 
+def run_sweep(args):
+    """Batch-size sweep (the paper's Observation 2: throughput and latency against batch size): detector + classifier,
+    bf16, negative-binomial object counts, every batch size from 1 to 64 at its real shape."""
+    import torch
+    from paper_2502_01277_amd import binding, synth, zoo
+    n_cu = binding.device_cu_count()
+    ninst = max(1, args.instances)
+    streams = [binding.stream_create_range(0, n_cu) for _ in range(ninst)]
+    now = binding.lib().octo_now_ms
+    rows = []
+    for bz in (1, 2, 4, 8, 16, 32, 64):
+        spec = zoo.sweep_cascade(bz)
+        det = spec.models[0]
+        rng = np.random.default_rng(zoo.SEED0 + 3)
+        counts = synth.counts_negbin(rng, bz)
+        scene = synth.make_scene(rng, bz, 1080, 1920, counts, 24, 200, log_uniform=True)
+        heads = synth.planted_heads(rng, det, scene, 1080, 1920)
+        dev = [torch.from_numpy(f).cuda() for f in scene.frames]
+        pipes, keep = [], []
+        for _ in range(ninst):
+            P = binding.Pipeline(spec)
+            dh = [binding.to_device(h, det.dtype) for h in heads]
+            for l, h in enumerate(dh):
+                P.set_head(0, l, h)
+            keep.append(dh); pipes.append(P)
+        # batch latency alone on the GPU
+        solo = []
+        for k in range(10 + 30):
+            pipes[0].submit(dev, arrival_ms=[now()] * bz); pipes[0].run(streams[0])
+            fr, _, _ = pipes[0].collect()
+            if k >= 10:
+                solo.append(float(fr["latency_ms"].max()))
+        # throughput with all instances busy
+        steps = max(50, args.steps // 4)
+        lat, met, done = [], 0, 0
+        pend = [0] * ninst
+        def take(j):
+            nonlocal met, done
+            fr, _, _ = pipes[j].collect()
+            pend[j] -= len(fr) // bz; done += len(fr); met += int(fr["slo_met"].sum()); lat.extend(fr["latency_ms"].tolist())
+        for k in range(10):
+            pipes[k % ninst].submit(dev); pipes[k % ninst].run(streams[k % ninst]); pipes[k % ninst].collect()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for k in range(steps):
+            j = k % ninst
+            if pend[j] >= 2:
+                take(j)
+            pipes[j].submit(dev, arrival_ms=[now()] * bz); pipes[j].run(streams[j]); pend[j] += 1
+        for j in range(ninst):
+            while pend[j] > 0:
+                take(j)
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
+        rows.append({"bz": bz, "objects_per_batch": int(counts.sum()), "batch_latency_ms_p50": float(np.percentile(solo, 50)),
+                     "batch_latency_ms_p99": float(np.percentile(solo, 99)), "frames_per_s": done / dt,
+                     "slo_met_frames_per_s": met / dt, "latency_ms_p99_loaded": float(np.percentile(lat, 99))})
+        print("bz %2d  objects %4d  latency %.2f ms  %.0f frames/s" % (bz, counts.sum(), rows[-1]["batch_latency_ms_p50"], done / dt), file=sys.stderr)
+        torch.cuda.synchronize()
+        for P in pipes:
+            P.close()
+        del pipes, keep, dev
+    best = max(rows, key=lambda r: r["slo_met_frames_per_s"])
+    for st in streams:
+        binding.stream_destroy(st)
+    print(json.dumps({
+        "metric": "pipeline frames/s within 200 ms SLO on 1 GPU", "value": best["slo_met_frames_per_s"], "unit": "frames/s",
+        "n_gpus": 1, "steps": max(50, args.steps // 4), "warmup": 10, "ms_per_step": 1e3 * best["bz"] / best["frames_per_s"],
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "batch-size sweep: CSP-s detector 640 + ResNet-18-shaped classifier 224, bf16, 1080p frames, "
+                               "planted heads NegBin(mean 6, var 60) cap 200", "best_bz": best["bz"], "instances": ninst,
+                   "slo_ms": 200.0, "heads": "planted"},
+        "sweep": rows}))
+
+
+def run_colocate(args):
+    """Three pipelines and sixteen cameras sharing the GPU (Sec. III-C): scheduler-lite + slot executor on CU-range
+    streams, and for comparison the same load without portions (one ordinary stream, launch on arrival)."""
+    import torch
+    from paper_2502_01277_amd import binding, executor
+    dur = args.duration
+    scale = max(1, args.camera_scale)
+    co = executor.make_colocation(dur, n_cameras=(6 * scale, 6 * scale, 4 * scale), pool_frames=8, det_batch=args.det_batch)
+    pipes = [binding.Pipeline(s) for s in co.specs]
+    profiles = [executor.profile_pipeline(P, widths=(64, 128, 256), iters=2) for P in pipes]
+    sch = executor.plan(co.specs, profiles, co.frame_rates, co.objects_per_frame, co.burstiness, n_streams=8)
+    res = {}
+    for tag, slotted, masked in (("portions", True, True), ("no_portions", False, False)):
+        ex = executor.Executor(pipes, sch, co.cameras, co.head_pools, slotted=slotted, masked=masked)
+        res[tag] = ex.serve(dur)
+        ex.close()
+    out = res["portions"]
+    print(json.dumps({
+        "metric": "pipeline frames/s within 200 ms SLO on 1 GPU", "value": out["effective_frames_per_s"], "unit": "frames/s",
+        "n_gpus": 1, "steps": int(1e3 * dur / sch.duty_ms), "warmup": 1, "ms_per_step": sch.duty_ms,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "co-location: traffic + surveillance + detector-only pipelines, %d cameras at 15 fps "
+                               "(sinusoidal), %.0f s, planted heads Poisson(8); offered load %.0f frames/s" %
+                               (16 * scale, dur, sum(co.frame_rates)), "slo_ms": 200.0, "heads": "planted"},
+        "schedule": {"duty_ms": sch.duty_ms, "bz": sch.bz, "batches_per_cycle": sch.batches_per_cycle,
+                     "placements": sch.placements, "stream_cus": {str(k): v for k, v in sch.stream_cus.items()},
+                     "est_latency_ms": sch.est_latency_ms, "widths": [[m.util for m in pr] for pr in profiles]},
+        "portions": res["portions"], "no_portions": res["no_portions"]}))
+    for P in pipes:
+        P.close()
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -106,6 +213,9 @@ def main():
     ap.add_argument("--calib-copy-mib", type=int, default=0,
                     help="also run one plain device pass over this many MiB before the timed region (a known-size kernel "
                          "against which hardware traffic counters are scaled)")
+    ap.add_argument("--duration", type=float, default=5.0, help="co-location workload: seconds of arrivals to serve")
+    ap.add_argument("--camera-scale", type=int, default=1, help="co-location workload: multiply the sixteen cameras")
+    ap.add_argument("--det-batch", type=int, default=16, help="co-location workload: largest detector batch")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU only (frames are independent: more GPUs = more copies of this run); --gpus %d refused" % args.gpus,
@@ -115,6 +225,10 @@ def main():
     from paper_2502_01277_amd import binding
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     binding.lib()
+    if args.workload == "sweep":
+        return run_sweep(args)
+    if args.workload == "colocate":
+        return run_colocate(args)
     spec, scene, heads, desc = make_workload(args.workload)
     det = spec.models[0]
     n = scene.frames.shape[0]
