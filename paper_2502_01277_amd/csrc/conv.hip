@@ -105,12 +105,15 @@ __global__ __launch_bounds__(THREADS, MINB) void conv_mfma_kernel(const ConvArgs
 
   // operand tiles; after the K loop the same memory stages the output tile as [pixel][channel] so that it can be
   // written with 16-byte stores that cover whole cache lines
-  __shared__ u32x4 smem[2 * (BC + BP) * ROWV];
+  constexpr int OPITCH = BC * ES + 16;                                    // bytes per staged output row
+  constexpr int OPER_VECS = 2 * (BC + BP) * ROWV;                         // double-buffered operand tiles
+  constexpr int STAGE_VECS = BP * OPITCH / 16;                            // output tile
+  constexpr bool STAGED = STAGE_VECS <= 4096;                             // stage outputs of up to 64 KB
+  constexpr int SMEM_VECS = STAGED && STAGE_VECS > OPER_VECS ? STAGE_VECS : OPER_VECS;
+  __shared__ u32x4 smem[SMEM_VECS];
   __shared__ float sBias[BC];
   u32x4 (*sA)[BC][ROWV] = (u32x4 (*)[BC][ROWV])smem;
   u32x4 (*sB)[BP][ROWV] = (u32x4 (*)[BP][ROWV])(smem + 2 * BC * ROWV);
-  constexpr int OPITCH = BC * ES + 16;                                    // bytes per staged output row
-  constexpr bool STAGED = BP * OPITCH <= 2 * (BC + BP) * ROWV * 16;       // does the output tile fit?
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -403,7 +406,9 @@ static hipError_t launch_typed(const ConvArgs& a, int num_cu, hipStream_t s, int
   constexpr int VN = Elem<T>::N;
   const bool vec = (a.Cin % VN == 0) && (a.x_ld % VN == 0) && (a.x_coff % VN == 0) && (((uintptr_t)a.x & 15) == 0) &&
                    a.kh <= 15 && a.kw <= 15;
-  const long long M = (long long)a.n * a.Ho * a.Wo;
+  // the tile shape is chosen for the expected number of items (any shape is correct for any count: the grid strides
+  // over however many tiles the device-side count gives)
+  const long long M = (long long)(a.n_hint > 0 && a.n_hint < a.n ? a.n_hint : a.n) * a.Ho * a.Wo;
   auto tiles = [&](int bc, int bp) { return ((M + bp - 1) / bp) * ((a.Cout + bc - 1) / bc); };
   if (!vec) {
     // element-wise gather (first layers with 3 input channels)
@@ -413,7 +418,11 @@ static hipError_t launch_typed(const ConvArgs& a, int num_cu, hipStream_t s, int
   // Tile choice (measured on MI355X): the widest tile whose tile count still covers the chip; K steps of 128 bytes
   // when the padded reduction length allows it; small tiles at high occupancy for layers with few output pixels.
   if (a.Cout <= 32) return launch_cfg<T, 32, 128, 1, 4, 4, 2, 4, true>(a, num_cu, s, kernel_id, tm);
-  if (a.Cout >= 128 && tiles(128, 128) >= num_cu) return launch_cfg<T, 128, 128, 2, 2, 4, 2, 2, true>(a, num_cu, s, kernel_id, tm);
+  if (a.Cout > 128 && tiles(256, 128) >= 2 * num_cu) return launch_cfg<T, 256, 128, 2, 2, 4, 2, 2, true>(a, num_cu, s, kernel_id, tm);
+  if (a.Cout >= 96 && tiles(128, 128) >= num_cu) {
+    if (sizeof(T) == 2 && a.Kp % (16 * VN) == 0) return launch_cfg<T, 128, 128, 2, 2, 8, 2, 2, true>(a, num_cu, s, kernel_id, tm);
+    return launch_cfg<T, 128, 128, 2, 2, 4, 2, 2, true>(a, num_cu, s, kernel_id, tm);
+  }
   if (tiles(64, 128) >= num_cu / 2) {
     if (sizeof(T) == 2 && a.Kp % (16 * VN) == 0) return launch_cfg<T, 64, 128, 2, 2, 8, 2, 2, true>(a, num_cu, s, kernel_id, tm);
     return launch_cfg<T, 64, 128, 2, 2, 4, 2, 3, true>(a, num_cu, s, kernel_id, tm);

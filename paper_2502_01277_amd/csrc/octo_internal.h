@@ -36,6 +36,7 @@ struct ConvArgs {
   unsigned magic_cin, magic_kw;   // floor(2^32 / d) + 1 for d = Cin, kw (set by launch_conv)
   int act, res_mode;
   int out_f32;          // write fp32 instead of the storage type
+  int n_hint;           // host only: expected item count when it is taken on the device (0: assume n); picks the tile shape
 };
 
 // element size of a storage type

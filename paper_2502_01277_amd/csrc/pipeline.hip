@@ -69,6 +69,7 @@ struct ModelPlan {
   int cap = 0;             // item capacity
   int bz = 0;              // current batch size (root: frames per batch)
   const int* n_dyn = nullptr;
+  double items_hint = 0;   // smoothed item count of recent batches (children; 0: none seen yet)
   char* act_base = nullptr;
   size_t act_bytes = 0;
   // detector
@@ -422,6 +423,7 @@ hipError_t run_layer(octo_pipeline* p, ModelPlan& m, int i, int n, const int* n_
       if (lp.pair_view) { a.W = x.w / 2; a.Cin = 8; a.x_ld = 8; a.kw = lp.pair_kw; a.stride_w = 1; a.pad_w = lp.pair_pad; }
       a.act = L.act; a.res_mode = L.res_mode; a.out_f32 = m.tensors[i + 1].f32 ? 1 : 0;
       if (L.n_in == 2) { const TensorView r = view_of(m, L.in[1]); a.res = r.ptr; a.res_ld = r.ld; a.res_coff = r.coff; }
+      if (n_dyn && m.items_hint > 0) a.n_hint = std::max(1, (int)(m.items_hint + 0.999));
       return launch_conv(m.d.dtype, a, p->num_cu, s, &lp.kernel_id, tm);
     }
     case OCTO_MAXPOOL: {
@@ -868,6 +870,13 @@ octo_status octo_collect(octo_pipeline* p, octo_frame_result* frames, int32_t fr
     const int* fl = (const int*)(h + p->off_flags);
     const octo_box* hb = (const octo_box*)(h + p->off_boxes);
     const int max_det = p->models[0].d.max_det;
+    const int* nroi = (const int*)(h + p->off_nroi);
+    for (size_t e = 0; e < p->edges.size(); ++e) {
+      // what the children saw: the next batches' kernels are shaped for about as many items
+      ModelPlan& c = p->models[p->edges[e].child];
+      const double obs = std::min(nroi[e], c.cap);
+      c.items_hint = c.items_hint > 0 ? 0.75 * c.items_hint + 0.25 * obs : obs;
+    }
     int total = 0;
     for (int i = 0; i < B.n; ++i) total += std::min(nk[i], max_det);
     if (*n_frames + B.n > frame_cap || *n_boxes + total > box_cap) {

@@ -94,6 +94,8 @@ CONV_CASES = [
     (33, 31, 3, 32, 6, 2, 2, 2), (30, 30, 3, 64, 7, 2, 3, 2), (12, 12, 48, 40, 3, 1, 1, 3),
     (8, 8, 16, 255, 1, 1, 0, 4), (40, 40, 8, 16, 3, 2, 1, 2), (7, 7, 512, 512, 3, 1, 1, 2),
     (14, 14, 24, 520, 1, 1, 0, 1), (5, 5, 200, 72, 3, 1, 1, 2),
+    # enough output pixels for the wide tiles: 256x128 (ragged channel tail), 128x128, 64x128 with 64- and 32-element K steps
+    (128, 128, 16, 200, 1, 1, 0, 4), (96, 96, 16, 128, 3, 1, 1, 4), (64, 64, 128, 64, 1, 1, 0, 4), (64, 64, 64, 64, 1, 1, 0, 4),
 ]
 
 
