@@ -94,7 +94,9 @@ __global__ __launch_bounds__(THREADS, MINB) void conv_mfma_kernel(const ConvArgs
   constexpr int VN = E::N;
   constexpr int ES = (int)sizeof(T);
   constexpr int BK = KV * VN;            // elements per K step
-  constexpr int ROWV = KV + 1;           // LDS row pitch in vectors: (16*KV + 16) bytes keeps 16-byte reads conflict-free
+  constexpr int ROWV = KV;               // LDS row pitch in vectors; the vector slot of a row is XOR-swizzled (below)
+  constexpr int RPW = 16 / KV;           // tile rows per 256 bytes of LDS (one pass over all banks)
+  static_assert(KV == 4 || KV == 8, "swizzle assumes 64- or 128-byte rows");
   constexpr int RP = THREADS / KV;       // tile rows covered by one pass of the 256 loader lanes
   constexpr int TC = BC / WC / 32;       // 32x32 blocks per wavefront along channels
   constexpr int TP = BP / WP / 32;
@@ -134,6 +136,11 @@ __global__ __launch_bounds__(THREADS, MINB) void conv_mfma_kernel(const ConvArgs
 
   const int ld_row = tid / KV;
   const int ld_kv = tid % KV;
+  // Row r keeps its 16-byte vector v in slot v ^ ((r / RPW) % KV).  Sixteen lanes that write RPW whole rows, and sixteen
+  // lanes that read the same logical vector of sixteen consecutive rows, then each touch a different 16-byte bank group.
+  // 32 and THREADS / KV are multiples of RPW * KV, so the swizzle term depends only on the lane.
+  const int wsw = ld_kv ^ ((ld_row / RPW) % KV);      // slot this lane writes
+  const int rsw = (l32 / RPW) % KV;                   // XOR term for this lane's fragment reads
   const bool vec_ok = ((a.y_ld | a.y_coff) & 3) == 0 && (!a.res || ((a.res_ld | a.res_coff) & 3) == 0);
   const bool is_silu = a.act == OCTO_ACT_SILU;
   const float act_lo = a.act == OCTO_ACT_RELU ? 0.0f : -INFINITY;
@@ -251,18 +258,18 @@ __global__ __launch_bounds__(THREADS, MINB) void conv_mfma_kernel(const ConvArgs
         // operands of step kb: registers -> LDS
 #pragma unroll
         for (int i = 0; i < LA; ++i)
-          if (BC % RP == 0 || ld_row + RP * i < BC) sA[buf][ld_row + RP * i][ld_kv] = ra[d][i];
+          if (BC % RP == 0 || ld_row + RP * i < BC) sA[buf][ld_row + RP * i][wsw] = ra[d][i];
 #pragma unroll
-        for (int i = 0; i < LB; ++i) sB[buf][ld_row + RP * i][ld_kv] = rb[d][i];
+        for (int i = 0; i < LB; ++i) sB[buf][ld_row + RP * i][wsw] = rb[d][i];
         __syncthreads();
         OCTO_CONV_LOAD(kb + D, d)
 #pragma unroll
         for (int kk = 0; kk < KV / 2; ++kk) {
           u32x4 fa[TC], fb[TP];
 #pragma unroll
-          for (int i = 0; i < TC; ++i) fa[i] = sA[buf][wc * (BC / WC) + i * 32 + l32][kk * 2 + g];
+          for (int i = 0; i < TC; ++i) fa[i] = sA[buf][wc * (BC / WC) + i * 32 + l32][(kk * 2 + g) ^ rsw];
 #pragma unroll
-          for (int j = 0; j < TP; ++j) fb[j] = sB[buf][wp * (BP / WP) + j * 32 + l32][kk * 2 + g];
+          for (int j = 0; j < TP; ++j) fb[j] = sB[buf][wp * (BP / WP) + j * 32 + l32][(kk * 2 + g) ^ rsw];
 #pragma unroll
           for (int i = 0; i < TC; ++i)
 #pragma unroll
