@@ -151,7 +151,14 @@ __global__ __launch_bounds__(THREADS, MINB) void conv_mfma_kernel(const ConvArgs
   const long long w_bytes = (long long)a.w_rows * a.Kp * ES;
   const __amdgpu_buffer_rsrc_t rsrc_w = __builtin_amdgcn_make_buffer_rsrc((void*)a.w, 0, (int)(w_bytes < BUF_MAX ? w_bytes : BUF_MAX), BUF_FLAGS);
 
-  for (long long tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
+  // Workgroups are handed to the eight dies in turn (workgroup b runs on die b % 8) and every die has its own L2.  The
+  // tile list is therefore cut into eight contiguous chunks, one per die: tiles that share input rows (neighbouring
+  // pixel tiles, and all channel tiles of the same pixels) then meet in one L2 instead of being fetched by every die.
+  // The grid is a multiple of 8, so a workgroup stays on its chunk while it strides.
+  const long long per_die = (n_tiles + 7) >> 3;
+  for (long long t = blockIdx.x; t < per_die * 8; t += gridDim.x) {
+    const long long tile = (t & 7) * per_die + (t >> 3);
+    if (tile >= n_tiles) continue;
     const int tc = (int)(tile % tiles_c);
     const long long tp = tile / tiles_c;
     const int c0 = tc * BC;
@@ -397,8 +404,8 @@ static hipError_t launch_cfg(const ConvArgs& a, int num_cu, hipStream_t s, int* 
   const long long M = (long long)a.n * a.Ho * a.Wo;
   const long long tiles = ((M + BP - 1) / BP) * ((a.Cout + BC - 1) / BC);
   if (tiles <= 0) return hipSuccess;
-  long long grid = tiles;
-  const long long cap = (long long)num_cu * MINB;
+  long long grid = (tiles + 7) / 8 * 8;          // a multiple of the die count (see the kernel's tile order)
+  const long long cap = ((long long)num_cu * MINB + 7) / 8 * 8;
   if (grid > cap) grid = cap;
   // with timing events the dispatch itself carries them, so their difference is the kernel's own run time
   if (tm.start && tm.stop)
