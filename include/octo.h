@@ -228,9 +228,10 @@ octo_status octo_get_layer_info(octo_pipeline* p, int32_t model, float* ms, int3
 octo_status octo_set_stage_timing(octo_pipeline* p, int32_t enable);
 octo_status octo_get_stage_ms(octo_pipeline* p, float* ms, int32_t cap, int32_t* n);
 
-/* Copy a tensor of the last run to host as dense NHWC in the tensor's type (fp32 for fc outputs).
- * tensor_id as in octo_layer; n_items items.  Synchronises the device. */
-octo_status octo_debug_get_tensor(octo_pipeline* p, int32_t model, int32_t tensor_id, int32_t n_items, void* host_dst, size_t bytes);
+/* Copy items [first_item, first_item + n_items) of a tensor of the last run to host as dense NHWC in the tensor's
+ * type (fp32 for fc outputs).  tensor_id as in octo_layer.  Synchronises the device. */
+octo_status octo_debug_get_tensor(octo_pipeline* p, int32_t model, int32_t tensor_id, int32_t first_item, int32_t n_items,
+                                  void* host_dst, size_t bytes);
 octo_status octo_debug_tensor_shape(octo_pipeline* p, int32_t model, int32_t tensor_id, int32_t* h, int32_t* w, int32_t* c);
 /* Replace (d_head != NULL) or restore (NULL) the head tensor of `level` that decode reads: dense
  * [items][G][G][A*(5+C)] in the model's type, device memory owned by the caller. */

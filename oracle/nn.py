@@ -64,6 +64,33 @@ def conv2d(x: np.ndarray, w: np.ndarray, stride: int, pad: int) -> np.ndarray:
     return y.permute(0, 2, 3, 1).contiguous().numpy()
 
 
+def conv_layer_at(x: np.ndarray, L, dtype: str, positions, res: np.ndarray = None) -> np.ndarray:
+    """One conv layer (definition of `direct_conv`, then bias, residual, activation and the storage rounding of
+    `run_model`) evaluated only at the listed output positions (n, p, q).  x [N][H][W][C] holds the layer's input;
+    res, if the layer has a residual input, the tensor it adds.  Returns [len(positions)][K].  Lets a full-size
+    tensor be checked on samples without evaluating all of it."""
+    n, h, wd, c = x.shape
+    k, r, s, _ = L.weight.shape
+    w64 = L.weight.astype(np.float64)
+    out = np.zeros((len(positions), k), np.float64)
+    for j, (ni, p, q) in enumerate(positions):
+        acc = np.zeros(k, np.float64)
+        for ri in range(r):
+            for si in range(s):
+                yy, xx = p * L.stride + ri - L.pad, q * L.stride + si - L.pad
+                if 0 <= yy < h and 0 <= xx < wd:
+                    acc += w64[:, ri, si, :] @ x[ni, yy, xx, :].astype(np.float64)
+        y = acc + L.bias.astype(np.float64)
+        if L.res_mode == RES_BEFORE_ACT:
+            y = activation(y + res[ni, p, q].astype(np.float64), L.act)
+        elif L.res_mode == RES_AFTER_ACT:
+            y = activation(y, L.act) + res[ni, p, q].astype(np.float64)
+        else:
+            y = activation(y, L.act)
+        out[j] = y
+    return round_storage(out, dtype)
+
+
 def maxpool(x: np.ndarray, k: int, stride: int, pad: int) -> np.ndarray:
     """Window maximum; padding counts as -inf."""
     n, h, w, c = x.shape

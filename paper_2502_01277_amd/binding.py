@@ -128,7 +128,7 @@ def lib() -> C.CDLL:
         L.octo_set_layer_timing.argtypes = [vp, i32]
         L.octo_get_layer_info.argtypes = [vp, i32, vp, vp, vp, vp, vp, i32, vp]
         L.octo_get_stage_ms.argtypes = [vp, vp, i32, vp]
-        L.octo_debug_get_tensor.argtypes = [vp, i32, i32, i32, vp, C.c_size_t]
+        L.octo_debug_get_tensor.argtypes = [vp, i32, i32, i32, i32, vp, C.c_size_t]
         L.octo_debug_tensor_shape.argtypes = [vp, i32, i32, vp, vp, vp]
         L.octo_debug_set_head.argtypes = [vp, i32, i32, vp]
         L.octo_debug_run_model.argtypes = [vp, i32, vp, i32, vp]
@@ -313,15 +313,15 @@ class Pipeline:
         self._check(self.L.octo_debug_tensor_shape(self.h, model, tid, C.byref(h), C.byref(w), C.byref(c)))
         return h.value, w.value, c.value
 
-    def get_tensor(self, model: int, tid: int, n: int) -> np.ndarray:
-        """Tensor of the last run as fp32 numpy [n][h][w][c]."""
+    def get_tensor(self, model: int, tid: int, n: int, first: int = 0) -> np.ndarray:
+        """Items [first, first + n) of a tensor of the last run as fp32 numpy [n][h][w][c]."""
         from .synth import from_storage
         h, w, c = self.tensor_shape(model, tid)
         m = self.spec.models[model]
         is_fc = tid > 0 and m.layers[tid - 1].op == "fc"
         dt = "f32" if is_fc else m.dtype
         raw = np.empty((n, h, w, c), {"f32": np.float32, "f16": np.float16, "bf16": np.uint16}[dt])
-        self._check(self.L.octo_debug_get_tensor(self.h, model, tid, n, raw.ctypes.data, raw.nbytes))
+        self._check(self.L.octo_debug_get_tensor(self.h, model, tid, first, n, raw.ctypes.data, raw.nbytes))
         return from_storage(raw, dt)
 
     def set_head(self, model: int, level: int, tensor):

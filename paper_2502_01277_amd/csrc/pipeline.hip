@@ -1028,20 +1028,22 @@ octo_status octo_debug_tensor_shape(octo_pipeline* p, int32_t model, int32_t ten
   return OCTO_OK;
 }
 
-octo_status octo_debug_get_tensor(octo_pipeline* p, int32_t model, int32_t tensor_id, int32_t n_items, void* host_dst, size_t bytes) {
+octo_status octo_debug_get_tensor(octo_pipeline* p, int32_t model, int32_t tensor_id, int32_t first_item, int32_t n_items,
+                                  void* host_dst, size_t bytes) {
   if (!p) return OCTO_EINVAL;
   if (model < 0 || model >= (int)p->models.size() || tensor_id < 0 || tensor_id >= (int)p->models[model].tensors.size() || !host_dst)
     return fail(p, OCTO_EINVAL, "bad tensor reference");
   ModelPlan& m = p->models[model];
   const TensorPlan& t = m.tensors[tensor_id];
-  if (n_items < 0 || n_items > m.cap) return fail(p, OCTO_EINVAL, "bad item count");
+  if (first_item < 0 || n_items < 0 || (long long)first_item + n_items > m.cap) return fail(p, OCTO_EINVAL, "bad item range");
   const size_t es = t.f32 ? 4 : dtype_size(m.d.dtype);
   const size_t rows = (size_t)n_items * t.h * t.w;
   if (bytes < rows * t.c * es) return fail(p, OCTO_EINVAL, "destination too small");
   HIPCHK(p, hipDeviceSynchronize());
   const TensorView v = view_of(m, tensor_id);
   if (rows == 0) return OCTO_OK;
-  HIPCHK(p, hipMemcpy2D(host_dst, t.c * es, (const char*)v.ptr + (size_t)v.coff * es, (size_t)v.ld * es, t.c * es, rows, hipMemcpyDeviceToHost));
+  const char* src = (const char*)v.ptr + ((size_t)first_item * t.h * t.w * v.ld + (size_t)v.coff) * es;
+  HIPCHK(p, hipMemcpy2D(host_dst, t.c * es, src, (size_t)v.ld * es, t.c * es, rows, hipMemcpyDeviceToHost));
   return OCTO_OK;
 }
 

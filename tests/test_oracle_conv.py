@@ -174,3 +174,24 @@ def test_zoo_shapes():
     assert tiny.models[0].tensor_shapes()[-1] == (20, 20, 39) and tiny.models[0].n_cand() == 1200
     r50 = zoo.surveillance_cascade().models[1]
     assert r50.tensor_shapes()[-1] == (1, 1, 32) and 4.5e9 < r50.flops_per_item() < 6.5e9
+
+
+def test_sampled_layer_evaluation_equals_the_full_layer():
+    """conv_layer_at is the layer definition restricted to chosen output positions: it must reproduce run_model's
+    tensor there, borders, stride and residual included."""
+    from paper_2502_01277_amd import zoo
+    rng = np.random.default_rng(5)
+    B = zoo._Builder("t", "bf16", 11, 9, "classifier", rng)
+    B.ch = [6]
+    B.m.in_c = 6
+    a = B.conv(0, 10, 3, 2, 1, act=zoo.ACT_SILU)
+    b = B.conv(a, 10, 3, 1, 1, act=zoo.ACT_RELU, res=a, res_mode=zoo.RES_BEFORE_ACT)
+    B.m.outputs = [B.fc(B.gap(b), 4)]
+    x = zoo.round_to_dtype(rng.uniform(-1, 1, (2, 11, 9, 6)).astype(np.float32), "bf16")
+    ts = nn.run_model(B.m, x, keep_all=True)
+    pos = [(0, 0, 0), (1, 5, 4), (0, 3, 2), (1, 0, 4), (1, 5, 0)]
+    got1 = nn.conv_layer_at(ts[0], B.m.layers[0], "bf16", pos)
+    got2 = nn.conv_layer_at(ts[1], B.m.layers[1], "bf16", pos, res=ts[1])
+    for j, (n, p, q) in enumerate(pos):
+        assert np.array_equal(got1[j], ts[1][n, p, q])
+        assert np.array_equal(got2[j], ts[2][n, p, q])
