@@ -432,7 +432,9 @@ static hipError_t launch_typed(const ConvArgs& a, int num_cu, hipStream_t s, int
   // Tile choice (measured on MI355X): the widest tile whose tile count still covers the chip; K steps of 128 bytes
   // when the padded reduction length allows it; small tiles at high occupancy for layers with few output pixels.
   if (a.Cout <= 32) return launch_cfg<T, 32, 128, 1, 4, 4, 2, 4, true>(a, num_cu, s, kernel_id, tm);
-  if (a.Cout > 128 && tiles(256, 128) >= 2 * num_cu) return launch_cfg<T, 256, 128, 2, 2, 4, 2, 2, true>(a, num_cu, s, kernel_id, tm);
+  // 256 channels per tile only where that pads the channel count no further than 128 does (384 = 3 x 128, but 2 x 256)
+  const bool fits256 = (a.Cout + 255) / 256 * 256 == (a.Cout + 127) / 128 * 128;
+  if (a.Cout > 128 && fits256 && tiles(256, 128) >= 2 * num_cu) return launch_cfg<T, 256, 128, 2, 2, 4, 2, 2, true>(a, num_cu, s, kernel_id, tm);
   if (a.Cout >= 96 && tiles(128, 128) >= num_cu) {
     if (sizeof(T) == 2 && a.Kp % (16 * VN) == 0) return launch_cfg<T, 128, 128, 2, 2, 8, 2, 2, true>(a, num_cu, s, kernel_id, tm);
     return launch_cfg<T, 128, 128, 2, 2, 4, 2, 2, true>(a, num_cu, s, kernel_id, tm);
