@@ -186,9 +186,14 @@ def run_colocate(args):
     pipes = [binding.Pipeline(s) for s in co.specs]
     profiles = [executor.profile_pipeline(P, widths=(64, 128, 256), iters=2) for P in pipes]
     sch = executor.plan(co.specs, profiles, co.frame_rates, co.objects_per_frame, co.burstiness, n_streams=8)
+    # the paper's ablations (Sec. IV-C): no spatiotemporal portions (launch on arrival, one ordinary stream), and
+    # static batch sizes (detector 8, downstream models 2) under the same portion scheduler
+    static = executor.plan(co.specs, profiles, co.frame_rates, co.objects_per_frame, co.burstiness, n_streams=8,
+                           fixed_bz=[[min(8, args.det_batch)] + [2] * (len(s.models) - 1) for s in co.specs])
     res = {}
-    for tag, slotted, masked in (("portions", True, True), ("no_portions", False, False)):
-        ex = executor.Executor(pipes, sch, co.cameras, co.head_pools, slotted=slotted, masked=masked)
+    for tag, plan_, slotted, masked in (("portions", sch, True, True), ("no_portions", sch, False, False),
+                                        ("static_batch", static, True, True)):
+        ex = executor.Executor(pipes, plan_, co.cameras, co.head_pools, slotted=slotted, masked=masked)
         res[tag] = ex.serve(dur)
         ex.close()
     out = res["portions"]
@@ -202,7 +207,8 @@ def run_colocate(args):
         "schedule": {"duty_ms": sch.duty_ms, "bz": sch.bz, "batches_per_cycle": sch.batches_per_cycle,
                      "placements": sch.placements, "stream_cus": {str(k): v for k, v in sch.stream_cus.items()},
                      "est_latency_ms": sch.est_latency_ms, "widths": [[m.util for m in pr] for pr in profiles]},
-        "portions": res["portions"], "no_portions": res["no_portions"]}))
+        "portions": res["portions"], "no_portions": res["no_portions"], "static_batch": res["static_batch"],
+        "static_batch_schedule": {"bz": static.bz, "batches_per_cycle": static.batches_per_cycle}}))
     for P in pipes:
         P.close()
 

@@ -125,33 +125,40 @@ class Schedule:
 
 def plan(specs, profiles: List[List[ModelProfile]], frame_rates: Sequence[float], objects_per_frame: Sequence[float],
          burstiness: Sequence[Sequence[float]], n_streams: int = 8, gpu_mem_mb: float = 288e3,
-         fixed_bz: Optional[List[List[int]]] = None) -> Schedule:
-    """Scheduler-lite: Algorithm 1's batch-size search per pipeline, then Algorithm 2 over all pipelines."""
+         fixed_bz: Optional[List[List[int]]] = None, cycle_share: float = 0.8) -> Schedule:
+    """Scheduler-lite: Algorithm 1's batch-size search per pipeline, then Algorithm 2 over all pipelines.
+
+    Widths: every model starts at the width its profile chose; if the pipeline's work per duty cycle (sum over its
+    models of batches-per-cycle x batch latency at that width) does not fit in cycle_share of the cycle, all its models
+    are moved to the next profiled width and the batch sizes are searched again with the latencies of that width."""
     total = binding.device_cu_count()
     sched_in, all_bz, all_k, est_l, est_t = [], [], [], [], []
     duty = min(s.slo_ms for s in specs) / 2.0
     for i, spec in enumerate(specs):
         parent = {e.child: e.parent for e in spec.edges}
-        models = []
-        for mi, m in enumerate(spec.models):
-            rate = frame_rates[i] * (objects_per_frame[i] if mi > 0 else 1.0)
-            wmem = sum(L.weight.size for L in m.layers if getattr(L, "weight", None) is not None) * (4 if m.dtype == "f32" else 2) / 1e6
-            models.append(dict(parent=parent.get(mi, -1), profile=dict(profiles[i][mi].latency_ms), rate=max(rate, 1e-3),
-                               burstiness=burstiness[i][mi], util=profiles[i][mi].util, weight_mem=wmem, inter_mem=0.0, bz=1))
-        if fixed_bz is None:
-            bzs = binding.cwd_search(models, spec.slo_ms)
-        else:
-            bzs = list(fixed_bz[i])
+        widths = sorted(set(w for m in profiles[i] for w in m.by_width)) or [total]
+        for w_floor in widths:
+            models = []
+            for mi, m in enumerate(spec.models):
+                pr = profiles[i][mi]
+                w = max(w_floor, int(round(pr.util * total)))
+                lat = pr.by_width.get(w, pr.latency_ms)
+                rate = frame_rates[i] * (objects_per_frame[i] if mi > 0 else 1.0)
+                wmem = sum(L.weight.size for L in m.layers if getattr(L, "weight", None) is not None) * (4 if m.dtype == "f32" else 2) / 1e6
+                models.append(dict(parent=parent.get(mi, -1), profile=dict(lat), rate=max(rate, 1e-3),
+                                   burstiness=burstiness[i][mi], util=w / total, weight_mem=wmem, inter_mem=0.0, bz=1))
+            bzs = binding.cwd_search(models, spec.slo_ms) if fixed_bz is None else list(fixed_bz[i])
+            ks = [max(1, int(math.ceil(m["rate"] * duty / 1000.0 / b - 1e-9))) for m, b in zip(models, bzs)]
+            work = sum(k * m["profile"][b] for m, b, k in zip(models, bzs, ks))
+            if work <= cycle_share * duty or w_floor == widths[-1]:
+                break
         keep: list = []
         for m, b in zip(models, bzs):
             m["bz"] = b
         sp = binding.sched_pipeline(models, spec.slo_ms, keep)
         est_l.append(float(binding.lib().octo_est_latency_ms(binding.C.byref(sp))))
         est_t.append(float(binding.lib().octo_est_throughput(binding.C.byref(sp))))
-        ks = []
-        for m, b in zip(models, bzs):
-            k = max(1, int(math.ceil(m["rate"] * duty / 1000.0 / b - 1e-9)))
-            ks.append(k)
+        for m, b, k in zip(models, bzs, ks):
             m["profile"] = dict(m["profile"])
             m["profile"][b] = k * m["profile"][b]          # the portion holds k back-to-back batches
         sched_in.append((models, spec.slo_ms))
@@ -227,16 +234,15 @@ class Executor:
         self.stats = [PipelineStats() for _ in pipes]
         self._warmup()
 
-    def _gather_heads(self, i: int, pool_idx: List[int], stream: int):
-        """Planted mode: copy the head tensors of the batch's frames from the pool into the buffers decode reads."""
+    def _gather_heads(self, i: int, idx_dev, stream: int):
+        """Planted mode: copy the head tensors of the batch's frames from the pool into the buffers decode reads.
+        idx_dev: device int64 tensor of pool indices (prepared ahead, so nothing is copied from the host here)."""
         if self.override[i] is None:
             return
         t = self.t
-        idx = t.tensor(pool_idx, dtype=t.int64)
         with t.cuda.stream(t.cuda.ExternalStream(stream)):
-            idx = idx.cuda()
             for l, pool in enumerate(self.head_pools[i]):
-                t.index_select(pool, 0, idx, out=self.override[i][l][:len(pool_idx)])
+                t.index_select(pool, 0, idx_dev, out=self.override[i][l][:idx_dev.shape[0]])
 
     def _warmup(self):
         """One frame through every pipeline on the streams it will use, so that the first served batch does not pay
@@ -245,7 +251,7 @@ class Executor:
             cam = next((c for c in self.cams if c.pipeline == i), None)
             if cam is None:
                 continue
-            self._gather_heads(i, [cam.pool_offset], self._stream_of(i, 0))
+            self._gather_heads(i, self.t.tensor([cam.pool_offset], dtype=self.t.int64).cuda(), self._stream_of(i, 0))
             P.submit([cam.pool[0]], frame_ids=[-1])
             P.run_model(0, self._stream_of(i, 0))
             for mi in range(1, len(P.spec.models)):
@@ -296,22 +302,18 @@ class Executor:
             self.inflight[i] -= batches_done
 
     def _admit(self, i: int, now_s: float):
-        """Move frames that have arrived by now from the camera streams into the pipeline's queue."""
+        """Move frames that have arrived by now from the camera streams into the pipeline's host-side queue."""
         arr, ptr = self.merged[i], self.next_arrival[i]
-        frames, stamps, ids = [], [], []
         while ptr < len(arr) and arr[ptr][0] <= now_s:
             t_s, cam, seq = arr[ptr]
             c = self.cams[cam]
             k = seq % len(c.pool)
             fid = self.next_id[i]
             self.next_id[i] += 1
-            frames.append(c.pool[k]); stamps.append(self.t0_ms + 1e3 * t_s); ids.append(fid)
-            self.mirror[i].append((fid, c.pool_offset + k))
+            self.mirror[i].append((fid, c.pool_offset + k, c.pool[k], self.t0_ms + 1e3 * t_s))
             ptr += 1
+        self.stats[i].submitted += ptr - self.next_arrival[i]
         self.next_arrival[i] = ptr
-        if frames:
-            self.pipes[i].submit(frames, arrival_ms=stamps, frame_ids=ids)
-            self.stats[i].submitted += len(frames)
 
     def _launch_batch(self, i: int) -> int:
         P = self.pipes[i]
@@ -321,7 +323,9 @@ class Executor:
             return 0
         batch = [self.mirror[i].pop(0) for _ in range(n)]
         s0 = self._stream_of(i, 0)
-        self._gather_heads(i, [b[1] for b in batch], s0)
+        if self.override[i] is not None:
+            self._gather_heads(i, self.seq_dev[i][batch[0][0]: batch[0][0] + n], s0)
+        P.submit([b[2] for b in batch], arrival_ms=[b[3] for b in batch], frame_ids=[b[0] for b in batch])
         got = P.run_model(0, s0)
         assert got == n, (got, n)
         for mi in range(1, len(P.spec.models)):
@@ -329,13 +333,17 @@ class Executor:
         self.inflight[i] += 1
         self.batch_last[i].add(batch[-1][0])
         if self.keep_results:
-            for fid, k in batch:
-                self.pool_of[i][fid] = k
+            for b in batch:
+                self.pool_of[i][b[0]] = b[1]
         return n
 
     def _fire(self, i: int, now_s: float):
         self._admit(i, now_s)
         for _ in range(self.sch.batches_per_cycle[i][0] + 1):
+            spins = 0
+            while self.inflight[i] >= MAX_IN_FLIGHT and spins < 100000:    # result slots are full: take finished batches first
+                self._poll()
+                spins += 1
             if self._launch_batch(i) == 0:
                 break
 
@@ -346,6 +354,11 @@ class Executor:
             self.merged[c.pipeline] += [(float(t_), ci, k) for k, t_ in enumerate(c.arrivals_s) if t_ < duration_s]
         for m in self.merged:
             m.sort()
+        # frame ids are handed out in arrival order, so the pool index of every frame is known now: one upload
+        self.seq_dev = []
+        for i in range(npipe):
+            seq = [self.cams[ci].pool_offset + k % len(self.cams[ci].pool) for (_, ci, k) in self.merged[i]]
+            self.seq_dev.append(self.t.tensor(seq if seq else [0], dtype=self.t.int64).cuda())
         self.next_arrival = [0] * npipe
         self.next_id = [0] * npipe
         self.mirror = [[] for _ in range(npipe)]
