@@ -55,10 +55,13 @@ def make_workload(name: str):
 def conv_name(kid: int, dtype: str) -> str:
     """Template instance behind a conv kernel id (digits 1 BBB PPP K M V), as rocprofv3 prints it."""
     d = kid - 1000000000
-    bc, bp, kv, minb, vec = d // 1000000, (d // 1000) % 1000, (d // 100) % 10, (d // 10) % 10, d % 10
+    bc, bp, kv, minb, v = d // 1000000, (d // 1000) % 1000, (d // 100) % 10, (d // 10) % 10, d % 10
+    vec, dma = v & 1, v >> 1
     wc, wp = (1, 4) if bc == 32 else (2, 2)
+    depth = 1 if (dma and kv == 8) else 2
     ctype = {"f16": "_Float16", "bf16": "__bf16", "f32": "float"}[dtype]
-    return "octo::conv_mfma_kernel<%s, %d, %d, %d, %d, %d, 2, %d, %s>" % (ctype, bc, bp, wc, wp, kv, minb, "true" if vec else "false")
+    return "octo::conv_mfma_kernel<%s, %d, %d, %d, %d, %d, %d, %d, %s, %s>" % (
+        ctype, bc, bp, wc, wp, kv, depth, minb, "true" if vec else "false", "true" if dma else "false")
 
 
 # HBM traffic per launch of the dominant kernel, from `rocprofv3 --pmc FETCH_SIZE` and `--pmc WRITE_SIZE` runs of

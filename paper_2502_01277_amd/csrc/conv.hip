@@ -7,15 +7,17 @@
 // GEMM view: rows = output channels (weights, [Cout][K] with K = kh*kw*Cin contiguous),
 // columns = output pixels (gathered on the fly from the NHWC input), reduction = K.
 // One workgroup = 4 wavefronts (256 lanes) computes a BC x BP tile with
-// v_mfma_f32_32x32x16 (fp16 / bf16) or v_mfma_f32_32x32x2 (fp32).  Both operands go
-// global -> registers -> LDS (double buffered, one barrier per K step); each lane
-// feeds the MFMA with 16-byte LDS reads from rows padded by 16 bytes (conflict free).
+// v_mfma_f32_32x32x16 (fp16 / bf16) or v_mfma_f32_32x32x2 (fp32).  Operands reach LDS in one of two ways: straight
+// from global memory (buffer loads with the LDS bit, a ring of stages, one barrier per K step; the path of all layers
+// with more than 32 output channels), or through registers (double buffered; 3-channel first layers, whose gather is
+// element-wise, and layers with up to 32 output channels).  A tile row is 64 or 128 bytes of K; its 16-byte vectors
+// are XOR-swizzled so that both the fills and the MFMA operand reads (16 bytes per lane) are bank-conflict free.
 //
 // The inner loop is kept nearly free of vector-ALU work, which would otherwise
 // starve the matrix cores: operands are fetched with buffer loads whose 32-bit
 // offsets are "row offset + tap offset", an out-of-image tap gets an offset beyond
 // the buffer range so the hardware returns zeros, and the weight offsets advance
-// through the scalar offset operand.  Loads run D K-steps ahead of the MFMA work.
+// through the scalar offset operand.
 //
 // The grid is persistent: workgroups stride over the tile list, whose length may
 // depend on an item count that lives in device memory (a variable number of ROIs),
@@ -88,7 +90,11 @@ constexpr long long BUF_MAX = 0x7FFFFFFFLL;
 // BC: output channels per tile, BP: pixels per tile, WC x WP: wavefront grid (WC * WP == 4),
 // KV: 16-byte vectors per tile row and K step (one K step = KV*16 bytes of K per row),
 // D: K steps whose global loads are in flight in registers (even), MINB: workgroups per CU to fit registers for.
-template <typename T, int BC, int BP, int WC, int WP, int KV, int D, int MINB, bool VEC>
+// DMA: operands go global -> LDS directly (buffer loads with the LDS bit), D K-steps ahead, into a ring of D + 1 LDS
+// stages; no registers are spent on staging and no LDS store instructions are issued.  The loads are issued from
+// inline assembly (the wave's LDS destination is base M0 + lane * 16), and their completion is awaited with explicit
+// vmcnt waits whose counts rely on every wave issuing the same number of loads per K step.
+template <typename T, int BC, int BP, int WC, int WP, int KV, int D, int MINB, bool VEC, bool DMA = false>
 __global__ __launch_bounds__(THREADS, MINB) void conv_mfma_kernel(const ConvArgs a) {
   using E = Elem<T>;
   constexpr int VN = E::N;
@@ -102,13 +108,17 @@ __global__ __launch_bounds__(THREADS, MINB) void conv_mfma_kernel(const ConvArgs
   constexpr int TP = BP / WP / 32;
   constexpr int LA = (BC + RP - 1) / RP; // vectors per lane per K step (weights)
   constexpr int LB = BP / RP;            // (pixels)
-  static_assert(D % 2 == 0, "pipeline depth must be even");
+  static_assert(DMA || D % 2 == 0, "pipeline depth must be even");
   static_assert(WC * WP == 4 && TC >= 1 && TP >= 1 && LB >= 1 && BP % RP == 0 && BC % 32 == 0, "tile shape");
+  static_assert(!DMA || (VEC && BC % RP == 0), "direct-to-LDS loads need whole passes of all lanes");
+  constexpr int NST = DMA ? D + 1 : 2;   // LDS stages
+  constexpr int STAGE_VECS_OP = (BC + BP) * ROWV;
+  constexpr int NL = LA + LB;            // load instructions per wave and K step
 
   // operand tiles; after the K loop the same memory stages the output tile as [pixel][channel] so that it can be
   // written with 16-byte stores that cover whole cache lines
   constexpr int OPITCH = BC * ES + 16;                                    // bytes per staged output row
-  constexpr int OPER_VECS = 2 * (BC + BP) * ROWV;                         // double-buffered operand tiles
+  constexpr int OPER_VECS = NST * (BC + BP) * ROWV;                       // operand tiles, all stages
   constexpr int STAGE_VECS = BP * OPITCH / 16;                            // output tile
   constexpr bool STAGED = STAGE_VECS <= 4096;                             // stage outputs of up to 64 KB
   constexpr int SMEM_VECS = STAGED && STAGE_VECS > OPER_VECS ? STAGE_VECS : OPER_VECS;
@@ -140,6 +150,8 @@ __global__ __launch_bounds__(THREADS, MINB) void conv_mfma_kernel(const ConvArgs
   // lanes that read the same logical vector of sixteen consecutive rows, then each touch a different 16-byte bank group.
   // 32 and THREADS / KV are multiples of RPW * KV, so the swizzle term depends only on the lane.
   const int wsw = ld_kv ^ ((ld_row / RPW) % KV);      // slot this lane writes
+  // direct-to-LDS: the lane's slot is fixed by its lane id (ld_kv), so it fetches the vector that belongs there
+  const int lkv = DMA ? wsw : ld_kv;                  // logical vector this lane fetches
   const int rsw = (l32 / RPW) % KV;                   // XOR term for this lane's fragment reads
   const bool vec_ok = ((a.y_ld | a.y_coff) & 3) == 0 && (!a.res || ((a.res_ld | a.res_coff) & 3) == 0);
   const bool is_silu = a.act == OCTO_ACT_SILU;
@@ -199,7 +211,7 @@ __global__ __launch_bounds__(THREADS, MINB) void conv_mfma_kernel(const ConvArgs
     }
     int woff[LA];
 #pragma unroll
-    for (int i = 0; i < LA; ++i) woff[i] = ((c0 + ld_row + RP * i) * a.Kp + ld_kv * VN) * ES;
+    for (int i = 0; i < LA; ++i) woff[i] = ((c0 + ld_row + RP * i) * a.Kp + lkv * VN) * ES;
 
     floatx16 acc[TC][TP];
 #pragma unroll
@@ -209,17 +221,72 @@ __global__ __launch_bounds__(THREADS, MINB) void conv_mfma_kernel(const ConvArgs
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
 
+    // Operands of K step KB.  Element k = KB*BK + lkv*VN of the reduction is channel c of tap (r, s):
+    // k = (r*kw + s)*Cin + c; the two divisions use precomputed reciprocals (exact for k < 65536).
+    __syncthreads();   // the previous tile's LDS reads are done
+    if (tid < BC) sBias[tid] = a.bias[c0 + tid];     // bias is padded to a multiple of 128 channels
+    if constexpr (DMA) {
+      // LDS byte address of this wave's 1 KB slice of pass 0 of stage 0 (lane l writes at + 16 l)
+      const unsigned lds_wave = (unsigned)__builtin_amdgcn_readfirstlane((int)((unsigned)(uintptr_t)smem + (unsigned)wave * 1024u));
+      constexpr unsigned STAGE_BYTES = STAGE_VECS_OP * 16, PASS_BYTES = RP * ROWV * 16, A_BYTES = BC * ROWV * 16;
+#define OCTO_CONV_DMA(KB, ST)                                                                                       \
+      {                                                                                                             \
+        const unsigned sbase = lds_wave + (unsigned)(ST) * STAGE_BYTES;                                             \
+        const int koff = (KB) * (BK * ES);                                                                          \
+        _Pragma("unroll") for (int i = 0; i < LA; ++i)                                                              \
+          asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"                  \
+                       :: "s"(sbase + i * PASS_BYTES), "v"(woff[i]), "s"(rsrc_w), "s"(koff) : "memory");             \
+        const unsigned k = (unsigned)(KB) * BK + lkv * VN;                                                          \
+        const unsigned tap = __umulhi(k, a.magic_cin);                                                              \
+        const int c = (int)(k - tap * a.Cin);                                                                       \
+        const int r = a.kw == 1 ? (int)tap : (int)__umulhi(tap, a.magic_kw);                                        \
+        const int s2 = (int)tap - r * a.kw;                                                                         \
+        const int delta = ((r * a.W + s2) * a.x_ld + c) * ES;                                                       \
+        const unsigned need = k < (unsigned)a.K ? ((1u << r) | (0x10000u << s2)) : 0xFFFFFFFFu;                     \
+        _Pragma("unroll") for (int i = 0; i < LB; ++i) {                                                            \
+          const int off = (hw_ok[i] & need) == need ? rowoff[i] + delta : OOB;                                      \
+          asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"                   \
+                       :: "s"(sbase + A_BYTES + i * PASS_BYTES), "v"(off), "s"(rsrc_x) : "memory");                  \
+        }                                                                                                           \
+      }
+      int st_rd = 0, st_wr = D;          // ring positions: stage read in this step, stage filled for step kb + D
+#pragma unroll
+      for (int d = 0; d < D; ++d) OCTO_CONV_DMA(d, d)
+      for (int kb = 0; kb < nk; ++kb) {
+        // loads of the D - 1 later steps may stay in flight; those of step kb (issued before them) are complete
+        asm volatile("s_waitcnt vmcnt(%0)" :: "n"((D - 1) * NL) : "memory");
+        __builtin_amdgcn_s_barrier();    // everyone's part of step kb is in LDS, and everyone is done reading step kb - 1
+        OCTO_CONV_DMA(kb + D, st_wr)     // refills the stage that step kb - 1 read; past the last step: zeros, never read
+        const u32x4* pa = smem + st_rd * STAGE_VECS_OP;
+        const u32x4* pb = pa + BC * ROWV;
+#pragma unroll
+        for (int kk = 0; kk < KV / 2; ++kk) {
+          u32x4 fa[TC], fb[TP];
+#pragma unroll
+          for (int i = 0; i < TC; ++i) fa[i] = pa[(wc * (BC / WC) + i * 32 + l32) * ROWV + ((kk * 2 + g) ^ rsw)];
+#pragma unroll
+          for (int j = 0; j < TP; ++j) fb[j] = pb[(wp * (BP / WP) + j * 32 + l32) * ROWV + ((kk * 2 + g) ^ rsw)];
+#pragma unroll
+          for (int i = 0; i < TC; ++i)
+#pragma unroll
+            for (int j = 0; j < TP; ++j) acc[i][j] = E::mfma(fa[i], fb[j], acc[i][j]);
+        }
+        st_rd = st_rd + 1 == NST ? 0 : st_rd + 1;
+        st_wr = st_wr + 1 == NST ? 0 : st_wr + 1;
+      }
+#undef OCTO_CONV_DMA
+      // the loads issued past the last step still write (zeros) into the ring: drain them before the memory is reused
+      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+      __syncthreads();
+    } else {
     u32x4 ra[D][LA], rb[D][LB];
-
-    // Operands of K step KB -> register slot SL.  Element k = KB*BK + ld_kv*VN of the reduction is channel c of tap
-    // (r, s): k = (r*kw + s)*Cin + c; the two divisions use precomputed reciprocals (exact for k < 65536).
 #define OCTO_CONV_LOAD(KB, SL)                                                                                      \
     {                                                                                                               \
       _Pragma("unroll") for (int i = 0; i < LA; ++i)                                                                \
         if (BC % RP == 0 || ld_row + RP * i < BC)                                                                   \
           ra[SL][i] = __builtin_amdgcn_raw_buffer_load_b128(rsrc_w, woff[i], (KB) * (BK * ES), 0);                  \
       if (VEC) {                                                                                                    \
-        const unsigned k = (unsigned)(KB) * BK + ld_kv * VN;                                                        \
+        const unsigned k = (unsigned)(KB) * BK + lkv * VN;                                                          \
         const unsigned tap = __umulhi(k, a.magic_cin);                                                              \
         const int c = (int)(k - tap * a.Cin);                                                                       \
         const int r = a.kw == 1 ? (int)tap : (int)__umulhi(tap, a.magic_kw);                                        \
@@ -252,8 +319,6 @@ __global__ __launch_bounds__(THREADS, MINB) void conv_mfma_kernel(const ConvArgs
       }                                                                                                             \
     }
 
-    __syncthreads();   // the previous tile's LDS reads are done
-    if (tid < BC) sBias[tid] = a.bias[c0 + tid];     // bias is padded to a multiple of 128 channels
     // nk is a multiple of D (the packed K extent is padded accordingly); loads past the end return zeros
 #pragma unroll
     for (int d = 0; d < D; ++d) OCTO_CONV_LOAD(d, d)
@@ -285,6 +350,7 @@ __global__ __launch_bounds__(THREADS, MINB) void conv_mfma_kernel(const ConvArgs
       }
     }
 #undef OCTO_CONV_LOAD
+    }
 
     // epilogue: a lane holds pixel column l32 of each 32x32 block and 4 groups of 4 consecutive channels
     const bool staged = STAGED && !a.out_f32 && ((a.y_ld | a.y_coff) & (VN - 1)) == 0 && (((uintptr_t)a.y & 15) == 0);
@@ -384,7 +450,7 @@ __global__ __launch_bounds__(THREADS, MINB) void conv_mfma_kernel(const ConvArgs
 
 // kernel id of a conv tile configuration, decimal digits 1 BBB PPP K M V: channel tile, pixel tile, 16-byte vectors per
 // K step, workgroups per CU the registers are sized for, vectorised gather
-int conv_kernel_id(int bc, int bp, int kv, int minb, bool vec) { return 1000000000 + bc * 1000000 + bp * 1000 + kv * 100 + minb * 10 + (vec ? 1 : 0); }
+int conv_kernel_id(int bc, int bp, int kv, int minb, bool vec, bool dma) { return 1000000000 + bc * 1000000 + bp * 1000 + kv * 100 + minb * 10 + (vec ? 1 : 0) + (dma ? 2 : 0); }
 
 size_t conv_packed_weight_elems(int cout, int kh, int kw, int cin, int dtype, int* kp_out, int* cout_pad_out) {
   const int vn = dtype == OCTO_F32 ? 4 : 8;
@@ -398,9 +464,9 @@ size_t conv_packed_weight_elems(int cout, int kh, int kw, int cin, int dtype, in
 }
 
 #ifndef OCTO_CONV_NO_LAUNCHERS
-template <typename T, int BC, int BP, int WC, int WP, int KV, int D, int MINB, bool VEC>
+template <typename T, int BC, int BP, int WC, int WP, int KV, int D, int MINB, bool VEC, bool DMA = false>
 static hipError_t launch_cfg(const ConvArgs& a, int num_cu, hipStream_t s, int* kernel_id, const ConvTiming& tm) {
-  if (kernel_id) *kernel_id = conv_kernel_id(BC, BP, KV, MINB, VEC);
+  if (kernel_id) *kernel_id = conv_kernel_id(BC, BP, KV, MINB, VEC, DMA);
   const long long M = (long long)a.n * a.Ho * a.Wo;
   const long long tiles = ((M + BP - 1) / BP) * ((a.Cout + BC - 1) / BC);
   if (tiles <= 0) return hipSuccess;
@@ -409,9 +475,9 @@ static hipError_t launch_cfg(const ConvArgs& a, int num_cu, hipStream_t s, int* 
   if (grid > cap) grid = cap;
   // with timing events the dispatch itself carries them, so their difference is the kernel's own run time
   if (tm.start && tm.stop)
-    hipExtLaunchKernelGGL((conv_mfma_kernel<T, BC, BP, WC, WP, KV, D, MINB, VEC>), dim3((unsigned)grid), dim3(THREADS), 0, s, tm.start, tm.stop, 0, a);
+    hipExtLaunchKernelGGL((conv_mfma_kernel<T, BC, BP, WC, WP, KV, D, MINB, VEC, DMA>), dim3((unsigned)grid), dim3(THREADS), 0, s, tm.start, tm.stop, 0, a);
   else
-    hipLaunchKernelGGL((conv_mfma_kernel<T, BC, BP, WC, WP, KV, D, MINB, VEC>), dim3((unsigned)grid), dim3(THREADS), 0, s, a);
+    hipLaunchKernelGGL((conv_mfma_kernel<T, BC, BP, WC, WP, KV, D, MINB, VEC, DMA>), dim3((unsigned)grid), dim3(THREADS), 0, s, a);
   return hipGetLastError();
 }
 
@@ -429,21 +495,15 @@ static hipError_t launch_typed(const ConvArgs& a, int num_cu, hipStream_t s, int
     if (a.Cout <= 32) return launch_cfg<T, 32, 128, 1, 4, 4, 2, 2, false>(a, num_cu, s, kernel_id, tm);
     return launch_cfg<T, 64, 128, 2, 2, 4, 2, 2, false>(a, num_cu, s, kernel_id, tm);
   }
-  // Tile choice (measured on MI355X): the widest tile whose tile count still covers the chip; K steps of 128 bytes
-  // when the padded reduction length allows it; small tiles at high occupancy for layers with few output pixels.
+  // Tile choice (measured on MI355X).  Up to 32 output channels: register-staged 32x128 tiles.  Otherwise operands
+  // go straight into LDS with K steps of 128 bytes: 128x128 tiles where 128 channels per tile pad the channel count
+  // no further than 64 do (192 = 3 x 64, but 2 x 128) and there are enough tiles to cover the chip, 64x128 tiles for
+  // the middle ground, 64x64 tiles at high occupancy for layers with few output pixels.
   if (a.Cout <= 32) return launch_cfg<T, 32, 128, 1, 4, 4, 2, 4, true>(a, num_cu, s, kernel_id, tm);
-  // 256 channels per tile only where that pads the channel count no further than 128 does (384 = 3 x 128, but 2 x 256)
-  const bool fits256 = (a.Cout + 255) / 256 * 256 == (a.Cout + 127) / 128 * 128;
-  if (a.Cout > 128 && fits256 && tiles(256, 128) >= 2 * num_cu) return launch_cfg<T, 256, 128, 2, 2, 4, 2, 2, true>(a, num_cu, s, kernel_id, tm);
-  if (a.Cout >= 96 && tiles(128, 128) >= num_cu) {
-    if (sizeof(T) == 2 && a.Kp % (16 * VN) == 0) return launch_cfg<T, 128, 128, 2, 2, 8, 2, 2, true>(a, num_cu, s, kernel_id, tm);
-    return launch_cfg<T, 128, 128, 2, 2, 4, 2, 2, true>(a, num_cu, s, kernel_id, tm);
-  }
-  if (tiles(64, 128) >= num_cu / 2) {
-    if (sizeof(T) == 2 && a.Kp % (16 * VN) == 0) return launch_cfg<T, 64, 128, 2, 2, 8, 2, 2, true>(a, num_cu, s, kernel_id, tm);
-    return launch_cfg<T, 64, 128, 2, 2, 4, 2, 3, true>(a, num_cu, s, kernel_id, tm);
-  }
-  return launch_cfg<T, 64, 64, 2, 2, 4, 2, 4, true>(a, num_cu, s, kernel_id, tm);
+  const bool fits128 = a.Cout >= 96 && (a.Cout + 127) / 128 * 128 == (a.Cout + 63) / 64 * 64;
+  if (fits128 && tiles(128, 128) >= 5 * num_cu / 4) return launch_cfg<T, 128, 128, 2, 2, 8, 1, 2, true, true>(a, num_cu, s, kernel_id, tm);
+  if (tiles(64, 128) >= 9 * num_cu / 8) return launch_cfg<T, 64, 128, 2, 2, 8, 1, 3, true, true>(a, num_cu, s, kernel_id, tm);
+  return launch_cfg<T, 64, 64, 2, 2, 8, 1, 4, true, true>(a, num_cu, s, kernel_id, tm);
 }
 
 // Checks the limits the kernel relies on and fills the precomputed reciprocals.
