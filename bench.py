@@ -69,13 +69,11 @@ def conv_name(kid: int, dtype: str) -> str:
 # calibration pass of known size).  Valid only for the kernel source it was taken with: keyed by a hash of conv.hip.
 TRAFFIC = {
     # sha256(conv.hip)[:16]: {kernel name: bytes per launch}
-    "1049c95ad57aabeb": {
-        "octo::conv_mfma_kernel<_Float16, 64, 128, 2, 2, 8, 2, 2, true>": 21613621,
-        "octo::conv_mfma_kernel<_Float16, 64, 128, 2, 2, 4, 2, 3, true>": 39364148,
-        "octo::conv_mfma_kernel<_Float16, 32, 128, 1, 4, 4, 2, 4, true>": 32051856,
-        "octo::conv_mfma_kernel<_Float16, 128, 128, 2, 2, 8, 2, 2, true>": 35348209,
-        "octo::conv_mfma_kernel<_Float16, 64, 64, 2, 2, 4, 2, 4, true>": 8258069,
-        "octo::conv_mfma_kernel<_Float16, 128, 128, 2, 2, 4, 2, 2, true>": 34173186,
+    "524f88f476795a5f": {
+        "octo::conv_mfma_kernel<_Float16, 64, 128, 2, 2, 8, 1, 3, true, true>": 35377025,
+        "octo::conv_mfma_kernel<_Float16, 64, 64, 2, 2, 8, 1, 4, true, true>": 13365522,
+        "octo::conv_mfma_kernel<_Float16, 128, 128, 2, 2, 8, 1, 2, true, true>": 34821269,
+        "octo::conv_mfma_kernel<_Float16, 32, 128, 1, 4, 4, 2, 4, true, false>": 32045464,
     },
 }
 
