@@ -57,8 +57,8 @@ def conv_name(kid: int, dtype: str) -> str:
     d = kid - 1000000000
     bc, bp, kv, minb, v = d // 1000000, (d // 1000) % 1000, (d // 100) % 10, (d // 10) % 10, d % 10
     vec, dma = v & 1, v >> 1
-    wc, wp = (1, 4) if bc == 32 else (2, 2)
-    depth = 1 if (dma and kv == 8) else 2
+    wc, wp = (1, 4) if (bc == 32 or bp == 256) else (2, 2)
+    depth = 1 if dma else 2
     ctype = {"f16": "_Float16", "bf16": "__bf16", "f32": "float"}[dtype]
     return "octo::conv_mfma_kernel<%s, %d, %d, %d, %d, %d, %d, %d, %s, %s>" % (
         ctype, bc, bp, wc, wp, kv, depth, minb, "true" if vec else "false", "true" if dma else "false")

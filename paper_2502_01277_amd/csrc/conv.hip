@@ -498,10 +498,13 @@ static hipError_t launch_typed(const ConvArgs& a, int num_cu, hipStream_t s, int
   // Tile choice (measured on MI355X).  Up to 32 output channels: register-staged 32x128 tiles.  Otherwise operands
   // go straight into LDS with K steps of 128 bytes: 128x128 tiles where 128 channels per tile pad the channel count
   // no further than 64 do (192 = 3 x 64, but 2 x 128) and there are enough tiles to cover the chip, 64x128 tiles for
-  // the middle ground, 64x64 tiles at high occupancy for layers with few output pixels.
+  // the middle ground (64x256 with 64-byte K steps for very large, narrow layers), 64x64 tiles at high occupancy for
+  // layers with few output pixels.
   if (a.Cout <= 32) return launch_cfg<T, 32, 128, 1, 4, 4, 2, 4, true>(a, num_cu, s, kernel_id, tm);
   const bool fits128 = a.Cout >= 96 && (a.Cout + 127) / 128 * 128 == (a.Cout + 63) / 64 * 64;
   if (fits128 && tiles(128, 128) >= 5 * num_cu / 4) return launch_cfg<T, 128, 128, 2, 2, 8, 1, 2, true, true>(a, num_cu, s, kernel_id, tm);
+  // very many pixels and at most 64 channels (store-bound first layers, wide early stages): 256-pixel tiles
+  if (a.Cout <= 64 && tiles(64, 256) >= 4 * num_cu) return launch_cfg<T, 64, 256, 1, 4, 4, 1, 3, true, true>(a, num_cu, s, kernel_id, tm);
   if (tiles(64, 128) >= 9 * num_cu / 8) return launch_cfg<T, 64, 128, 2, 2, 8, 1, 3, true, true>(a, num_cu, s, kernel_id, tm);
   return launch_cfg<T, 64, 64, 2, 2, 8, 1, 4, true, true>(a, num_cu, s, kernel_id, tm);
 }

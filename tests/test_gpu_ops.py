@@ -96,6 +96,7 @@ CONV_CASES = [
     (14, 14, 24, 520, 1, 1, 0, 1), (5, 5, 200, 72, 3, 1, 1, 2),
     # enough output pixels for the wide tiles: 256x128 (ragged channel tail), 128x128, 64x128 with 64- and 32-element K steps
     (128, 128, 16, 200, 1, 1, 0, 4), (96, 96, 16, 128, 3, 1, 1, 4), (64, 64, 128, 64, 1, 1, 0, 4), (64, 64, 64, 64, 1, 1, 0, 4),
+    (256, 256, 8, 48, 1, 1, 0, 4),          # 64x256 tiles
 ]
 
 
