@@ -93,7 +93,8 @@ constexpr long long BUF_MAX = 0x7FFFFFFFLL;
 // DMA: operands go global -> LDS directly (buffer loads with the LDS bit), D K-steps ahead, into a ring of D + 1 LDS
 // stages; no registers are spent on staging and no LDS store instructions are issued.  The loads are issued from
 // inline assembly (the wave's LDS destination is base M0 + lane * 16), and their completion is awaited with explicit
-// vmcnt waits whose counts rely on every wave issuing the same number of loads per K step.
+// vmcnt waits whose counts rely on every wave issuing the same number of loads per K step.  M0 is reserved by the
+// compiler (it writes M0 immediately before each of its own uses), so setting it inside the asm statement is safe.
 template <typename T, int BC, int BP, int WC, int WP, int KV, int D, int MINB, bool VEC, bool DMA = false>
 __global__ __launch_bounds__(THREADS, MINB) void conv_mfma_kernel(const ConvArgs a) {
   using E = Elem<T>;

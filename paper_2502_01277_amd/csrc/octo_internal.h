@@ -66,6 +66,22 @@ hipError_t launch_gap(int dtype, const PoolArgs& a, hipStream_t s);             
 hipError_t launch_argmax(const float* logits, int ld, int n_out, const int* n_dyn, int n, int* labels, hipStream_t s);
 hipError_t launch_fill_i32(int* p, int value, int count, hipStream_t s);
 
+// floor(n / d) for n < 2^31 by multiply-high and shift; built on the host
+struct FastDiv { unsigned mul, shift; int is_one; };
+inline FastDiv make_fastdiv(unsigned d) {
+  FastDiv f{0u, 0u, d <= 1u ? 1 : 0};
+  if (f.is_one) return f;
+  unsigned s = 0;
+  while ((1ull << s) < d) ++s;
+  const unsigned long long m = ((1ull << (32 + s)) + d - 1) / d;
+  if (m >> 32) { f.mul = (unsigned)(((1ull << (31 + s)) + d - 1) / d); f.shift = s - 1; }
+  else { f.mul = (unsigned)m; f.shift = s; }
+  return f;
+}
+#ifdef __HIPCC__
+__device__ __forceinline__ unsigned fast_div(unsigned n, const FastDiv& f) { return f.is_one ? n : __umulhi(n, f.mul) >> f.shift; }
+#endif
+
 struct ResizeArgs {
   const uint8_t* const* frames;   // device table of frame base pointers
   const size_t* pitches;          // device table of row pitches in bytes
@@ -78,6 +94,7 @@ struct ResizeArgs {
   // crop mode only
   const octo_roi* rois;
   int n_frames;                   // frames behind `frames` (ROI frame indices are clamped to it)
+  FastDiv div_wq, div_h;          // set by the launchers: lanes per output row, rows per item
 };
 void letterbox_geometry(int src_h, int src_w, int dst_h, int dst_w, int* nw, int* nh, int* left, int* top);
 hipError_t launch_letterbox(int dtype, const ResizeArgs& a, hipStream_t s);

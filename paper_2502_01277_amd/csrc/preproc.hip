@@ -80,14 +80,14 @@ __global__ void letterbox_kernel(const ResizeArgs a, const LetterboxGeom g) {
   const int wq = a.dst_w / PX;
   int n_items = a.n;
   if (a.n_dyn) { int d = *a.n_dyn; n_items = d < a.n ? d : a.n; }
-  const long long total = (long long)n_items * a.dst_h * wq;
+  const unsigned total = (unsigned)n_items * (unsigned)a.dst_h * (unsigned)wq;       // < 2^31 (checked by the launcher)
   T* dst = (T*)a.dst;
   const int rx = a.src_w / g.nw, ry = a.src_h / g.nh;      // only meaningful when EXACT
-  for (long long i = blockIdx.x * (long long)blockDim.x + threadIdx.x; i < total; i += (long long)gridDim.x * blockDim.x) {
-    const int xq = (int)(i % wq);
-    const long long t = i / wq;
-    const int y = (int)(t % a.dst_h);
-    const int img = (int)(t / a.dst_h);
+  for (unsigned i = blockIdx.x * blockDim.x + threadIdx.x; i < total; i += gridDim.x * blockDim.x) {
+    const unsigned t = fast_div(i, a.div_wq);
+    const int xq = (int)(i - t * (unsigned)wq);
+    const int img = (int)fast_div(t, a.div_h);
+    const int y = (int)(t - (unsigned)img * (unsigned)a.dst_h);
     float v[3 * PX];
     const int yi = y - g.top;
     const bool row_in = (unsigned)yi < (unsigned)g.nh;
@@ -137,13 +137,13 @@ __global__ void crop_resize_kernel(const ResizeArgs a) {
   const int wq = a.dst_w / PX;
   int n_items = a.n;
   if (a.n_dyn) { int d = *a.n_dyn; n_items = d < a.n ? (d < 0 ? 0 : d) : a.n; }
-  const long long total = (long long)n_items * a.dst_h * wq;
+  const unsigned total = (unsigned)n_items * (unsigned)a.dst_h * (unsigned)wq;       // < 2^31 (checked by the launcher)
   T* dst = (T*)a.dst;
-  for (long long i = blockIdx.x * (long long)blockDim.x + threadIdx.x; i < total; i += (long long)gridDim.x * blockDim.x) {
-    const int xq = (int)(i % wq);
-    const long long t = i / wq;
-    const int y = (int)(t % a.dst_h);
-    const int roi = (int)(t / a.dst_h);
+  for (unsigned i = blockIdx.x * blockDim.x + threadIdx.x; i < total; i += gridDim.x * blockDim.x) {
+    const unsigned t = fast_div(i, a.div_wq);
+    const int xq = (int)(i - t * (unsigned)wq);
+    const int roi = (int)fast_div(t, a.div_h);
+    const int y = (int)(t - (unsigned)roi * (unsigned)a.dst_h);
     const octo_roi r = a.rois[roi];
     const int fr = clampi(r.frame, 0, a.n_frames - 1);
     const uint8_t* base = a.frames[fr];
@@ -192,6 +192,16 @@ void letterbox_geometry(int src_h, int src_w, int dst_h, int dst_w, int* nw, int
   *nw = g.nw; *nh = g.nh; *left = g.left; *top = g.top;
 }
 
+// lanes per output row for the pixel-group width the dispatch below will pick
+static bool resize_prepare(ResizeArgs& a) {
+  const bool px4 = a.dst_w % 4 == 0 && ((uintptr_t)a.dst & 15) == 0;
+  const int wq = px4 ? a.dst_w / 4 : a.dst_w;
+  if ((long long)a.n * a.dst_h * wq >= 0x7FFFFFFFLL || a.dst_h < 1 || wq < 1) return false;
+  a.div_wq = make_fastdiv((unsigned)wq);
+  a.div_h = make_fastdiv((unsigned)a.dst_h);
+  return true;
+}
+
 template <typename T, bool EXACT> static hipError_t letterbox_e(const ResizeArgs& a, const LetterboxGeom& g, hipStream_t s) {
   if (a.dst_c == 4 && ((uintptr_t)a.dst & 15) == 0 && a.dst_w % 4 == 0) {
     hipLaunchKernelGGL((letterbox_kernel<T, 4, true, EXACT>), dim3(resize_grid((long long)a.n * a.dst_h * (a.dst_w / 4))), dim3(256), 0, s, a, g);
@@ -222,9 +232,10 @@ template <typename T> static hipError_t crop_t(const ResizeArgs& a, hipStream_t 
   return hipGetLastError();
 }
 
-hipError_t launch_letterbox(int dtype, const ResizeArgs& a, hipStream_t s) {
-  if (a.n <= 0) return hipSuccess;
-  if ((a.dst_c != 3 && a.dst_c != 4) || a.src_w < 4) return hipErrorInvalidValue;
+hipError_t launch_letterbox(int dtype, const ResizeArgs& a0, hipStream_t s) {
+  if (a0.n <= 0) return hipSuccess;
+  ResizeArgs a = a0;
+  if ((a.dst_c != 3 && a.dst_c != 4) || a.src_w < 4 || !resize_prepare(a)) return hipErrorInvalidValue;
   switch (dtype) {
     case OCTO_F32: return letterbox_t<float>(a, s);
     case OCTO_F16: return letterbox_t<_Float16>(a, s);
@@ -232,9 +243,10 @@ hipError_t launch_letterbox(int dtype, const ResizeArgs& a, hipStream_t s) {
   }
   return hipErrorInvalidValue;
 }
-hipError_t launch_crop_resize(int dtype, const ResizeArgs& a, hipStream_t s) {
-  if (a.n <= 0) return hipSuccess;
-  if ((a.dst_c != 3 && a.dst_c != 4) || a.src_w < 4) return hipErrorInvalidValue;
+hipError_t launch_crop_resize(int dtype, const ResizeArgs& a0, hipStream_t s) {
+  if (a0.n <= 0) return hipSuccess;
+  ResizeArgs a = a0;
+  if ((a.dst_c != 3 && a.dst_c != 4) || a.src_w < 4 || !resize_prepare(a)) return hipErrorInvalidValue;
   switch (dtype) {
     case OCTO_F32: return crop_t<float>(a, s);
     case OCTO_F16: return crop_t<_Float16>(a, s);

@@ -57,6 +57,21 @@ def test_workspace_size_and_host_validation():
     assert L.octo_now_ms() > 0
 
 
+def test_stream_masks_are_validated_on_the_host():
+    """A compute-unit mask that leaves one of the eight dies without units is refused before any HIP call (bit i of a
+    mask selects unit i / 8 of die i % 8), and so are empty arguments."""
+    L = binding.lib()
+    out = C.c_void_p()
+    one_die = (C.c_uint32 * 8)(*([0x01010101] * 8))            # bits 0, 8, 16, ...: die 0 only
+    assert L.octo_stream_create_masked(one_die, 8, C.byref(out)) == binding.EINVAL
+    two_dies = (C.c_uint32 * 8)(*([0x03030303] * 8))
+    assert L.octo_stream_create_masked(two_dies, 8, C.byref(out)) == binding.EINVAL
+    assert L.octo_stream_create_masked(None, 8, C.byref(out)) == binding.EINVAL
+    assert L.octo_stream_create_masked(one_die, 0, C.byref(out)) == binding.EINVAL
+    assert L.octo_stream_destroy(None) == binding.EINVAL
+    assert out.value is None
+
+
 def _rand_models(rng, n):
     ms = []
     for i in range(n):
