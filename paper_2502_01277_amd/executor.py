@@ -125,7 +125,7 @@ class Schedule:
 
 def plan(specs, profiles: List[List[ModelProfile]], frame_rates: Sequence[float], objects_per_frame: Sequence[float],
          burstiness: Sequence[Sequence[float]], n_streams: int = 8, gpu_mem_mb: float = 288e3,
-         fixed_bz: Optional[List[List[int]]] = None, cycle_share: float = 0.8) -> Schedule:
+         fixed_bz: Optional[List[List[int]]] = None, cycle_share: float = 0.5) -> Schedule:
     """Scheduler-lite: Algorithm 1's batch-size search per pipeline, then Algorithm 2 over all pipelines.
 
     Widths: every model starts at the width its profile chose; if the pipeline's work per duty cycle (sum over its
@@ -432,7 +432,7 @@ class Colocation:
 
 def make_colocation(duration_s: float, n_cameras=(6, 6, 4), pool_frames: int = 8, det_batch: int = 16, dtype: str = "bf16",
                     seed: int = 20250201 + 4, mean_objects: float = 8.0, base_fps: float = 15.0,
-                    src_hw=(1080, 1920)) -> Colocation:
+                    src_hw=(1080, 1920), slo_ms: float = 200.0) -> Colocation:
     """Traffic cascade, surveillance cascade and a detector-only pipeline fed by cameras whose frame rate swings
     sinusoidally around 15 fps (inhomogeneous Poisson arrivals); frames cycle through a small pool per pipeline and
     the detector heads are planted per pool frame with Poisson object counts."""
@@ -441,6 +441,8 @@ def make_colocation(duration_s: float, n_cameras=(6, 6, 4), pool_frames: int = 8
     rng = np.random.default_rng(seed)
     specs = [zoo.traffic_cascade(dtype=dtype, det_batch=det_batch), zoo.surveillance_cascade(dtype=dtype, det_batch=det_batch),
              zoo.detector_only(dtype=dtype, det_batch=det_batch)]
+    for sp in specs:
+        sp.slo_ms = slo_ms
     h, w = src_hw
     arrivals = synth.sinusoid_arrivals(rng, sum(n_cameras), duration_s, base_fps=base_fps)
     cams, pools, scenes, heads_host = [], [], [], []
