@@ -69,11 +69,12 @@ def conv_name(kid: int, dtype: str) -> str:
 # calibration pass of known size).  Valid only for the kernel source it was taken with: keyed by a hash of conv.hip.
 TRAFFIC = {
     # sha256(conv.hip)[:16]: {kernel name: bytes per launch}
-    "524f88f476795a5f": {
-        "octo::conv_mfma_kernel<_Float16, 64, 128, 2, 2, 8, 1, 3, true, true>": 35377025,
-        "octo::conv_mfma_kernel<_Float16, 64, 64, 2, 2, 8, 1, 4, true, true>": 13365522,
-        "octo::conv_mfma_kernel<_Float16, 128, 128, 2, 2, 8, 1, 2, true, true>": 34821269,
-        "octo::conv_mfma_kernel<_Float16, 32, 128, 1, 4, 4, 2, 4, true, false>": 32045464,
+    "3bffe28e92406602": {
+        "octo::conv_mfma_kernel<_Float16, 64, 128, 2, 2, 8, 1, 3, true, true>": 31060678,
+        "octo::conv_mfma_kernel<_Float16, 64, 64, 2, 2, 8, 1, 4, true, true>": 13369637,
+        "octo::conv_mfma_kernel<_Float16, 128, 128, 2, 2, 8, 1, 2, true, true>": 34824515,
+        "octo::conv_mfma_kernel<_Float16, 32, 128, 1, 4, 4, 2, 4, true, false>": 32029312,
+        "octo::conv_mfma_kernel<_Float16, 64, 256, 1, 4, 4, 1, 3, true, true>": 123826650,
     },
 }
 

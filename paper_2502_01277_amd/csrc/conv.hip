@@ -103,7 +103,7 @@ __global__ __launch_bounds__(THREADS, MINB) void conv_mfma_kernel(const ConvArgs
   constexpr int BK = KV * VN;            // elements per K step
   constexpr int ROWV = KV;               // LDS row pitch in vectors; the vector slot of a row is XOR-swizzled (below)
   constexpr int RPW = 16 / KV;           // tile rows per 256 bytes of LDS (one pass over all banks)
-  static_assert(KV == 4 || KV == 8, "swizzle assumes 64- or 128-byte rows");
+  static_assert(KV == 4 || KV == 8 || KV == 16, "swizzle assumes 64-, 128- or 256-byte rows");
   constexpr int RP = THREADS / KV;       // tile rows covered by one pass of the 256 loader lanes
   constexpr int TC = BC / WC / 32;       // 32x32 blocks per wavefront along channels
   constexpr int TP = BP / WP / 32;
@@ -140,7 +140,9 @@ __global__ __launch_bounds__(THREADS, MINB) void conv_mfma_kernel(const ConvArgs
   const int tiles_c = (a.Cout + BC - 1) / BC;
   const long long tiles_p = (M + BP - 1) / BP;
   const long long n_tiles = tiles_p * tiles_c;
-  const int nk = a.Kp / BK;              // a multiple of D: the host pads Kp to a multiple of 128 bytes
+  // register path: a multiple of D (the host pads Kp to a multiple of 128 bytes); direct-to-LDS path: any count, and a
+  // last step that runs past Kp multiplies zero-filled pixels
+  const int nk = DMA ? (a.Kp + BK - 1) / BK : a.Kp / BK;
   const T* __restrict__ xg = (const T*)a.x + a.x_coff;
   const int HoWo = a.Ho * a.Wo;
   const long long img_elems = (long long)a.H * a.W * a.x_ld;
