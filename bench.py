@@ -55,11 +55,14 @@ def make_workload(name: str):
 def conv_name(kid: int, dtype: str) -> str:
     """Template instance behind a conv kernel id (digits 1 BBB PPP K M V), as rocprofv3 prints it."""
     d = kid - 1000000000
+    ctype = {"f16": "_Float16", "bf16": "__bf16", "f32": "float"}[dtype]
+    if d >= 900000000:                                   # first-layer kernel: digits BBB KK P
+        d -= 900000000
+        return "octo::stem_conv_kernel<%s, %d, %d, %d>" % (ctype, d // 1000, (d // 10) % 100, d % 10)
     bc, bp, kv, minb, v = d // 1000000, (d // 1000) % 1000, (d // 100) % 10, (d // 10) % 10, d % 10
     vec, dma = v & 1, v >> 1
     wc, wp = (1, 4) if (bc == 32 or bp == 256) else (2, 2)
     depth = 1 if dma else 2
-    ctype = {"f16": "_Float16", "bf16": "__bf16", "f32": "float"}[dtype]
     return "octo::conv_mfma_kernel<%s, %d, %d, %d, %d, %d, %d, %d, %s, %s>" % (
         ctype, bc, bp, wc, wp, kv, depth, minb, "true" if vec else "false", "true" if dma else "false")
 

@@ -1,0 +1,69 @@
+// Pieces shared by the matrix-core kernels: 16-byte operand vectors, the MFMA instruction per storage type, packed
+// loads / stores of four values, the fast SiLU and the buffer-load constants.
+#pragma once
+#include "octo_internal.h"
+
+namespace octo {
+
+typedef _Float16 half8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));   // one 16-byte operand vector
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+
+template <typename T> struct Elem;
+template <> struct Elem<_Float16> {
+  static constexpr int N = 8;   // elements per 16-byte vector
+  static __device__ __forceinline__ floatx16 mfma(u32x4 a, u32x4 b, floatx16 c) {
+    return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(half8, a), __builtin_bit_cast(half8, b), c, 0, 0, 0);
+  }
+};
+template <> struct Elem<__bf16> {
+  static constexpr int N = 8;
+  static __device__ __forceinline__ floatx16 mfma(u32x4 a, u32x4 b, floatx16 c) {
+    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
+  }
+};
+template <> struct Elem<float> {
+  static constexpr int N = 4;
+  static __device__ __forceinline__ floatx16 mfma(u32x4 a, u32x4 b, floatx16 c) {
+    const floatx4 fa = __builtin_bit_cast(floatx4, a), fb = __builtin_bit_cast(floatx4, b);
+#pragma unroll
+    for (int j = 0; j < 4; ++j) c = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[j], fb[j], c, 0, 0, 0);
+    return c;
+  }
+};
+
+template <typename T>
+__device__ __forceinline__ floatx4 load4(const T* p) {
+  if constexpr (sizeof(T) == 4) {
+    return *(const floatx4*)p;
+  } else {
+    typedef T t4 __attribute__((ext_vector_type(4)));
+    const t4 v = __builtin_bit_cast(t4, *(const u32x2*)p);
+    return floatx4{(float)v[0], (float)v[1], (float)v[2], (float)v[3]};
+  }
+}
+template <typename T>
+__device__ __forceinline__ void store4(T* p, floatx4 v) {
+  if constexpr (sizeof(T) == 4) {
+    *(floatx4*)p = v;
+  } else {
+    typedef T t4 __attribute__((ext_vector_type(4)));
+    const t4 o = {(T)v[0], (T)v[1], (T)v[2], (T)v[3]};
+    *(u32x2*)p = __builtin_bit_cast(u32x2, o);
+  }
+}
+// floor(n / d) for n < 2^31 with magic = ceil(2^(32+shift) / d) (fits 32 bits for the shift chosen on the host)
+__device__ __forceinline__ unsigned udiv(unsigned n, unsigned magic, unsigned shift) { return __umulhi(n, magic) >> shift; }
+// x * sigmoid(x) with the hardware exp2 / reciprocal (about 1 ulp each: far below the storage precision)
+__device__ __forceinline__ float silu(float v) { return v * __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(v * -1.4426950408889634f)); }
+
+constexpr int THREADS = 256;
+constexpr unsigned BUF_FLAGS = 0x00020000u;      // raw buffer, 32-bit data format
+constexpr int OOB = (int)0x80000000;             // offset beyond any buffer range: the load returns zeros
+constexpr long long BUF_MAX = 0x7FFFFFFFLL;
+
+
+}  // namespace octo

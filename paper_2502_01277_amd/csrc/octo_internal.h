@@ -37,6 +37,7 @@ struct ConvArgs {
   int act, res_mode;
   int out_f32;          // write fp32 instead of the storage type
   int n_hint;           // host only: expected item count when it is taken on the device (0: assume n); picks the tile shape
+  int pair_view;        // the layer is a 3-channel first layer run on pixel pairs of a 4-channel-padded input
 };
 
 // element size of a storage type
@@ -46,6 +47,8 @@ inline __host__ __device__ int dtype_size(int dt) { return dt == OCTO_F32 ? 4 : 
 // Optional pair of events attached to the convolution's own dispatch (start and end of the kernel on the device).
 struct ConvTiming { hipEvent_t start = nullptr, stop = nullptr; };
 hipError_t launch_conv(int dtype, const ConvArgs& a, int num_cu, hipStream_t s, int* kernel_id = nullptr, ConvTiming tm = ConvTiming());
+// first-layer kernel for pixel-pair layers; hipErrorNotSupported when the layer does not fit it
+hipError_t launch_stem(int dtype, const ConvArgs& a, int num_cu, hipStream_t s, int* kernel_id, ConvTiming tm);
 int conv_kernel_id(int bc, int bp, int kv, int minb, bool vec, bool dma = false);
 enum { KID_NONE = 0, KID_MAXPOOL = 1, KID_UPSAMPLE = 2, KID_COPY = 3, KID_ADD = 4, KID_GAP = 5 };
 size_t conv_packed_weight_elems(int cout, int kh, int kw, int cin, int dtype, int* kp_out, int* cout_pad_out);

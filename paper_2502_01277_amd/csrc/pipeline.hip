@@ -420,7 +420,7 @@ hipError_t run_layer(octo_pipeline* p, ModelPlan& m, int i, int n, const int* n_
       a.H = x.h; a.W = x.w; a.Cin = x.c; a.x_ld = x.ld; a.x_coff = x.coff;
       a.Ho = y.h; a.Wo = y.w; a.Cout = y.c; a.y_ld = y.ld; a.y_coff = y.coff;
       a.kh = L.kh; a.kw = L.kw; a.stride_h = a.stride_w = L.stride; a.pad_h = a.pad_w = L.pad; a.K = lp.K; a.Kp = lp.Kp; a.w_rows = lp.cout_pad;
-      if (lp.pair_view) { a.W = x.w / 2; a.Cin = 8; a.x_ld = 8; a.kw = lp.pair_kw; a.stride_w = 1; a.pad_w = lp.pair_pad; }
+      if (lp.pair_view) { a.W = x.w / 2; a.Cin = 8; a.x_ld = 8; a.kw = lp.pair_kw; a.stride_w = 1; a.pad_w = lp.pair_pad; a.pair_view = 1; }
       a.act = L.act; a.res_mode = L.res_mode; a.out_f32 = m.tensors[i + 1].f32 ? 1 : 0;
       if (L.n_in == 2) { const TensorView r = view_of(m, L.in[1]); a.res = r.ptr; a.res_ld = r.ld; a.res_coff = r.coff; }
       if (n_dyn && m.items_hint > 0) a.n_hint = std::max(1, (int)(m.items_hint + 0.999));

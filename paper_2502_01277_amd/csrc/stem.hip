@@ -1,0 +1,199 @@
+// First-layer convolution (3 input channels, stride 2) on the matrix cores.
+//
+// The input is stored with 4 channels, so two neighbouring pixels form one 16-byte vector of 8 values, and a
+// stride-2 convolution becomes a stride-1 convolution over pixel pairs with a kernel of KH x PKW pairs (see
+// pipeline.hip, which also re-packs the weights as [Cout][(row, pair, 8 values)]).  The general implicit-GEMM kernel
+// gathers every K vector of every output pixel from global memory: for a 7x7 kernel that is 28 loads of 16 bytes per
+// output pixel, almost all of them re-reads.  Here a workgroup instead
+//   - keeps the whole weight matrix in LDS for its lifetime (it is persistent over tiles),
+//   - loads the input patch of an 8 x 32 output tile once (21 x 35 pair vectors for 7x7), zero-filled outside the image,
+//   - feeds the MFMA B operand straight from the patch: for kernel tap (r, s) output pixel (y, x) needs patch vector
+//     (2y + r, x + s), so the 32 lanes of a block read 32 consecutive vectors (bank-conflict free),
+//   - stages the output tile in LDS (over the patch) and writes it with 16-byte stores along the channels.
+// One K step of the MFMA (16 values) is two pair vectors; with an odd number of vectors the last half step multiplies
+// a zero weight column.
+#include "mfma_common.h"
+#include <hip/hip_ext.h>
+
+namespace octo {
+
+constexpr int STEM_TH = 8, STEM_TW = 32;   // output tile: rows x columns
+
+template <typename T, int BC, int KH, int PKW>
+__global__ __launch_bounds__(THREADS, 2) void stem_conv_kernel(const ConvArgs a) {
+  using E = Elem<T>;
+  static_assert(sizeof(T) == 2 && E::N == 8, "pixel pairs are 16-byte vectors of 8 values");
+  constexpr int TH = STEM_TH, TW = STEM_TW, BP = TH * TW;
+  constexpr int NV = KH * PKW;                 // K vectors
+  constexpr int NJ = (NV + 1) / 2;             // MFMA steps
+  constexpr int PH = (TH - 1) * 2 + KH, PW = TW + PKW - 1, PVEC = PH * PW;
+  constexpr int PLOADS = (PVEC + THREADS - 1) / THREADS;
+  constexpr int WPITCH = NV + 1;               // odd number of vectors per weight row: conflict-free column reads
+  static_assert(WPITCH % 2 == 1, "weight row pitch must be odd");
+  constexpr int TC = BC / 32;
+  constexpr int OPITCH = BC * 2 + 16;          // bytes per staged output pixel
+  constexpr int REGION_VECS = (PLOADS * THREADS > BP * OPITCH / 16) ? PLOADS * THREADS : BP * OPITCH / 16;
+  __shared__ u32x4 sW[BC * WPITCH];
+  __shared__ u32x4 sR[REGION_VECS];            // input patch, then the staged output tile
+  __shared__ float sBias[BC];
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l32 = lane & 31, g = lane >> 5;
+  int n_items = a.n;
+  if (a.n_dyn) { int d = *a.n_dyn; n_items = d < a.n ? d : a.n; }
+  const int tiles_x = (a.Wo + TW - 1) / TW, tiles_y = (a.Ho + TH - 1) / TH;
+  const int per_img = tiles_x * tiles_y;
+  const long long n_tiles = (long long)n_items * per_img;
+  const T* __restrict__ xg = (const T*)a.x + a.x_coff;
+  const long long img_elems = (long long)a.H * a.W * a.x_ld;
+  const bool is_silu = a.act == OCTO_ACT_SILU;
+  const float act_lo = a.act == OCTO_ACT_RELU ? 0.0f : -INFINITY;
+
+  // weights -> LDS, once (rows beyond Cout and the pad column are zero in the packed matrix / written as zero here)
+  {
+    const long long w_bytes = (long long)a.w_rows * a.Kp * 2;
+    const __amdgpu_buffer_rsrc_t rsrc_w = __builtin_amdgcn_make_buffer_rsrc((void*)a.w, 0, (int)(w_bytes < BUF_MAX ? w_bytes : BUF_MAX), BUF_FLAGS);
+    for (int q = tid; q < BC * WPITCH; q += THREADS) {
+      const int row = q / WPITCH, v = q - row * WPITCH;
+      u32x4 val = {0u, 0u, 0u, 0u};
+      if (v < NV) val = __builtin_amdgcn_raw_buffer_load_b128(rsrc_w, (row * a.Kp + v * 8) * 2, 0, 0);
+      sW[q] = val;
+    }
+    if (tid < BC) sBias[tid] = a.bias[tid];
+  }
+
+  const long long per_die = (n_tiles + 7) >> 3;      // contiguous chunk of the tile list per die (see conv.hip)
+  for (long long t = blockIdx.x; t < per_die * 8; t += gridDim.x) {
+    const long long tile = (t & 7) * per_die + (t >> 3);
+    if (tile >= n_tiles) continue;
+    const int img = (int)(tile / per_img);
+    const int rem = (int)(tile - (long long)img * per_img);
+    const int ty = rem / tiles_x, tx = rem - ty * tiles_x;
+    const int oy0 = ty * TH, ox0 = tx * TW;
+    const int iy0 = oy0 * 2 - a.pad_h, ix0 = ox0 - a.pad_w;      // patch origin in input rows / pairs
+
+    // one image per buffer: 32-bit offsets suffice
+    const long long img_bytes = img_elems * 2;
+    const __amdgpu_buffer_rsrc_t rsrc_x =
+        __builtin_amdgcn_make_buffer_rsrc((void*)(xg + (long long)img * img_elems), 0, (int)(img_bytes < BUF_MAX ? img_bytes : BUF_MAX), BUF_FLAGS);
+    u32x4 pv[PLOADS];
+#pragma unroll
+    for (int i = 0; i < PLOADS; ++i) {
+      const int q = i * THREADS + tid;
+      const int prow = q / PW, pcol = q - prow * PW;
+      const int iy = iy0 + prow, ix = ix0 + pcol;
+      const bool ok = q < PVEC && (unsigned)iy < (unsigned)a.H && (unsigned)ix < (unsigned)a.W;
+      pv[i] = __builtin_amdgcn_raw_buffer_load_b128(rsrc_x, ok ? (iy * a.W + ix) * a.x_ld * 2 : OOB, 0, 0);
+    }
+    __syncthreads();                     // the previous tile's staged output has been written out
+#pragma unroll
+    for (int i = 0; i < PLOADS; ++i) sR[i * THREADS + tid] = pv[i];
+    __syncthreads();
+
+    floatx16 acc[TC][2];
+#pragma unroll
+    for (int i = 0; i < TC; ++i)
+#pragma unroll
+      for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
+
+    const int prow0 = (wave * 2) * 2 * PW + l32;       // patch vector of tap (0, 0) for this lane's pixel of block 0
+#pragma unroll
+    for (int j = 0; j < NJ; ++j) {
+      const int v0 = 2 * j, v1 = 2 * j + 1 < NV ? 2 * j + 1 : NV - 1;   // a half step past the end re-reads a valid vector: its weights are zero
+      const int off0 = (v0 / PKW) * PW + (v0 % PKW), off1 = (v1 / PKW) * PW + (v1 % PKW);
+      const int boff = prow0 + (g ? off1 : off0);
+      u32x4 fa[TC], fb[2];
+#pragma unroll
+      for (int i = 0; i < TC; ++i) fa[i] = sW[(i * 32 + l32) * WPITCH + 2 * j + g];
+#pragma unroll
+      for (int tp = 0; tp < 2; ++tp) fb[tp] = sR[boff + tp * 2 * PW];
+#pragma unroll
+      for (int i = 0; i < TC; ++i)
+#pragma unroll
+        for (int tp = 0; tp < 2; ++tp) acc[i][tp] = E::mfma(fa[i], fb[tp], acc[i][tp]);
+    }
+
+    __syncthreads();                     // everyone is done with the patch: the region now stages the output
+#pragma unroll
+    for (int tp = 0; tp < 2; ++tp) {
+      const int pl = (wave * 2 + tp) * TW + l32;
+#pragma unroll
+      for (int i = 0; i < TC; ++i) {
+        const int cblk = i * 32 + g * 4;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const floatx4 b4 = *(const floatx4*)&sBias[cblk + q * 8];
+          floatx4 v;
+#pragma unroll
+          for (int e = 0; e < 4; ++e) v[e] = fmaxf(acc[i][tp][q * 4 + e] + b4[e], act_lo);
+          if (is_silu) {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) v[e] = silu(v[e]);
+          }
+          store4<T>((T*)((char*)sR + (size_t)pl * OPITCH) + cblk + q * 8, v);
+        }
+      }
+    }
+    __syncthreads();
+    constexpr int VPR = BC / 8;                  // 16-byte vectors per pixel
+    constexpr int PPP = THREADS / VPR;           // pixels per pass
+    const int v = tid % VPR, pr = tid / VPR;
+    const int c = v * 8;
+#pragma unroll
+    for (int ps = 0; ps < BP / PPP; ++ps) {
+      const int pl = ps * PPP + pr;
+      const int oy = oy0 + pl / TW, ox = ox0 + pl % TW;
+      if (oy < a.Ho && ox < a.Wo && c < a.Cout) {
+        const u32x4 val = *(const u32x4*)((const char*)sR + (size_t)pl * OPITCH + (size_t)v * 16);
+        T* yp = (T*)a.y + (((size_t)img * a.Ho + oy) * a.Wo + ox) * a.y_ld + a.y_coff + c;
+        if (c + 8 <= a.Cout) {
+          *(u32x4*)yp = val;
+        } else {
+          typedef T tv __attribute__((ext_vector_type(8)));
+          const tv tvv = __builtin_bit_cast(tv, val);
+#pragma unroll
+          for (int e = 0; e < 8; ++e) if (c + e < a.Cout) yp[e] = tvv[e];
+        }
+      }
+    }
+  }
+}
+
+int stem_kernel_id(int bc, int kh, int pkw) { return 1900000000 + bc * 1000 + kh * 10 + pkw; }
+
+template <typename T, int BC, int KH, int PKW>
+static hipError_t launch_stem_cfg(const ConvArgs& a, int num_cu, hipStream_t s, int* kernel_id, const ConvTiming& tm) {
+  if (kernel_id) *kernel_id = stem_kernel_id(BC, KH, PKW);
+  const long long tiles = (long long)a.n * ((a.Wo + STEM_TW - 1) / STEM_TW) * ((a.Ho + STEM_TH - 1) / STEM_TH);
+  if (tiles <= 0) return hipSuccess;
+  long long grid = (tiles + 7) / 8 * 8;
+  const long long cap = (long long)num_cu * 2;
+  if (grid > cap) grid = cap;
+  if (tm.start && tm.stop)
+    hipExtLaunchKernelGGL((stem_conv_kernel<T, BC, KH, PKW>), dim3((unsigned)grid), dim3(THREADS), 0, s, tm.start, tm.stop, 0, a);
+  else
+    hipLaunchKernelGGL((stem_conv_kernel<T, BC, KH, PKW>), dim3((unsigned)grid), dim3(THREADS), 0, s, a);
+  return hipGetLastError();
+}
+
+template <typename T>
+static hipError_t launch_stem_typed(const ConvArgs& a, int num_cu, hipStream_t s, int* kernel_id, const ConvTiming& tm) {
+  if (a.kh == 7 && a.kw == 4 && a.Cout <= 64) return launch_stem_cfg<T, 64, 7, 4>(a, num_cu, s, kernel_id, tm);
+  if (a.kh == 6 && a.kw == 3 && a.Cout <= 32) return launch_stem_cfg<T, 32, 6, 3>(a, num_cu, s, kernel_id, tm);
+  if (a.kh == 6 && a.kw == 3 && a.Cout <= 64) return launch_stem_cfg<T, 64, 6, 3>(a, num_cu, s, kernel_id, tm);
+  if (a.kh == 3 && a.kw == 2 && a.Cout <= 32) return launch_stem_cfg<T, 32, 3, 2>(a, num_cu, s, kernel_id, tm);
+  return hipErrorNotSupported;
+}
+
+// Pixel-pair first layers in the 16-bit types, stride 2, with one of the kernel shapes above, 16-byte aligned output
+// rows and no residual; anything else is left to the general kernel (hipErrorNotSupported).
+hipError_t launch_stem(int dtype, const ConvArgs& a, int num_cu, hipStream_t s, int* kernel_id, ConvTiming tm) {
+  if (!a.pair_view || dtype == OCTO_F32 || a.stride_h != 2 || a.stride_w != 1 || a.Cin != 8 || a.x_ld != 8 || a.res || a.out_f32)
+    return hipErrorNotSupported;
+  if (((a.y_ld | a.y_coff) & 7) || ((uintptr_t)a.y & 15) || ((uintptr_t)a.x & 15) || (a.x_coff & 7)) return hipErrorNotSupported;
+  if ((long long)a.H * a.W * 16 > BUF_MAX || a.w_rows < 64) return hipErrorNotSupported;
+  return dtype == OCTO_F16 ? launch_stem_typed<_Float16>(a, num_cu, s, kernel_id, tm) : launch_stem_typed<__bf16>(a, num_cu, s, kernel_id, tm);
+}
+
+}  // namespace octo

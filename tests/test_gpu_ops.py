@@ -97,6 +97,8 @@ CONV_CASES = [
     # enough output pixels for the wide tiles: 256x128 (ragged channel tail), 128x128, 64x128 with 64- and 32-element K steps
     (128, 128, 16, 200, 1, 1, 0, 4), (96, 96, 16, 128, 3, 1, 1, 4), (64, 64, 128, 64, 1, 1, 0, 4), (64, 64, 64, 64, 1, 1, 0, 4),
     (256, 256, 8, 48, 1, 1, 0, 4),          # 64x256 tiles
+    # 3-channel stride-2 first layers on even widths (pixel-pair view): every first-layer kernel shape, several tiles, ragged edges
+    (70, 90, 3, 64, 7, 2, 3, 2), (34, 32, 3, 32, 6, 2, 2, 2), (50, 132, 3, 48, 6, 2, 2, 3), (18, 20, 3, 16, 3, 2, 1, 3),
 ]
 
 
