@@ -481,6 +481,16 @@ hipError_t launch_conv(int dtype, const ConvArgs& a0, int num_cu, hipStream_t s,
   if (!conv_prepare(a, dtype)) return hipErrorInvalidValue;
   const hipError_t es = launch_stem(dtype, a, num_cu, s, kernel_id, tm);
   if (es != hipErrorNotSupported) return es;
+  // 3x3 layers with at most 64 output channels on wide images: the input patch of a tile lives in LDS (measured
+  // +20% on 56x56x64 layers; the 8x32 pixel tile wastes lanes on narrow feature maps, and with more output channels
+  // the general kernel's 128-channel tile re-uses the pixel operand enough)
+  {
+    const long long m_hint = (long long)(a.n_hint > 0 && a.n_hint < a.n ? a.n_hint : a.n) * a.Ho * a.Wo;
+    if (a.Cout <= 64 && a.Wo >= 28 && (a.Wo + 31) / 32 * 32 * 7 <= a.Wo * 8 && m_hint >= 2LL * num_cu * 256) {
+      const hipError_t e3 = launch_conv3x3_patch(dtype, a, num_cu, s, kernel_id, tm);
+      if (e3 != hipErrorNotSupported) return e3;
+    }
+  }
   switch (dtype) {
     case OCTO_F16: return launch_typed<_Float16>(a, num_cu, s, kernel_id, tm);
     case OCTO_BF16: return launch_typed<__bf16>(a, num_cu, s, kernel_id, tm);

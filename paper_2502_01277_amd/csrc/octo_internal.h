@@ -49,6 +49,8 @@ struct ConvTiming { hipEvent_t start = nullptr, stop = nullptr; };
 hipError_t launch_conv(int dtype, const ConvArgs& a, int num_cu, hipStream_t s, int* kernel_id = nullptr, ConvTiming tm = ConvTiming());
 // first-layer kernel for pixel-pair layers; hipErrorNotSupported when the layer does not fit it
 hipError_t launch_stem(int dtype, const ConvArgs& a, int num_cu, hipStream_t s, int* kernel_id, ConvTiming tm);
+// 3x3 stride-1 kernel with the input patch in LDS; hipErrorNotSupported when the layer does not fit it
+hipError_t launch_conv3x3_patch(int dtype, const ConvArgs& a, int num_cu, hipStream_t s, int* kernel_id, ConvTiming tm);
 int conv_kernel_id(int bc, int bp, int kv, int minb, bool vec, bool dma = false);
 enum { KID_NONE = 0, KID_MAXPOOL = 1, KID_UPSAMPLE = 2, KID_COPY = 3, KID_ADD = 4, KID_GAP = 5 };
 size_t conv_packed_weight_elems(int cout, int kh, int kw, int cin, int dtype, int* kp_out, int* cout_pad_out);

@@ -99,6 +99,8 @@ CONV_CASES = [
     (256, 256, 8, 48, 1, 1, 0, 4),          # 64x256 tiles
     # 3-channel stride-2 first layers on even widths (pixel-pair view): every first-layer kernel shape, several tiles, ragged edges
     (70, 90, 3, 64, 7, 2, 3, 2), (34, 32, 3, 32, 6, 2, 2, 2), (50, 132, 3, 48, 6, 2, 2, 3), (18, 20, 3, 16, 3, 2, 1, 3),
+    # 3x3 layers wide enough for the patch-in-LDS kernel: channel slices of 64 and 32, two slices, ragged tile edges, 40 channels out
+    (90, 92, 64, 64, 3, 1, 1, 17), (120, 124, 32, 40, 3, 1, 1, 20), (84, 90, 128, 64, 3, 1, 1, 18), (100, 60, 96, 48, 3, 1, 1, 24),
 ]
 
 
@@ -133,6 +135,21 @@ def test_residual_concat_pool_upsample_graph(octo, dtype):
     ref = nn.run_model(m, x, keep_all=True)
     for t in range(1, len(ref)):
         assert rel_err(got[t], ref[t]) <= TOL[dtype], (t, m.layers[t - 1].op)
+
+
+@pytest.mark.parametrize("dtype", ["f16", "bf16"])
+def test_wide_3x3_layers_with_residuals(octo, dtype):
+    """Large enough for the 3x3 kernel that keeps the input patch in LDS: both residual modes, SiLU and ReLU."""
+    def build(B):
+        a = B.conv(0, 64, 3, 1, act=zoo.ACT_RELU)
+        b = B.conv(a, 64, 3, 1, act=zoo.ACT_RELU, res=a, res_mode=zoo.RES_BEFORE_ACT)
+        return B.conv(b, 32, 3, 1, act=zoo.ACT_SILU, res=0, res_mode=zoo.RES_AFTER_ACT)
+    m = _model(dtype, (72, 100), 32, build, 20)
+    x = zoo.round_to_dtype(np.random.default_rng(12).uniform(-1, 1, (20, 72, 100, 32)).astype(np.float32), dtype)
+    got = _run_detached(octo, m, x)
+    ref = nn.run_model(m, x, keep_all=True)
+    for t in range(1, 4):
+        assert rel_err(got[t], ref[t]) <= TOL[dtype], t
 
 
 def test_memory_reuse_keeps_outputs_intact(octo):
