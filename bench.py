@@ -74,12 +74,11 @@ def conv_name(kid: int, dtype: str) -> str:
 # calibration pass of known size).  Valid only for the kernel source it was taken with: keyed by a hash of conv.hip.
 TRAFFIC = {
     # sha256(conv.hip)[:16]: {kernel name: bytes per launch}
-    "3bffe28e92406602": {
-        "octo::conv_mfma_kernel<_Float16, 64, 128, 2, 2, 8, 1, 3, true, true>": 31060678,
-        "octo::conv_mfma_kernel<_Float16, 64, 64, 2, 2, 8, 1, 4, true, true>": 13369637,
-        "octo::conv_mfma_kernel<_Float16, 128, 128, 2, 2, 8, 1, 2, true, true>": 34824515,
-        "octo::conv_mfma_kernel<_Float16, 32, 128, 1, 4, 4, 2, 4, true, false>": 32029312,
-        "octo::conv_mfma_kernel<_Float16, 64, 256, 1, 4, 4, 1, 3, true, true>": 123826650,
+    "e7cbe333664d5957": {
+        "octo::conv_mfma_kernel<_Float16, 64, 64, 2, 2, 8, 1, 4, true, true>": 13369631,
+        "octo::conv_mfma_kernel<_Float16, 64, 128, 2, 2, 8, 1, 3, true, true>": 24440758,
+        "octo::conv_mfma_kernel<_Float16, 128, 128, 2, 2, 8, 1, 2, true, true>": 34824105,
+        "octo::conv_mfma_kernel<_Float16, 32, 128, 1, 4, 4, 2, 4, true, false>": 23949707,
     },
 }
 
