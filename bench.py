@@ -226,9 +226,10 @@ def main():
     ap.add_argument("--steps", type=int, default=400)
     ap.add_argument("--warmup", type=int, default=40)
     ap.add_argument("--workload", default="traffic")
-    ap.add_argument("--instances", type=int, default=4,
+    ap.add_argument("--instances", type=int, default=None,
                     help="copies of the pipeline (own activations and tables) that take batches in turn, each on its own "
-                         "stream, so that kernels of different batches overlap on the GPU")
+                         "stream, so that kernels of different batches overlap on the GPU (default: 4 for the traffic and "
+                         "sweep workloads, 1 for the high-resolution one, whose batches fill the GPU by themselves)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--layers", action="store_true", help="print the per-kernel table to stderr")
     ap.add_argument("--calib-copy-mib", type=int, default=0,
@@ -239,6 +240,8 @@ def main():
     ap.add_argument("--det-batch", type=int, default=16, help="co-location workload: largest detector batch")
     ap.add_argument("--slo-ms", type=float, default=200.0, help="co-location workload: the pipelines' latency objective")
     args = ap.parse_args()
+    if args.instances is None:
+        args.instances = 1 if args.workload in ("hires", "tiny") else 4
     if args.gpus != 1:
         print("bench.py measures one GPU only (frames are independent: more GPUs = more copies of this run); --gpus %d refused" % args.gpus,
               file=sys.stderr)
