@@ -220,6 +220,46 @@ def run_colocate(args):
         P.close()
 
 
+def run_surge(args):
+    """A workload surge between two runs of the scheduler (Sec. III-D, IV-A): traffic cascade + detector-only pipeline
+    on half of the GPU; the cameras of the first send --surge-factor x as many frames during the middle third.  Served by
+    the scheduled instances alone, with lazy dropping of late requests, and with the run-time scaler (a stand-by copy
+    that Algorithm 2 places into free portions)."""
+    from paper_2502_01277_amd import binding, executor
+    dur, scale = args.duration, max(1, args.camera_scale)
+    t0, t1 = dur / 3.0, 2.0 * dur / 3.0
+    co = executor.make_colocation(dur, n_cameras=(6 * scale, 0, 4 * scale), pool_frames=8, det_batch=args.det_batch,
+                                  slo_ms=args.slo_ms, surge=(0, t0, t1, args.surge_factor))
+    specs = [co.specs[0], co.specs[2]]
+    cams = [executor.Camera(0 if c.pipeline == 0 else 1, c.arrivals_s, c.pool) for c in co.cameras]
+    pools = [co.head_pools[0], co.head_pools[2]]
+    pipes = [binding.Pipeline(s) for s in specs]
+    spares = [binding.Pipeline(specs[0]), None]
+    profiles = [executor.profile_pipeline(P, widths=(64, 128, 256), iters=2) for P in pipes]
+    sch = executor.plan(specs, profiles, [co.frame_rates[0], co.frame_rates[2]], [co.objects_per_frame[0], co.objects_per_frame[2]],
+                        [co.burstiness[0], co.burstiness[2]], n_streams=8)
+    res = {}
+    for tag, kw in (("scheduled_only", {}), ("lazy_dropping", dict(drop_late=True)), ("scaler", dict(spares=spares)),
+                    ("scaler_and_dropping", dict(spares=spares, drop_late=True))):
+        ex = executor.Executor(pipes, sch, cams, pools, slotted=True, masked=True, **kw)
+        res[tag] = ex.serve(dur)
+        res[tag]["stream_cus"] = {str(k): v for k, v in ex.stream_cus.items()}
+        ex.close()
+    out = res["scaler"]
+    print(json.dumps({
+        "metric": "pipeline frames/s within %g ms SLO on 1 GPU" % args.slo_ms, "value": out["effective_frames_per_s"], "unit": "frames/s",
+        "n_gpus": 1, "steps": int(1e3 * dur / sch.duty_ms), "warmup": 1, "ms_per_step": sch.duty_ms,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "surge: traffic cascade (%d cameras) + detector-only pipeline (%d cameras) at 15 fps, %.0f s; "
+                               "the traffic cameras send %gx the frames for %.2f s <= t < %.2f s; planted heads Poisson(8)" %
+                               (6 * scale, 4 * scale, dur, args.surge_factor, t0, t1), "slo_ms": args.slo_ms, "heads": "planted"},
+        "schedule": {"duty_ms": sch.duty_ms, "bz": sch.bz, "batches_per_cycle": sch.batches_per_cycle,
+                     "placements": sch.placements, "stream_cus": {str(k): v for k, v in sch.stream_cus.items()}},
+        **res}))
+    for P in pipes + [spares[0]]:
+        P.close()
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -239,6 +279,7 @@ def main():
     ap.add_argument("--camera-scale", type=int, default=1, help="co-location workload: multiply the sixteen cameras")
     ap.add_argument("--det-batch", type=int, default=16, help="co-location workload: largest detector batch")
     ap.add_argument("--slo-ms", type=float, default=200.0, help="co-location workload: the pipelines' latency objective")
+    ap.add_argument("--surge-factor", type=float, default=2.5, help="surge workload: rate multiplier during the middle third")
     args = ap.parse_args()
     if args.instances is None:
         args.instances = 1 if args.workload in ("hires", "tiny") else 4
@@ -254,6 +295,8 @@ def main():
         return run_sweep(args)
     if args.workload == "colocate":
         return run_colocate(args)
+    if args.workload == "surge":
+        return run_surge(args)
     spec, scene, heads, desc = make_workload(args.workload)
     det = spec.models[0]
     n = scene.frames.shape[0]

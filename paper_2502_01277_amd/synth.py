@@ -221,17 +221,21 @@ def planted_heads(rng, det: ModelSpec, scene: Scene, src_h, src_w, max_dups=4, n
 # ---------------------------------------------------------------------------
 # arrivals (open-loop load)
 # ---------------------------------------------------------------------------
-def sinusoid_arrivals(rng, n_streams, duration_s, base_fps=15.0, depth=0.5, period_s=10.0):
+def sinusoid_arrivals(rng, n_streams, duration_s, base_fps=15.0, depth=0.5, period_s=10.0, boost=None):
     """Inhomogeneous Poisson arrivals by thinning; stream i has rate base*(1+depth*sin(2 pi t/period + 2 pi i/n)).
 
-    Returns a list of sorted arrival-time arrays (seconds), one per stream.
+    boost: optional list with one entry per stream, None or (t0, t1, factor): the stream's rate is multiplied by
+    factor for t0 <= t < t1 (a workload surge).  Returns a list of sorted arrival-time arrays (seconds), one per stream.
     """
-    lam_max = base_fps * (1.0 + depth)
     out = []
     for i in range(n_streams):
-        n_prop = rng.poisson(lam_max * duration_s)
+        b = boost[i] if boost is not None else None
+        peak = base_fps * (1.0 + depth) * (max(1.0, b[2]) if b else 1.0)
+        n_prop = rng.poisson(peak * duration_s)
         t = np.sort(rng.uniform(0.0, duration_s, size=n_prop))
         lam = base_fps * (1.0 + depth * np.sin(2 * np.pi * t / period_s + 2 * np.pi * i / n_streams))
-        keep = rng.random(size=n_prop) < lam / lam_max
+        if b:
+            lam = np.where((t >= b[0]) & (t < b[1]), lam * b[2], lam)
+        keep = rng.random(size=n_prop) < lam / peak
         out.append(t[keep])
     return out

@@ -1,0 +1,136 @@
+"""Host logic of the slot executor that needs no GPU: lazy dropping of late requests, the run-time scaling decision,
+the property of the portion scheduler the scaler relies on, and the surge in the synthetic arrivals."""
+import numpy as np
+
+from oracle import sched
+from paper_2502_01277_amd import binding, executor, synth
+
+
+# ---- lazy dropping (Sec. IV-A) ----
+def test_late_prefix_counts_only_the_expired_head_of_the_queue():
+    now, slo = 1000.0, 200.0
+    assert executor.late_prefix([], now, slo) == 0
+    assert executor.late_prefix([900.0, 950.0], now, slo) == 0
+    assert executor.late_prefix([799.0, 799.9, 800.0, 900.0], now, slo) == 2          # exactly the SLO old is still served
+    assert executor.late_prefix([100.0, 200.0, 300.0], now, slo) == 3
+    # the queue is in arrival order, so an expired request behind a live one cannot happen; the count stops at the
+    # first live request in any case (nothing is taken out of the middle of a batch)
+    assert executor.late_prefix([700.0, 900.0, 750.0], now, slo) == 1
+
+
+# ---- run-time scaling decision (Sec. III-D) ----
+def _run(det, arrivals, backlog=None, n_active=1):
+    """Feeds a sequence of per-cycle arrivals and applies the decisions; returns (decisions, instances over time)."""
+    out, act = [], []
+    for t, a in enumerate(arrivals):
+        d = det.observe(a, 0 if backlog is None else backlog[t], n_active)
+        n_active += d
+        out.append(d)
+        act.append(n_active)
+    return out, act
+
+
+def test_steady_load_within_capacity_never_scales():
+    det = executor.SurgeDetector(capacity=32, window=5)
+    dec, act = _run(det, [30, 32, 28, 31, 32, 29, 32, 30] * 5)
+    assert not any(dec) and set(act) == {1}
+
+
+def test_surge_adds_one_instance_after_a_full_window_and_dip_removes_it():
+    det = executor.SurgeDetector(capacity=32, window=4, up=1.0, down=0.7, max_instances=2)
+    arr = [30] * 6 + [60] * 12 + [20] * 10
+    dec, act = _run(det, arr)
+    # the first surge cycle already lifts the mean of the last 4 cycles over the capacity: (30*3 + 60)/4 = 37.5 > 32
+    up_at = dec.index(1)
+    assert up_at == 6
+    assert dec.count(1) == 1, "two instances are the limit"
+    # removal: the first whole window below 0.7 * 32 = 22.4 is cycles 18..21 (all 20); (60 + 20*3)/4 = 30 is not
+    assert dec.index(-1) == 21 and act[-1] == 1 and dec.count(-1) == 1
+    assert all(d == 0 for d in dec[up_at + 1: up_at + 4]), "no decision inside the window after another"
+
+
+def test_load_between_the_two_thresholds_changes_nothing_in_either_state():
+    for n_active in (1, 2):
+        det = executor.SurgeDetector(capacity=40, window=3, up=1.0, down=0.7)
+        # one instance: 30 < 40; two instances: 30 > 0.7*40 = 28 and 30 < 80
+        dec, _ = _run(det, [30] * 30, n_active=n_active)
+        assert not any(dec)
+
+
+def test_a_queue_that_never_drains_scales_up_even_if_arrivals_look_fine():
+    det = executor.SurgeDetector(capacity=16, window=3)
+    dec, _ = _run(det, [10] * 6, backlog=[20, 25, 17, 30, 40, 50])
+    assert dec[:3] == [0, 0, 1]
+    det = executor.SurgeDetector(capacity=16, window=3)
+    dec, _ = _run(det, [10] * 6, backlog=[20, 25, 16, 30, 3, 50])           # drained to within capacity in between
+    assert not any(dec)
+
+
+def test_scale_down_waits_until_the_queue_fits_the_remaining_instance():
+    det = executor.SurgeDetector(capacity=16, window=2)
+    dec, _ = _run(det, [2, 2, 2, 2], backlog=[50, 40, 17, 16], n_active=2)
+    assert dec == [0, 0, 0, -1]
+
+
+def test_random_sequences_keep_the_instance_count_in_range_and_decisions_apart():
+    rng = np.random.default_rng(5)
+    for _ in range(50):
+        w = int(rng.integers(1, 7))
+        det = executor.SurgeDetector(capacity=float(rng.integers(4, 64)), window=w, max_instances=3)
+        arr = rng.poisson(rng.choice([5, 20, 60, 150]), size=200) * (rng.random(200) < 0.9)
+        dec, act = _run(det, arr.tolist(), backlog=rng.integers(0, 80, size=200).tolist())
+        assert min(act) >= 1 and max(act) <= 3
+        idx = [t for t, d in enumerate(dec) if d]
+        assert all(b - a >= w for a, b in zip(idx, idx[1:]))
+
+
+# ---- what the scaler relies on: copies appended to the pipeline list do not move what is already scheduled ----
+def _models(rng, n):
+    ms = []
+    for i in range(n):
+        base, slope = rng.uniform(1, 6), rng.uniform(0.2, 2.0)
+        ms.append(dict(parent=-1 if i == 0 else int(rng.integers(0, i)), profile={b: base + slope * b for b in (1, 2, 4, 8, 16)},
+                       rate=float(rng.uniform(15, 300)), burstiness=float(rng.uniform(0, 3)), util=float(rng.uniform(0.1, 0.5)),
+                       weight_mem=float(rng.uniform(1, 5)), inter_mem=float(rng.uniform(0.5, 3)), bz=int(rng.choice([1, 2, 4, 8]))))
+    return ms
+
+
+def test_appending_a_copy_leaves_scheduled_portions_where_they_are():
+    rng = np.random.default_rng(11)
+    placed_copies = 0
+    for _ in range(40):
+        pipes = [(_models(rng, int(rng.integers(1, 4))), float(rng.choice([200, 300]))) for _ in range(int(rng.integers(1, 4)))]
+        ns = int(rng.integers(2, 7))
+        base = binding.coral_schedule(pipes, 80.0, 1.0, ns)
+        k = int(rng.integers(0, len(pipes)))
+        ext = binding.coral_schedule(pipes + [pipes[k]], 80.0, 1.0, ns)
+        assert ext[:len(base)] == base
+        copy = ext[len(base):]
+        assert [c[0] for c in copy] == [len(pipes)] * len(pipes[k][0])
+        # the copy's portions do not overlap anything on their streams
+        for c in copy:
+            if c[2] < 0:
+                continue
+            placed_copies += 1
+            for o in ext:
+                if o is not c and o[2] == c[2]:
+                    assert c[4] <= o[3] + 1e-4 or o[4] <= c[3] + 1e-4, (c, o)
+    assert placed_copies > 10
+
+
+# ---- surge in the synthetic arrivals ----
+def test_boosted_arrivals_multiply_the_rate_inside_the_window_only():
+    n, dur = 40, 30.0
+    plain = synth.sinusoid_arrivals(np.random.default_rng(3), n, dur, base_fps=15.0, depth=0.0)
+    boost = synth.sinusoid_arrivals(np.random.default_rng(3), n, dur, base_fps=15.0, depth=0.0, boost=[(10.0, 20.0, 3.0)] * n)
+    def rate(streams, a, b):
+        return sum(int(((s >= a) & (s < b)).sum()) for s in streams) / (len(streams) * (b - a))
+    for s in boost:
+        assert np.all(np.diff(s) >= 0) and s.min() >= 0 and s.max() < dur
+    assert abs(rate(plain, 0, 30) - 15.0) < 0.6
+    assert abs(rate(boost, 0, 10) - 15.0) < 1.0 and abs(rate(boost, 20, 30) - 15.0) < 1.0
+    assert abs(rate(boost, 10, 20) - 45.0) < 2.0
+    # streams without a boost entry are drawn exactly as before while no boosted stream precedes them
+    mixed = synth.sinusoid_arrivals(np.random.default_rng(3), 3, dur, boost=[None, None, (1.0, 2.0, 2.0)])
+    ref = synth.sinusoid_arrivals(np.random.default_rng(3), 3, dur)
+    assert np.array_equal(mixed[0], ref[0]) and np.array_equal(mixed[1], ref[1]) and len(mixed[2]) > len(ref[2]) - 10

@@ -113,3 +113,71 @@ def test_unslotted_unmasked_serving_gives_the_same_results(octo):
     assert res[0] == res[1]
     for P in pipes:
         P.close()
+
+
+def _two_pipelines(dur, n_traffic, n_detonly, surge):
+    """Traffic cascade + detector-only pipeline (half of the GPU stays free for the scaler), surge on the first."""
+    co = executor.make_colocation(dur, n_cameras=(n_traffic, 0, n_detonly), pool_frames=3, det_batch=16, surge=surge)
+    specs = [co.specs[0], co.specs[2]]
+    cams = [executor.Camera(0 if c.pipeline == 0 else 1, c.arrivals_s, c.pool) for c in co.cameras]
+    pools = [co.head_pools[0], co.head_pools[2]]
+    args = ([co.frame_rates[0], co.frame_rates[2]], [co.objects_per_frame[0], co.objects_per_frame[2]],
+            [co.burstiness[0], co.burstiness[2]])
+    return specs, cams, pools, args
+
+
+def test_surge_lazy_dropping_and_a_second_instance(octo):
+    """A 3x surge on one pipeline for 0.8 s (Sec. III-D, IV-A).  The slot discipline serves at most k+1 batches per duty
+    cycle, so the scheduled instance alone falls behind; dropping requests that are already late keeps the rest on
+    time; a stand-by copy that Algorithm 2 places into the free part of the GPU absorbs the surge altogether.  Whatever
+    instance serves a frame, its boxes are the same."""
+    dur, t0, t1 = 2.0, 0.5, 1.3
+    specs, cams, pools, (rates, objs, burst) = _two_pipelines(dur, 24, 8, (0, t0, t1, 3.0))
+    pipes = [octo.Pipeline(s) for s in specs]
+    spare = octo.Pipeline(specs[0])
+    profiles = [executor.profile_pipeline(P, widths=(64, 128, 256), iters=1) for P in pipes]
+    sch = executor.plan(specs, profiles, rates, objs, burst, n_streams=8)
+    total = octo.device_cu_count()
+    assert sum(n for (_, n) in sch.stream_cus.values()) <= total // 2, "the scenario needs free compute units"
+    cap = (sch.batches_per_cycle[0][0] + 1) * sch.bz[0][0]
+    in_surge = sum(int(((c.arrivals_s >= t0) & (c.arrivals_s < t1)).sum()) for c in cams if c.pipeline == 0)
+    assert in_surge / ((t1 - t0) * 1e3 / sch.duty_ms) > 1.3 * cap, "the surge must exceed what the slots can take"
+    runs = {}
+    for tag, kw in (("plain", {}), ("drop", dict(drop_late=True)), ("scaled", dict(spares=[spare, None]))):
+        ex = executor.Executor(pipes, sch, cams, pools, slotted=True, masked=True, keep_results=True, **kw)
+        out = ex.serve(dur)
+        ex.close()
+        runs[tag] = (out, ex.stats, dict(ex.stream_cus))
+        print(tag, out)
+    plain, drop, scaled = runs["plain"][0], runs["drop"][0], runs["scaled"][0]
+    slo = specs[0].slo_ms
+    # the scheduled instance alone: everything is served, much of it late
+    assert plain["dropped"] == 0 and plain["per_pipeline"][0]["served"] == plain["per_pipeline"][0]["submitted"]
+    assert plain["per_pipeline"][0]["slo_met"] < 0.8 * plain["per_pipeline"][0]["submitted"]
+    assert plain["per_pipeline"][1]["slo_met"] == plain["per_pipeline"][1]["submitted"], "the other pipeline keeps its slots"
+    # lazy dropping: nothing is lost track of, what is served is (almost) on time, and more results count
+    p0 = drop["per_pipeline"][0]
+    assert p0["dropped"] > 0 and p0["served"] + p0["dropped"] == p0["submitted"]
+    assert p0["latency_ms_max"] <= slo + 0.5 * sch.duty_ms      # admitted at most one SLO old, then one slot of batches
+    assert p0["slo_met"] > plain["per_pipeline"][0]["slo_met"]
+    # the scaler: one copy added soon after the surge began, placed on compute units nothing else uses
+    ev = scaled["scale_events"]
+    ups = [e for e in ev if e[2] == 1]
+    assert len(ups) == 1 and ups[0][1] == 0 and t0 < ups[0][0] <= t0 + 0.7, ev
+    assert all(e[2] != 0 for e in ev), "there was room, so no request may have been denied"
+    downs = [e for e in ev if e[2] == -1]
+    assert len(downs) <= 1 and all(e[0] > t1 for e in downs), ev        # removed, if at all, only after the surge
+    cus = runs["scaled"][2]
+    new = [cus[s] for s in cus if s not in sch.stream_cus]
+    assert new and all(f >= max(a + b for (a, b) in sch.stream_cus.values()) and f + n <= total for (f, n) in new)
+    assert scaled["dropped"] == 0 and scaled["slo_attainment"] >= 0.97, scaled
+    # every frame, whichever run and instance served it: the boxes depend on the pool frame only
+    ref = {}
+    for tag in runs:
+        for i, S in enumerate(runs[tag][1]):
+            for fid, (k, bx) in S.results.items():
+                assert ref.setdefault((i, k), bx.tobytes()) == bx.tobytes(), (tag, i, fid, k)
+    assert len(runs["scaled"][1][0].results) == scaled["per_pipeline"][0]["submitted"]
+    spare.close()
+    for P in pipes:
+        P.close()
