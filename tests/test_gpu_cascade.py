@@ -248,3 +248,36 @@ def test_sweep_cascade_bursty_counts(octo, bz):
     lab = P.get_labels(0)
     assert len(lab) == len(exp) and np.array_equal(boxes["child_label"][:, 0], lab) and np.all((lab >= 0) & (lab < 1000))
     P.close()
+
+
+@pytest.mark.parametrize("dtype", ["f32", "f16", "bf16"])
+def test_every_tensor_of_a_csp_detector_with_odd_widths(octo, dtype):
+    """Every intermediate tensor of a small CSP detector against the oracle, with channel counts that fill no tile
+    (12, 24, 40, 72, 80, 144: ragged channel tiles, a width that is not a multiple of 8 and so takes the element-wise
+    gather, outputs written into concat slices at odd offsets); once with every tensor kept and once with buffers
+    reused as soon as their last reader is done."""
+    from oracle import nn
+    det = zoo.csp_detector("odd_det", dtype, 128, (16, 24, 48, 80, 144), (1, 2, 1, 1), 3, zoo.SEED0 + 77, batch_size=3,
+                           topk=100, max_det=20)
+    spec = zoo.PipelineSpec("odd", [det], [], 200.0, 96, 160, 3, 8)
+    rng = np.random.default_rng(zoo.SEED0 + 78)
+    scene = synth.make_scene(rng, 3, 96, 160, [3, 2, 4], 8, 48, n_classes=3)
+    ref = None
+    for keep_all in (True, False):
+        P = octo.Pipeline(spec, keep_all_tensors=keep_all)
+        P.submit(_frames_dev(scene.frames))
+        assert P.run() == 3
+        _, _, st = P.collect()
+        assert st == octo.OK
+        if keep_all:
+            x0 = P.get_tensor(0, 0, 3)
+            ref = nn.run_model(det, x0, keep_all=True)
+            shapes = det.tensor_shapes()
+            for t in range(1, len(det.layers) + 1):
+                got = P.get_tensor(0, t, 3)
+                assert got.shape[1:] == tuple(shapes[t]), t
+                assert rel_err(got, ref[t]) <= TOL[dtype], (t, det.layers[t - 1].op, det.layers[t - 1].cout)
+        else:
+            for t in det.outputs:
+                assert rel_err(P.get_tensor(0, t, 3), ref[t]) <= TOL[dtype], t
+        P.close()
