@@ -441,15 +441,21 @@ static hipError_t launch_typed(const ConvArgs& a, int num_cu, hipStream_t s, int
   }
   // Tile choice (measured on MI355X).  Up to 32 output channels: register-staged 32x128 tiles.  Otherwise operands
   // go straight into LDS with K steps of 128 bytes: 128x128 tiles where 128 channels per tile pad the channel count
-  // no further than 64 do (192 = 3 x 64, but 2 x 128) and there are enough tiles to cover the chip, 64x128 tiles for
-  // the middle ground (64x256 with 64-byte K steps for very large, narrow layers), 64x64 tiles at high occupancy for
-  // layers with few output pixels.
+  // no further than 64 do (192 = 3 x 64, but 2 x 128), 64x128 tiles for the middle ground (64x256 with 64-byte K steps
+  // for very large, narrow layers), 64x64 tiles for layers with few output pixels.  How many tiles a shape must yield
+  // depends on the length of the reduction.  A layer with a short K loop is dominated by start-up and epilogue and runs
+  // fastest on the shape that spreads it over all compute units.  A long K loop is paced by the operand fetch from the
+  // L2s, so the shape with the most arithmetic per fetched byte wins as soon as a quarter of the compute units get a
+  // tile: alone it takes a little longer, but it moves half the bytes, and kernels of other streams use the rest of
+  // the chip meanwhile (+4 % on the traffic cascade with four pipeline instances).
   if (a.Cout <= 32) return launch_cfg<T, 32, 128, 1, 4, 4, 2, 4, true>(a, num_cu, s, kernel_id, tm);
   const bool fits128 = a.Cout >= 96 && (a.Cout + 127) / 128 * 128 == (a.Cout + 63) / 64 * 64;
-  if (fits128 && tiles(128, 128) >= 5 * num_cu / 4) return launch_cfg<T, 128, 128, 2, 2, 8, 1, 2, true, true>(a, num_cu, s, kernel_id, tm);
+  if (fits128 && tiles(128, 128) >= (a.Kp >= 1024 ? num_cu / 4 : 5 * num_cu / 4))
+    return launch_cfg<T, 128, 128, 2, 2, 8, 1, 2, true, true>(a, num_cu, s, kernel_id, tm);
   // very many pixels and at most 64 channels (store-bound first layers, wide early stages): 256-pixel tiles
   if (a.Cout <= 64 && tiles(64, 256) >= 4 * num_cu) return launch_cfg<T, 64, 256, 1, 4, 4, 1, 3, true, true>(a, num_cu, s, kernel_id, tm);
-  if (tiles(64, 128) >= 9 * num_cu / 8) return launch_cfg<T, 64, 128, 2, 2, 8, 1, 3, true, true>(a, num_cu, s, kernel_id, tm);
+  if (tiles(64, 128) >= (a.Kp >= 512 ? num_cu / 4 : 9 * num_cu / 8))
+    return launch_cfg<T, 64, 128, 2, 2, 8, 1, 3, true, true>(a, num_cu, s, kernel_id, tm);
   return launch_cfg<T, 64, 64, 2, 2, 8, 1, 4, true, true>(a, num_cu, s, kernel_id, tm);
 }
 
