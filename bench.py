@@ -74,11 +74,11 @@ def conv_name(kid: int, dtype: str) -> str:
 # calibration pass of known size).  Valid only for the kernel source it was taken with: keyed by a hash of conv.hip.
 TRAFFIC = {
     # sha256(conv.hip)[:16]: {kernel name: bytes per launch}
-    "e7cbe333664d5957": {
-        "octo::conv_mfma_kernel<_Float16, 64, 64, 2, 2, 8, 1, 4, true, true>": 13369631,
-        "octo::conv_mfma_kernel<_Float16, 64, 128, 2, 2, 8, 1, 3, true, true>": 24440758,
-        "octo::conv_mfma_kernel<_Float16, 128, 128, 2, 2, 8, 1, 2, true, true>": 34824105,
-        "octo::conv_mfma_kernel<_Float16, 32, 128, 1, 4, 4, 2, 4, true, false>": 23949707,
+    "dae568f40f073d9b": {
+        "octo::conv_mfma_kernel<_Float16, 128, 128, 2, 2, 8, 1, 2, true, true>": 28915761,
+        "octo::conv_mfma_kernel<_Float16, 64, 128, 2, 2, 8, 1, 3, true, true>": 17868058,
+        "octo::conv_mfma_kernel<_Float16, 64, 64, 2, 2, 8, 1, 4, true, true>": 7607163,
+        "octo::conv_mfma_kernel<_Float16, 32, 128, 1, 4, 4, 2, 4, true, false>": 23949629,
     },
 }
 
