@@ -166,6 +166,110 @@ __global__ void crop_resize_kernel(const ResizeArgs a) {
   }
 }
 
+// Crop-resize with the source rows staged in LDS.  One wavefront (a 64-thread workgroup) produces one output row of
+// one ROI, 4 pixels per lane.  The two source rows it taps are first copied into LDS - only the span of pixels this
+// part of the row needs, with aligned 16-byte loads - and every lane then picks its taps from there.  Sampling
+// straight from global memory costs two 12-byte loads at arbitrary addresses per output pixel; for crops that are
+// enlarged or mildly reduced (the usual case: objects of 24-360 pixels to 224) neighbouring lanes hit the same few
+// cache lines over and over, and the kernel runs at the rate the L1 can look lines up, not at memory bandwidth.
+// A span too long for the buffer (strong reduction: taps of neighbouring pixels share no lines anyway) is sampled
+// directly, as in the kernel above.  Same arithmetic, so the results are identical.
+constexpr int CROP_ROWBUF = 2048;     // bytes of LDS per staged source row
+
+template <typename T, bool C4>
+__global__ __launch_bounds__(64) void crop_resize_rows_kernel(const ResizeArgs a) {
+  __shared__ __attribute__((aligned(16))) uint8_t srow[2][CROP_ROWBUF];
+  const int wq = a.dst_w / 4;
+  int n_items = a.n;
+  if (a.n_dyn) { int d = *a.n_dyn; n_items = d < a.n ? (d < 0 ? 0 : d) : a.n; }
+  const unsigned total_rows = (unsigned)n_items * (unsigned)a.dst_h;       // < 2^31 (checked by the launcher)
+  const int lane = threadIdx.x;
+  T* dst = (T*)a.dst;
+  for (unsigned row = blockIdx.x; row < total_rows; row += gridDim.x) {
+    const int roi = (int)fast_div(row, a.div_h);
+    const int y = (int)(row - (unsigned)roi * (unsigned)a.dst_h);
+    const octo_roi r = a.rois[roi];
+    const int fr = clampi(r.frame, 0, a.n_frames - 1);
+    const uint8_t* base = a.frames[fr];
+    const size_t pitch = a.pitches[fr];
+    const float sy = r.y1 + ((float)y + 0.5f) * ((r.y2 - r.y1) / (float)a.dst_h) - 0.5f;
+    const float y0f = floorf(sy);
+    const float fy = sy - y0f;
+    const int ya = clampi((int)y0f, 0, a.src_h - 1), yb = clampi((int)y0f + 1, 0, a.src_h - 1);
+    const uint8_t* rowp[2] = {base + (size_t)ya * pitch, base + (size_t)yb * pitch};
+    const float step = (r.x2 - r.x1) / (float)a.dst_w;
+    for (int xq0 = 0; xq0 < wq; xq0 += 64) {
+      // source pixels this chunk of the row taps: the coordinate is monotonic in the output pixel, so the ends bound it
+      const int pa = xq0 * 4, pb = (xq0 + 64 < wq ? xq0 + 64 : wq) * 4 - 1;
+      const float sa = r.x1 + ((float)pa + 0.5f) * step - 0.5f, sb = r.x1 + ((float)pb + 0.5f) * step - 0.5f;
+      const int xlo = clampi((int)floorf(fminf(sa, sb)), 0, a.src_w - 1);
+      const int xhi = clampi((int)floorf(fmaxf(sa, sb)) + 1, 0, a.src_w - 1);
+      const int span = (xhi - xlo + 1) * 3;
+      const bool staged = span > 0 && span + 32 <= CROP_ROWBUF;
+      int koff[2] = {0, 0};                // LDS byte index of source pixel x in row rr: koff[rr] + 3 * x
+      if (staged) {
+#pragma unroll
+        for (int rr = 0; rr < 2; ++rr) {
+          const uint8_t* p0 = rowp[rr] + 3 * xlo;
+          const uint8_t* a0 = (const uint8_t*)((uintptr_t)p0 & ~(uintptr_t)15);
+          const int nvec = (int)((p0 + span - a0 + 15) >> 4);
+          const uint8_t* row_end = rowp[rr] + (size_t)a.src_w * 3;
+          for (int v = lane; v < nvec; v += 64) {
+            const uint8_t* va = a0 + 16 * v;
+            uint4 q;
+            if (va >= rowp[rr] && va + 16 <= row_end) {
+              q = *(const uint4*)va;
+            } else {
+              // first or last vector of the row: never touch bytes outside the row
+              alignas(16) uint8_t b[16];
+#pragma unroll
+              for (int e = 0; e < 16; ++e) b[e] = (va + e >= rowp[rr] && va + e < row_end) ? va[e] : (uint8_t)0;
+              q = *(const uint4*)b;
+            }
+            *(uint4*)&srow[rr][16 * v] = q;
+          }
+          koff[rr] = (int)(p0 - a0) - 3 * xlo;
+        }
+      }
+      __syncthreads();
+      const int xq = xq0 + lane;
+      if (xq < wq) {
+        float v[12];
+#pragma unroll
+        for (int px = 0; px < 4; ++px) {
+          const float sx = r.x1 + ((float)(xq * 4 + px) + 0.5f) * step - 0.5f;
+          const float x0f = floorf(sx);
+          const float fx = sx - x0f;
+          const int xa = clampi((int)x0f, 0, a.src_w - 1), xb = clampi((int)x0f + 1, 0, a.src_w - 1);
+          if (staged) {
+            float t[2][2][3];
+#pragma unroll
+            for (int rr = 0; rr < 2; ++rr)
+#pragma unroll
+              for (int tp = 0; tp < 2; ++tp) {
+                int k = koff[rr] + 3 * (tp ? xb : xa);
+                k = k < 0 ? 0 : (k > CROP_ROWBUF - 8 ? CROP_ROWBUF - 8 : k);      // taps lie inside the span; non-finite boxes must not index outside the buffer
+                const uint32_t* w = (const uint32_t*)&srow[rr][k & ~3];
+                const unsigned u = (unsigned)((((unsigned long long)w[1] << 32) | w[0]) >> (8 * (k & 3)));
+                t[rr][tp][0] = (float)(u & 0xFFu); t[rr][tp][1] = (float)((u >> 8) & 0xFFu); t[rr][tp][2] = (float)((u >> 16) & 0xFFu);
+              }
+#pragma unroll
+            for (int c = 0; c < 3; ++c) {
+              float top = (1.0f - fx) * t[0][0][c] + fx * t[0][1][c];
+              float bot = (1.0f - fx) * t[1][0][c] + fx * t[1][1][c];
+              v[3 * px + c] = ((1.0f - fy) * top + fy * bot) * a.scale[c] + a.bias[c];
+            }
+          } else {
+            bilinear_rgb(rowp[0], rowp[1], xa, xb, a.src_w, fx, fy, a.scale, a.bias, v + 3 * px);
+          }
+        }
+        store_pixels<T, 4, C4>(dst + (((size_t)roi * a.dst_h + y) * a.dst_w + (size_t)xq * 4) * (C4 ? 4 : 3), v);
+      }
+      __syncthreads();                   // the next chunk overwrites the staged rows
+    }
+  }
+}
+
 static inline unsigned resize_grid(long long work) {
   long long g = (work + 255) / 256;
   if (g < 1) g = 1;
@@ -220,12 +324,15 @@ template <typename T> static hipError_t letterbox_t(const ResizeArgs& a, hipStre
   return exact ? letterbox_e<T, true>(a, g, s) : letterbox_e<T, false>(a, g, s);
 }
 template <typename T> static hipError_t crop_t(const ResizeArgs& a, hipStream_t s) {
+  // one 64-thread workgroup per output row, at most 32 per compute unit at a time, striding over the rows
+  const long long rows = (long long)a.n * a.dst_h;
+  const unsigned row_grid = (unsigned)(rows < 256 * 32 ? (rows < 1 ? 1 : rows) : 256 * 32);
   if (a.dst_c == 4 && ((uintptr_t)a.dst & 15) == 0 && a.dst_w % 4 == 0) {
-    hipLaunchKernelGGL((crop_resize_kernel<T, 4, true>), dim3(resize_grid((long long)a.n * a.dst_h * (a.dst_w / 4))), dim3(256), 0, s, a);
+    hipLaunchKernelGGL((crop_resize_rows_kernel<T, true>), dim3(row_grid), dim3(64), 0, s, a);
   } else if (a.dst_c == 4) {
     hipLaunchKernelGGL((crop_resize_kernel<T, 1, true>), dim3(resize_grid((long long)a.n * a.dst_h * a.dst_w)), dim3(256), 0, s, a);
   } else if (a.dst_w % 4 == 0 && ((uintptr_t)a.dst & 15) == 0) {
-    hipLaunchKernelGGL((crop_resize_kernel<T, 4, false>), dim3(resize_grid((long long)a.n * a.dst_h * (a.dst_w / 4))), dim3(256), 0, s, a);
+    hipLaunchKernelGGL((crop_resize_rows_kernel<T, false>), dim3(row_grid), dim3(64), 0, s, a);
   } else {
     hipLaunchKernelGGL((crop_resize_kernel<T, 1, false>), dim3(resize_grid((long long)a.n * a.dst_h * a.dst_w)), dim3(256), 0, s, a);
   }

@@ -65,6 +65,39 @@ def test_crop_resize_parity(octo, dtype):
     assert float(empty.float().abs().max()) == 0.0
 
 
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_crop_resize_wide_outputs_and_all_sampling_regimes(octo, dtype):
+    """Output rows of 224 and 260 pixels (the second needs more than one pass of a wavefront over the row), boxes
+    from a few pixels (strong enlargement: all lanes share a handful of source bytes) to the whole frame (strong
+    reduction: the source span of a row does not fit the staging buffer), boxes on every frame border, inverted and
+    empty boxes, frames whose rows are strided views (arbitrary byte alignment of every row)."""
+    import torch
+    rng = np.random.default_rng(16)
+    big = torch.from_numpy(rng.integers(0, 256, (2, 300, 1301, 3), dtype=np.uint8)).cuda()
+    views = [big[i, :, 1:1298] for i in range(2)]                  # 1297 pixels per row, pitch 3903 bytes, rows start at odd addresses
+    frames = np.stack([v.cpu().numpy() for v in views])
+    H, W = 300, 1297
+    boxes = [[0, 0, W, H], [0, 0, 5, 4], [W - 6, H - 5, W, H], [100.3, 50.7, 130.9, 90.2], [3, 3, 900, 40], [0, 120, W, 130],
+             [W - 1, 0, W, H], [500, 299, 700, 300], [640, 10, 600, 200], [10, 250, 400, 200], [77, 77, 77, 77],
+             [-20, -10, 60, 50], [W - 50, H - 40, W + 30, H + 25], [200.5, 100.5, 424.5, 212.5]]
+    for _ in range(20):
+        x, y = rng.uniform(0, W - 8), rng.uniform(0, H - 8)
+        w, h = np.exp(rng.uniform(np.log(4), np.log(900))), np.exp(rng.uniform(np.log(4), np.log(250)))
+        boxes.append([x, y, min(x + w, W), min(y + h, H)])
+    box = np.asarray(boxes, np.float32)
+    n = len(box)
+    fr = rng.integers(0, 2, n).astype(np.int32)
+    rois = np.zeros(n, octo.ROI_DTYPE)
+    rois["frame"], rois["x1"], rois["y1"], rois["x2"], rois["y2"] = fr, box[:, 0], box[:, 1], box[:, 2], box[:, 3]
+    tol = {"f32": 2e-4, "bf16": 8e-3}[dtype]
+    for (oh, ow) in ((9, 224), (5, 260), (7, 64)):
+        got = _host(octo.op_crop_resize(views, rois, oh, ow, dtype, cap=n + 2), dtype)
+        ref = pre.crop_resize(frames, fr, box, oh, ow, dtype)
+        err = np.abs(got[:n] - ref).reshape(n, -1).max(axis=1)
+        assert err.max() <= tol, (oh, ow, int(err.argmax()), boxes[int(err.argmax())])
+        assert np.all(got[n:] == 0)
+
+
 # ---------------------------------------------------------------- conv graph
 def _model(dtype, in_hw, in_c, build, batch):
     rng = np.random.default_rng(7)
