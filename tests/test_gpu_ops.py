@@ -185,6 +185,35 @@ def test_wide_3x3_layers_with_residuals(octo, dtype):
         assert rel_err(got[t], ref[t]) <= TOL[dtype], t
 
 
+@pytest.mark.parametrize("dtype", ["f16", "bf16"])
+def test_3x3_64_channel_layers_on_wide_maps(octo, dtype):
+    """64 -> 64 (and 64 -> 40) channel 3x3 layers large enough for the kernel with the input patch in LDS: ragged tile
+    edges in both directions (52 = 6 x 8 + 4 rows, 60 = 32 + 28 columns), SiLU / ReLU, both residual modes, an input that
+    is a channel slice of a wider buffer (the concat), and a batch whose tile count is not a multiple of the workgroup
+    count."""
+    def build(B):
+        a = B.conv(0, 64, 3, 1, act=zoo.ACT_SILU)
+        b = B.conv(a, 40, 3, 1, act=zoo.ACT_RELU)
+        c = B.conv(a, 64, 3, 1, act=zoo.ACT_SILU, res=a, res_mode=zoo.RES_AFTER_ACT)
+        d = B.conv(c, 64, 3, 1, act=zoo.ACT_RELU, res=a, res_mode=zoo.RES_BEFORE_ACT)
+        e = B.cat([d, c])
+        return B.conv(e, 24, 1, 1)
+    n = 49
+    m = _model(dtype, (52, 60), 64, build, n)
+    x = zoo.round_to_dtype(np.random.default_rng(13).uniform(-1, 1, (n, 52, 60, 64)).astype(np.float32), dtype)
+    root = small_root(dtype)
+    spec = zoo.PipelineSpec("t", [root, m], [], 200.0, 32, 32, 1, 1)
+    P = octo.Pipeline(spec, keep_all_tensors=True)
+    P.run_model_on(1, octo.to_device(x, dtype))
+    got = [P.get_tensor(1, t, n) for t in range(len(m.layers) + 1)]
+    kid = P.layer_info(1)[1]
+    P.close()
+    assert [int(k) for k in kid[:4]] == [1800064064] * 4, kid          # the patch kernel, 64-channel slices, 64 output channels
+    ref = nn.run_model(m, x, keep_all=True)
+    for t in range(1, len(m.layers) + 1):
+        assert rel_err(got[t], ref[t]) <= TOL[dtype], t
+
+
 def test_memory_reuse_keeps_outputs_intact(octo):
     # same graph with and without per-tensor buffers must give the same logits
     m = zoo.residual_classifier("r", "f16", 64, 64, "basic", (1, 1, 1, 1), 10, seed=3, batch_size=4)
