@@ -263,8 +263,9 @@ def run_surge(args):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=400)
-    ap.add_argument("--warmup", type=int, default=40)
+    ap.add_argument("--steps", type=int, default=None, help="timed batches (default: 4000 for the traffic workload, about 3.5 s; 200 for "
+                    "the high-resolution one, about 8 s; 400 otherwise)")
+    ap.add_argument("--warmup", type=int, default=None, help="untimed batches before them (default: steps / 20)")
     ap.add_argument("--workload", default="traffic")
     ap.add_argument("--instances", type=int, default=None,
                     help="copies of the pipeline (own activations and tables) that take batches in turn, each on its own "
@@ -283,6 +284,10 @@ def main():
     args = ap.parse_args()
     if args.instances is None:
         args.instances = 1 if args.workload in ("hires", "tiny") else 4
+    if args.steps is None:
+        args.steps = {"traffic": 4000, "hires": 200}.get(args.workload, 400)
+    if args.warmup is None:
+        args.warmup = max(4, args.steps // 20)
     if args.gpus != 1:
         print("bench.py measures one GPU only (frames are independent: more GPUs = more copies of this run); --gpus %d refused" % args.gpus,
               file=sys.stderr)
