@@ -137,3 +137,51 @@ def test_hires_workload_full_batch_on_samples(octo):
 
 def det_heads_layers(det):
     return [t - 1 for t in det.outputs]
+
+
+@pytest.mark.parametrize("bz", [8, 64])
+def test_sweep_workload_at_full_batch_on_samples(octo, bz):
+    """The batch-size sweep's configuration (bf16, negative-binomial object counts) exactly as bench.py builds it, at
+    its largest batch and at 8: all integer work on every frame, convolution layers on sampled outputs from both ends
+    of the batch, classifier logits on ROIs from both ends of the table."""
+    from paper_2502_01277_amd import synth, zoo
+    spec = zoo.sweep_cascade(bz)
+    det, cls = spec.models
+    rng = np.random.default_rng(zoo.SEED0 + 3)
+    counts = synth.counts_negbin(rng, bz)
+    scene = synth.make_scene(rng, bz, 1080, 1920, counts, 24, 200, log_uniform=True)
+    heads = synth.planted_heads(rng, det, scene, 1080, 1920)
+    P = octo.Pipeline(spec, keep_all_tensors=True)
+    d_heads = [octo.to_device(h, det.dtype) for h in heads]
+    for l, h in enumerate(d_heads):
+        P.set_head(0, l, h)
+    P.submit(_dev(scene.frames))
+    assert P.run() == bz
+    frames, boxes, st = P.collect(frame_cap=bz, box_cap=bz * det.max_det)
+    assert st == octo.OK and len(frames) == bz
+    dets = cascade.postprocess_heads(heads, det)
+    for f, d in enumerate(dets):
+        cc, top, keep = P.get_detections(0, f)
+        assert cc == d.cand_count and top["idx"].tolist() == d.top.idx.tolist() and keep.tolist() == d.keep.tolist(), f
+    assert frames["n_boxes"].tolist() == [len(d.keep) for d in dets]
+    rois = P.get_rois(0)
+    assert list(zip(rois["frame"].tolist(), rois["rank"].tolist())) == [(f, r) for f, d in enumerate(dets) for r in range(len(d.keep))]
+    k = min(2, bz // 2)
+    rng2 = np.random.default_rng(79)
+    conv_ids = [i for i, L in enumerate(det.layers) if L.op == "conv"]
+    for i in sorted(set(conv_ids[::9] + det_heads_layers(det))):
+        L = det.layers[i]
+        x = _ends(P, 0, L.inputs[0], bz, k)
+        y = _ends(P, 0, i + 1, bz, k)
+        res = _ends(P, 0, L.inputs[1], bz, k) if len(L.inputs) > 1 else None
+        pos = _sample_positions(rng2, 2 * k, y.shape[1], y.shape[2], 16)
+        assert rel_err(np.stack([y[a, b, c] for (a, b, c) in pos]), nn.conv_layer_at(x, L, det.dtype, pos, res)) <= TOL[det.dtype], (i, L.kh, L.stride)
+    n_roi = len(rois)
+    assert n_roi >= 8
+    pick = [0, 1, n_roi // 2, n_roi - 2, n_roi - 1]
+    box = np.stack([rois["x1"], rois["y1"], rois["x2"], rois["y2"]], 1)[pick].astype(np.float64)
+    crops = pre.crop_resize(scene.frames, rois["frame"][pick], box, cls.in_h, cls.in_w, cls.dtype, cls.norm_scale, cls.norm_bias)
+    ref_logits = nn.run_model(cls, crops)[cls.outputs[0]].reshape(len(pick), -1)
+    logits = P.get_tensor(1, cls.outputs[0], n_roi).reshape(n_roi, -1)[pick]
+    assert rel_err(logits, ref_logits) <= TOL[cls.dtype]
+    P.close()
