@@ -12,6 +12,15 @@ def pytest_configure(config):
     config.addinivalue_line("markers", "gpu: needs a real MI355X (run with -m gpu)")
 
 
+@pytest.fixture(scope="session", autouse=True)
+def _library_is_built():
+    """The tests load the library that is built in-tree; only if there is none (a fresh checkout) it is built once."""
+    from paper_2502_01277_amd import binding
+    if not os.path.exists(binding.LIB_PATH):
+        from paper_2502_01277_amd import build
+        build.build(verbose=False)
+
+
 @pytest.fixture(scope="session")
 def octo():
     """The ctypes binding over the HIP library; GPU tests fail loudly if it cannot load or no GPU is present."""
