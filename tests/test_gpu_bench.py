@@ -39,3 +39,19 @@ def test_default_workload_prints_one_json_line_with_the_agreed_fields():
 def test_more_than_one_gpu_is_refused_with_a_message():
     r = _bench("--gpus", "2")
     assert r.returncode == 2 and "one GPU" in r.stderr and r.stdout.strip() == ""
+
+
+@pytest.mark.parametrize("args,keys", [
+    (["--workload", "hires", "--steps", "3", "--warmup", "1", "--no-cpu-baseline"], ["roofline"]),
+    (["--workload", "colocate", "--duration", "0.5"], ["portions", "no_portions", "static_batch", "schedule"]),
+    (["--workload", "surge", "--duration", "1.5", "--camera-scale", "4"], ["scheduled_only", "lazy_dropping", "scaler", "scaler_and_dropping"]),
+])
+def test_other_workloads_print_one_json_line(args, keys):
+    r = _bench(*args)
+    assert r.returncode == 0, r.stderr[-2000:]
+    lines = [l for l in r.stdout.splitlines() if l.strip()]
+    assert len(lines) == 1
+    d = json.loads(lines[0])
+    assert d["n_gpus"] == 1 and d["vs_baseline"] is None and d["unit"] == "frames/s" and d["value"] > 0 and "workload" in d["config"]
+    for k in keys:
+        assert k in d, k
