@@ -155,6 +155,13 @@ octo_status octo_collect(octo_pipeline* p, octo_frame_result* frames, int32_t fr
                          int32_t* n_frames, int32_t* n_boxes, int32_t blocking);
 
 octo_status octo_set_batch_size(octo_pipeline* p, int32_t model, int32_t bz);   /* 1 <= bz <= the model's capacity */
+/* Every model has a batch size of its own (Sec. III-B, Algorithm 1): with frames_per_execution = b > 0 the detector's
+ * layers and post-processing run on b frames at a time, ceil(n / b) executions per batch of n frames, while the
+ * downstream models still run once on the ROIs of the whole batch - a detector at batch size b feeding children that
+ * batch the objects of several of its executions.  0 (the default): one execution for the whole batch.  Results are
+ * identical either way.  Layer tensors read back with octo_debug_get_tensor, and the per-layer times, are those of
+ * the last execution.  0 <= b <= max_frames. */
+octo_status octo_set_detector_batch(octo_pipeline* p, int32_t frames_per_execution);
 const char* octo_last_error(const octo_pipeline* p);    /* library-owned text, valid until the next call on p (NULL p: last create error) */
 double octo_now_ms(void);                               /* monotonic host clock used for arrival / completion times */
 

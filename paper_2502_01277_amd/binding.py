@@ -82,7 +82,7 @@ class OctoPlacement(C.Structure):
 # Every symbol include/octo.h declares.
 EXPORTS = [
     "octo_pipeline_workspace_size", "octo_pipeline_create", "octo_pipeline_destroy", "octo_submit_frames", "octo_run",
-    "octo_collect", "octo_set_batch_size", "octo_last_error", "octo_now_ms", "octo_stream_create_masked", "octo_stream_create_range",
+    "octo_collect", "octo_set_batch_size", "octo_set_detector_batch", "octo_last_error", "octo_now_ms", "octo_stream_create_masked", "octo_stream_create_range",
     "octo_stream_destroy", "octo_device_cu_count", "octo_cwd_search", "octo_coral_schedule", "octo_est_latency_ms",
     "octo_est_throughput", "octo_run_model", "octo_profile_layers", "octo_set_layer_timing", "octo_get_layer_info", "octo_set_stage_timing", "octo_get_stage_ms",
     "octo_debug_get_tensor", "octo_debug_tensor_shape", "octo_debug_set_head", "octo_debug_run_model",
@@ -115,6 +115,7 @@ def lib() -> C.CDLL:
         L.octo_run_model.argtypes = [vp, i32, vp, vp]
         L.octo_collect.argtypes = [vp, vp, i32, vp, i32, vp, vp, i32]
         L.octo_set_batch_size.argtypes = [vp, i32, i32]
+        L.octo_set_detector_batch.argtypes = [vp, i32]
         L.octo_stream_create_masked.argtypes = [vp, i32, vp]
         L.octo_stream_create_range.argtypes = [i32, i32, vp]
         L.octo_stream_destroy.argtypes = [vp]
@@ -306,6 +307,9 @@ class Pipeline:
 
     def set_batch_size(self, model: int, bz: int):
         self._check(self.L.octo_set_batch_size(self.h, model, bz))
+
+    def set_detector_batch(self, frames_per_execution: int):
+        self._check(self.L.octo_set_detector_batch(self.h, frames_per_execution))
 
     # ---- hooks ----
     def tensor_shape(self, model: int, tid: int):

@@ -68,6 +68,7 @@ struct ModelPlan {
   bool input_c4 = false;   // tensor 0 is stored with a zero fourth channel
   int cap = 0;             // item capacity
   int bz = 0;              // current batch size (root: frames per batch)
+  int exec_bz = 0;         // root only: frames per execution of the detector's layers (0: the whole batch at once)
   const int* n_dyn = nullptr;
   double items_hint = 0;   // smoothed item count of recent batches (children; 0: none seen yet)
   char* act_base = nullptr;
@@ -479,27 +480,32 @@ hipError_t run_layers(octo_pipeline* p, ModelPlan& m, int n, const int* n_dyn, h
   return hipSuccess;
 }
 
-// decode -> top-k -> NMS of a detector (root or child) for n items
-hipError_t run_detect_tail(octo_pipeline* p, ModelPlan& m, int n, const int* n_dyn, hipStream_t s, hipEvent_t* evs) {
-  hipError_t e = launch_fill_i32(m.cand_count, 0, m.cap * CNT_STRIDE, s);
+// decode -> top-k -> NMS of a detector (root or child) for n items.  The head tensors hold items 0 .. n-1 of this
+// execution; their results go to slots item0 .. item0 + n - 1 of the model's per-item arrays (item0 > 0 when the
+// detector of one batch runs in several executions).
+hipError_t run_detect_tail(octo_pipeline* p, ModelPlan& m, int n, const int* n_dyn, hipStream_t s, hipEvent_t* evs, int item0 = 0) {
+  hipError_t e = launch_fill_i32(m.cand_count + (size_t)item0 * CNT_STRIDE, 0, n * CNT_STRIDE, s);
   if (e != hipSuccess) return e;
   DecodeArgs da{};
   da.n_levels = m.d.n_outputs;
+  const int es = dtype_size(m.d.dtype);
   for (int l = 0; l < m.d.n_outputs; ++l) {
     const TensorView h = view_of(m, m.d.outputs[l]);
-    if (m.head_override[l]) { da.head[l] = m.head_override[l]; da.head_ld[l] = h.c; }
-    else { da.head[l] = (const char*)h.ptr + (size_t)h.coff * dtype_size(m.d.dtype); da.head_ld[l] = h.ld; }
+    if (m.head_override[l]) { da.head[l] = (const char*)m.head_override[l] + (size_t)item0 * h.h * h.w * h.c * es; da.head_ld[l] = h.c; }
+    else { da.head[l] = (const char*)h.ptr + (size_t)h.coff * es; da.head_ld[l] = h.ld; }
     da.gh[l] = m.gh[l]; da.gw[l] = m.gw[l]; da.stride[l] = m.d.stride[l];
     memcpy(da.anchors[l], m.d.anchors[l], sizeof da.anchors[l]);
   }
   da.n_anchors = m.d.n_anchors; da.n_classes = m.d.n_classes; da.score_thr = m.d.score_thr;
-  da.n = n; da.n_dyn = n_dyn; da.cand = m.cand; da.count = m.cand_count; da.cap = m.n_cand; da.count_stride = CNT_STRIDE; da.overflow = m.flags;
+  da.n = n; da.n_dyn = n_dyn; da.cand = m.cand + (size_t)item0 * m.n_cand; da.count = m.cand_count + (size_t)item0 * CNT_STRIDE; da.cap = m.n_cand;
+  da.count_stride = CNT_STRIDE; da.overflow = m.flags + item0;
   if ((e = launch_decode(m.d.dtype, da, s)) != hipSuccess) return e;
   if (evs) hipEventRecord(evs[0], s);
-  TopkArgs ta{m.cand, m.cand_count, m.n_cand, CNT_STRIDE, m.top, m.top_count, std::min(m.d.topk, m.n_cand), m.k_cap, n, n_dyn};
+  TopkArgs ta{da.cand, da.count, m.n_cand, CNT_STRIDE, m.top + (size_t)item0 * m.k_cap, m.top_count + item0, std::min(m.d.topk, m.n_cand), m.k_cap, n, n_dyn};
   if ((e = launch_topk(ta, s)) != hipSuccess) return e;
   if (evs) hipEventRecord(evs[1], s);
-  NmsArgs na{m.top, m.top_count, m.k_cap, m.d.iou_thr, m.d.max_det, m.mask, m.keep, m.n_keep, n, n_dyn};
+  // the suppression bit mask is scratch of one execution: every execution uses the first n items' worth of it
+  NmsArgs na{ta.out, ta.out_count, m.k_cap, m.d.iou_thr, m.d.max_det, m.mask, m.keep + (size_t)item0 * m.d.max_det, m.n_keep + item0, n, n_dyn};
   if ((e = launch_nms(na, s)) != hipSuccess) return e;
   if (evs) hipEventRecord(evs[2], s);
   return hipSuccess;
@@ -655,16 +661,26 @@ octo_status start_batch(octo_pipeline* p, hipStream_t s, int* launched) {
   HIPCHK(p, hipMemcpyAsync(p->d_pitch[B.slot], hpitch, n * sizeof(size_t), hipMemcpyHostToDevice, s));
   if (ev) HIPCHK(p, hipEventRecord(ev[0], s));
   ResizeArgs ra{};
-  ra.frames = p->d_frames[B.slot]; ra.pitches = p->d_pitch[B.slot]; ra.src_h = p->d.src_h; ra.src_w = p->d.src_w;
+  ra.src_h = p->d.src_h; ra.src_w = p->d.src_w;
   ra.dst = view_of(root, 0).ptr; ra.dst_h = root.d.in_h; ra.dst_w = root.d.in_w; ra.dst_c = root.input_c4 ? 4 : 3;
   for (int c = 0; c < 3; ++c) { ra.scale[c] = root.d.norm_scale[c]; ra.bias[c] = root.d.norm_bias[c]; }
-  ra.pad_value = root.d.pad_value; ra.n = n; ra.n_frames = n;
-  HIPCHK(p, launch_letterbox(root.d.dtype, ra, s));
-  if (ev) HIPCHK(p, hipEventRecord(ev[1 + ST_LETTERBOX], s));
-  HIPCHK(p, run_layers(p, root, n, nullptr, s, p->layer_timing ? &B.layer_ev[0] : nullptr));
-  if (ev) HIPCHK(p, hipEventRecord(ev[1 + ST_DET_LAYERS], s));
+  ra.pad_value = root.d.pad_value;
   HIPCHK(p, launch_fill_i32((int*)p->d_result, 0, (int)((p->off_boxes) / sizeof(int)), s));   // n_keep, flags, n_roi
-  HIPCHK(p, run_detect_tail(p, root, n, nullptr, s, ev ? ev + 1 + ST_DECODE : nullptr));
+  // The detector runs on exec_bz frames at a time (its own batch size; by default the whole batch), every execution
+  // through the same activation buffers; candidates, top-k lists and keep lists are per frame and collect in place.
+  // Stage events (when enabled) bracket the last execution's stages; the letterbox and layer stages of the earlier
+  // executions fall into the "letterbox" interval.
+  const int chunk = root.exec_bz > 0 && root.exec_bz < n ? root.exec_bz : n;
+  for (int c0 = 0; c0 < n; c0 += chunk) {
+    const int cn = std::min(chunk, n - c0);
+    const bool last = c0 + cn >= n;
+    ra.frames = p->d_frames[B.slot] + c0; ra.pitches = p->d_pitch[B.slot] + c0; ra.n = cn; ra.n_frames = cn;
+    HIPCHK(p, launch_letterbox(root.d.dtype, ra, s));
+    if (ev && last) HIPCHK(p, hipEventRecord(ev[1 + ST_LETTERBOX], s));
+    HIPCHK(p, run_layers(p, root, cn, nullptr, s, p->layer_timing && last ? &B.layer_ev[0] : nullptr));
+    if (ev && last) HIPCHK(p, hipEventRecord(ev[1 + ST_DET_LAYERS], s));
+    HIPCHK(p, run_detect_tail(p, root, cn, nullptr, s, ev && last ? ev + 1 + ST_DECODE : nullptr, c0));
+  }
   CompactArgs ca{};
   ca.top = root.top; ca.k_cap = root.k_cap; ca.keep = root.keep; ca.n_keep = root.n_keep; ca.max_det = root.d.max_det; ca.n = n;
   ca.left = (float)p->left; ca.top_pad = (float)p->top;
@@ -804,6 +820,13 @@ octo_status octo_set_batch_size(octo_pipeline* p, int32_t model, int32_t bz) {
   if (!p) return OCTO_EINVAL;
   if (model < 0 || model >= (int)p->models.size() || bz < 1 || bz > p->models[model].cap) return fail(p, OCTO_EINVAL, "bad model or batch size");
   p->models[model].bz = bz;
+  return OCTO_OK;
+}
+
+octo_status octo_set_detector_batch(octo_pipeline* p, int32_t frames_per_execution) {
+  if (!p) return OCTO_EINVAL;
+  if (frames_per_execution < 0 || frames_per_execution > p->models[0].cap) return fail(p, OCTO_EINVAL, "bad detector batch size");
+  p->models[0].exec_bz = frames_per_execution;
   return OCTO_OK;
 }
 

@@ -281,3 +281,57 @@ def test_every_tensor_of_a_csp_detector_with_odd_widths(octo, dtype):
             for t in det.outputs:
                 assert rel_err(P.get_tensor(0, t, 3), ref[t]) <= TOL[dtype], t
         P.close()
+
+
+def test_detector_batch_smaller_than_the_frame_batch(octo):
+    """The detector at its own batch size (executions of 4, then 2 frames of a 6-frame batch; and one frame at a
+    time) with the children still on the ROIs of the whole batch: every result equals the one-execution run and the
+    oracle (planted heads: integer work exact, detector heads of the last execution and child tensors within tolerance)."""
+    dtype, n = "f16", 6
+    spec = zoo.traffic_cascade(dtype, det_batch=n, max_rois_per_frame=24)
+    det, cls, plate = spec.models
+    rng = np.random.default_rng(zoo.SEED0 + 9)
+    counts = np.minimum(synth.counts_poisson(rng, n, 8, 64), 12)
+    counts[2] = 0
+    scene = synth.make_scene(rng, n, 1080, 1920, counts, 24, 360, log_uniform=True)
+    planted = synth.planted_heads(rng, det, scene, 1080, 1920)
+    ref = cascade.run_cascade(spec, scene.frames, planted_heads=planted)
+    P = octo.Pipeline(spec)
+    d_heads = [octo.to_device(h, dtype) for h in planted]
+    for l, h in enumerate(d_heads):
+        P.set_head(0, l, h)
+    runs = {}
+    for b in (0, 4, 1):
+        P.set_detector_batch(b)
+        P.submit(_frames_dev(scene.frames))
+        assert P.run() == n
+        frames, boxes, st = P.collect()
+        assert st == octo.OK
+        rois = [P.get_rois(e) for e in (0, 1)]
+        dets = [P.get_detections(0, f) for f in range(n)]
+        n_roi = len(rois[0])
+        logits = P.get_tensor(1, cls.outputs[0], n_roi).reshape(n_roi, -1)
+        last = n - 1 - ((n - 1) % b) if b else 0                       # first frame of the last execution
+        head_last = [P.get_tensor(0, t, n - last) for t in det.outputs]
+        runs[b] = (frames, boxes, rois, dets, logits, head_last, last)
+    with pytest.raises(octo.OctoError):
+        P.set_detector_batch(n + 1)
+    P.close()
+    f0, b0, r0, d0, l0, _, _ = runs[0]
+    assert f0["n_boxes"].tolist() == [len(d.keep) for d in ref.dets] and f0["n_boxes"][2] == 0
+    for f, d in enumerate(ref.dets):
+        cc, top, keep = d0[f]
+        assert cc == d.cand_count and top["idx"].tolist() == d.top.idx.tolist() and keep.tolist() == d.keep.tolist()
+    assert rel_err(l0, ref.children[0].logits) <= TOL[dtype]
+    for b in (4, 1):
+        fb, bb, rb, db, lb, hb, last = runs[b]
+        for k in ("frame_id", "n_boxes", "flags", "box_offset", "slo_met"):
+            assert fb[k].tolist() == f0[k].tolist(), (b, k)
+        assert bb.tobytes() == b0.tobytes(), b
+        for e in (0, 1):
+            assert rb[e].tobytes() == r0[e].tobytes(), (b, e)
+        for f in range(n):
+            assert db[f][0] == d0[f][0] and db[f][1].tobytes() == d0[f][1].tobytes() and db[f][2].tolist() == d0[f][2].tolist(), (b, f)
+        assert rel_err(lb, l0) <= 1e-6                                  # same crops, same kernels
+        for l, t in enumerate(det.outputs):                           # the activation buffers hold the last execution
+            assert rel_err(hb[l], ref.heads[l][last:]) <= TOL[dtype], (b, l)
