@@ -216,6 +216,64 @@ def test_hires_cascade_planted_heavy_tail(octo):
     P.close()
 
 
+def test_surveillance_cascade_planted_bottleneck_child(octo):
+    """The people-surveillance pipeline of the co-location workload at its real shapes (bf16): three planted 1080p
+    frames, s-shaped detector at 640, every ROI stretched to 256 x 128 and classified by the ResNet-50-shaped attribute
+    model with 32 outputs.  Detector heads, all integer work and the ROI table against the oracle on every frame; the
+    child on the first ROIs (oracle time): crops, every tensor of the network, logits, labels with a clear margin."""
+    from oracle import nn
+    dtype, n_frames, m = "bf16", 3, 8
+    spec = zoo.surveillance_cascade(dtype, det_batch=n_frames, max_rois_per_frame=24)
+    det, attr = spec.models
+    assert (attr.in_h, attr.in_w) == (256, 128) and attr.layers[-1].cout == 32
+    rng = np.random.default_rng(zoo.SEED0 + 4)
+    counts = np.minimum(synth.counts_poisson(rng, n_frames, 8, 64), 12)
+    scene = synth.make_scene(rng, n_frames, 1080, 1920, counts, 24, 360, log_uniform=True)
+    planted = synth.planted_heads(rng, det, scene, 1080, 1920)
+    ref = cascade.run_cascade(spec, scene.frames, planted_heads=planted, max_child_rois=m)
+    P = octo.Pipeline(spec, keep_all_tensors=True)
+    d_heads = [octo.to_device(h, dtype) for h in planted]
+    for l, h in enumerate(d_heads):
+        P.set_head(0, l, h)
+    P.submit(_frames_dev(scene.frames))
+    assert P.run() == n_frames
+    frames, boxes, st = P.collect()
+    assert st == octo.OK
+    for l, t in enumerate(det.outputs):
+        assert rel_err(P.get_tensor(0, t, n_frames), ref.heads[l]) <= TOL[dtype], l
+    for f, d in enumerate(ref.dets):
+        cc, top, keep = P.get_detections(0, f)
+        assert cc == d.cand_count and top["idx"].tolist() == d.top.idx.tolist() and keep.tolist() == d.keep.tolist()
+    assert frames["n_boxes"].tolist() == [len(d.keep) for d in ref.dets]
+    rois, r = P.get_rois(0), ref.children[0].rois
+    n_roi = len(r)
+    assert n_roi >= m and rois["frame"].tolist() == r.frame.tolist() and rois["rank"].tolist() == r.rank.tolist()
+    assert rois["cls"].tolist() == r.cls.tolist()
+    assert np.abs(np.stack([rois["x1"], rois["y1"], rois["x2"], rois["y2"]], 1) - r.box).max() < 1e-2
+    off = 0
+    for f, d in enumerate(ref.dets):
+        b = boxes[off:off + len(d.keep)]
+        assert np.abs(np.stack([b["x1"], b["y1"], b["x2"], b["y2"]], 1) - d.box_src).max() < 1e-2
+        assert b["cls"].tolist() == d.top.cls[d.keep].tolist()
+        off += len(d.keep)
+    # the child on the first m ROIs: every tensor
+    assert rel_err(P.get_tensor(1, 0, m), ref.children[0].crops) <= 8e-3
+    ts = nn.run_model(attr, ref.children[0].crops, keep_all=True)
+    shapes = attr.tensor_shapes()
+    assert max(s[2] for s in shapes) == 2048
+    for t in range(1, len(attr.layers) + 1):
+        got = P.get_tensor(1, t, m)
+        assert rel_err(got.reshape(ts[t].shape), ts[t]) <= TOL[dtype], (t, attr.layers[t - 1].op, attr.layers[t - 1].cout)
+    logits = P.get_tensor(1, attr.outputs[0], n_roi).reshape(n_roi, -1)
+    assert logits.shape[1] == 32 and rel_err(logits[:m], ref.children[0].logits) <= TOL[dtype]
+    lab = P.get_labels(0)
+    srt = np.sort(ref.children[0].logits, axis=1)
+    clear = (srt[:, -1] - srt[:, -2]) > 4 * TOL[dtype] * max(1.0, np.abs(ref.children[0].logits).max())
+    assert np.array_equal(lab[:m][clear], ref.children[0].labels[clear])
+    assert np.array_equal(lab, logits.argmax(axis=1)) and np.array_equal(boxes["child_label"][:, 0], lab)
+    P.close()
+
+
 @pytest.mark.parametrize("bz", [1, 4])
 def test_sweep_cascade_bursty_counts(octo, bz):
     """Batch-size sweep workload (bf16, negative-binomial object counts, cap 200): post-processing and ROI routing are

@@ -214,6 +214,25 @@ def test_3x3_64_channel_layers_on_wide_maps(octo, dtype):
         assert rel_err(got[t], ref[t]) <= TOL[dtype], t
 
 
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_every_tensor_of_a_bottleneck_residual_classifier(octo, dtype):
+    """ResNet-50-shaped blocks (1x1 -> 3x3 stride s -> 1x1 with 4x expansion up to 2048 channels, 1x1 stride-s projection
+    shortcuts, residual added before the ReLU) on a 64 x 32 input: every tensor against the oracle."""
+    n = 5
+    m = zoo.residual_classifier("r50ish", dtype, 64, 32, "bottleneck", (2, 1, 2, 1), 32, seed=5, batch_size=n)
+    x = zoo.round_to_dtype(np.random.default_rng(21).uniform(0, 1, (n, 64, 32, 3)).astype(np.float32), dtype)
+    spec = zoo.PipelineSpec("t", [small_root(dtype), m], [], 200.0, 32, 32, 1, 1)
+    P = octo.Pipeline(spec, keep_all_tensors=True)
+    P.run_model_on(1, octo.to_device(x, dtype))
+    got = [P.get_tensor(1, t, n) for t in range(len(m.layers) + 1)]
+    P.close()
+    ref = nn.run_model(m, x, keep_all=True)
+    shapes = m.tensor_shapes()
+    assert max(s[2] for s in shapes) == 2048 and any(L.op == "conv" and L.kh == 1 and L.stride == 2 for L in m.layers)
+    for t in range(1, len(m.layers) + 1):
+        assert rel_err(got[t].reshape(ref[t].shape), ref[t]) <= TOL[dtype], (t, m.layers[t - 1].op, m.layers[t - 1].cout)
+
+
 def test_memory_reuse_keeps_outputs_intact(octo):
     # same graph with and without per-tensor buffers must give the same logits
     m = zoo.residual_classifier("r", "f16", 64, 64, "basic", (1, 1, 1, 1), 10, seed=3, batch_size=4)
