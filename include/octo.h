@@ -281,6 +281,16 @@ octo_status octo_op_topk(const octo_cand* d_in, const int32_t* d_in_count, int32
 octo_status octo_op_nms(const octo_cand* d_top, const int32_t* d_top_count, int32_t k_cap, int32_t n, float iou_thr, int32_t max_det,
                         void* d_mask_scratch, int32_t* d_keep, int32_t* d_n_keep, void* hip_stream);
 size_t octo_op_nms_scratch_bytes(int32_t n, int32_t k_cap);
+/* octo_op_nms for callers that cannot allocate device memory (code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc): same arguments, results and kernels, but the suppression mask lives in a static
+ * device array inside the library (OCTO_NMS_STATIC_BYTES per GPU, held until the process ends) and the call itself
+ * allocates nothing.  OCTO_ECAP, with nothing launched, if octo_op_nms_scratch_bytes(n, k_cap) exceeds
+ * OCTO_NMS_STATIC_BYTES (e.g. 64 items at k_cap 1024 fit exactly).  All calls on one GPU share the array: calls
+ * that overlap on one GPU (different streams, or different threads) race; calls on one stream are ordered.  The
+ * array keeps the previous call's contents; none of them is read (each call writes every mask word it reads). */
+#define OCTO_NMS_STATIC_BYTES (8u << 20)
+octo_status octo_op_nms_static(const octo_cand* d_top, const int32_t* d_top_count, int32_t k_cap, int32_t n, float iou_thr, int32_t max_det,
+                               int32_t* d_keep, int32_t* d_n_keep, void* hip_stream);
 /* ROI compaction for one edge: kept boxes with class bit set, in (item, rank) order, converted to source pixels
  * (letterbox undone for a src_h x src_w frame letterboxed into in_h x in_w) and clamped.
  * d_n_rois[0] = count (clamped to cap); d_roi_of [n][max_det] = ROI id of each kept box or -1; d_item_counts [n] is

@@ -87,7 +87,7 @@ EXPORTS = [
     "octo_est_throughput", "octo_run_model", "octo_profile_layers", "octo_set_layer_timing", "octo_get_layer_info", "octo_set_stage_timing", "octo_get_stage_ms",
     "octo_debug_get_tensor", "octo_debug_tensor_shape", "octo_debug_set_head", "octo_debug_run_model",
     "octo_debug_get_detections", "octo_debug_get_rois", "octo_debug_get_labels", "octo_op_letterbox",
-    "octo_op_crop_resize", "octo_op_decode", "octo_op_topk", "octo_op_nms", "octo_op_nms_scratch_bytes", "octo_op_compact",
+    "octo_op_crop_resize", "octo_op_decode", "octo_op_topk", "octo_op_nms", "octo_op_nms_scratch_bytes", "octo_op_nms_static", "octo_op_compact",
 ]
 
 _lib = None
@@ -142,6 +142,7 @@ def lib() -> C.CDLL:
         L.octo_op_topk.argtypes = [vp, vp, i32, i32, i32, vp, vp, i32, vp]
         L.octo_op_nms.argtypes = [vp, vp, i32, i32, f32, i32, vp, vp, vp, vp]
         L.octo_op_nms_scratch_bytes.argtypes = [i32, i32]
+        L.octo_op_nms_static.argtypes = [vp, vp, i32, i32, f32, i32, vp, vp, vp]
         L.octo_op_compact.argtypes = [vp, i32, vp, vp, i32, i32, i32, i32, i32, i32, vp, vp, vp, i32, vp, vp, vp, vp, vp]
         _lib = L
     return _lib
@@ -484,6 +485,16 @@ def op_nms(top, top_count, iou_thr: float, max_det: int, stream=None):
     _st(lib().octo_op_nms(top.data_ptr(), top_count.data_ptr(), k_cap, n, iou_thr, max_det, scratch.data_ptr(),
                           keep.data_ptr(), nk.data_ptr(), _stream_ptr(stream)))
     return keep, nk
+
+
+NMS_STATIC_BYTES = 8 << 20
+
+
+def op_nms_static(top, top_count, iou_thr: float, max_det: int, keep, n_keep, stream=None) -> int:
+    """octo_op_nms_static on caller-made output tensors (the call itself allocates nothing); returns the status."""
+    n, k_cap = int(top.shape[0]), int(top.shape[1])
+    return int(lib().octo_op_nms_static(top.data_ptr(), top_count.data_ptr(), k_cap, n, iou_thr, max_det,
+                                        keep.data_ptr(), n_keep.data_ptr(), _stream_ptr(stream)))
 
 
 def op_compact(top, keep, n_keep, src_hw, in_hw, class_mask: int, cap: int, stream=None):

@@ -1,14 +1,37 @@
 // Stage-level C ABI entry points: argument checks and one launch each of the
 // kernels the pipeline itself uses, on caller-owned device buffers.
 #include <cstring>
+#include <mutex>
 
 #include "octo_internal.h"
 
 using namespace octo;
 
+// Suppression-mask memory of octo_op_nms_static: one copy per GPU, held until the process ends.  In host code this
+// name is only a handle for hipGetSymbolAddress; the kernels get the device address that call returns.
+static __device__ __align__(256) unsigned char scratch[OCTO_NMS_STATIC_BYTES];
+
 namespace {
 octo_status from_hip(hipError_t e) { return e == hipSuccess ? OCTO_OK : (e == hipErrorInvalidValue ? OCTO_EINVAL : OCTO_EHIP); }
 bool valid_dtype(int dt) { return dt == OCTO_F32 || dt == OCTO_F16 || dt == OCTO_BF16; }
+
+constexpr int MAX_DEVICES = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_addr[MAX_DEVICES] = {};   // device address of `scratch` on each GPU, looked up on first use there
+
+// Device address of the static scratch array on the current device.
+octo_status static_scratch(void** out) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= MAX_DEVICES) return OCTO_EHIP;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_addr[dev]) {
+    void* p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return OCTO_EHIP;
+    g_scratch_addr[dev] = p;
+  }
+  *out = g_scratch_addr[dev];
+  return OCTO_OK;
+}
 }  // namespace
 
 extern "C" {
@@ -78,6 +101,20 @@ octo_status octo_op_nms(const octo_cand* d_top, const int32_t* d_top_count, int3
       !(iou_thr >= 0))
     return OCTO_EINVAL;
   NmsArgs a{d_top, d_top_count, k_cap, iou_thr, max_det, (unsigned long long*)d_mask_scratch, d_keep, d_n_keep, n, nullptr};
+  return from_hip(launch_nms(a, (hipStream_t)hip_stream));
+}
+
+octo_status octo_op_nms_static(const octo_cand* d_top, const int32_t* d_top_count, int32_t k_cap, int32_t n, float iou_thr, int32_t max_det,
+                               int32_t* d_keep, int32_t* d_n_keep, void* hip_stream) {
+  if (!d_top || !d_top_count || !d_keep || !d_n_keep || n < 0 || max_det < 1 || k_cap < 64 || k_cap % 64 || k_cap > 4096 || !(iou_thr >= 0))
+    return OCTO_EINVAL;
+  if (n == 0) return OCTO_OK;
+  if (nms_mask_bytes(n, k_cap) > (size_t)OCTO_NMS_STATIC_BYTES) return OCTO_ECAP;
+  void* mask = nullptr;
+  const octo_status st = static_scratch(&mask);
+  if (st != OCTO_OK) return st;
+  // every mask word the reduction reads is written by the mask kernel of the same call, so nothing is cleared
+  NmsArgs a{d_top, d_top_count, k_cap, iou_thr, max_det, (unsigned long long*)mask, d_keep, d_n_keep, n, nullptr};
   return from_hip(launch_nms(a, (hipStream_t)hip_stream));
 }
 
