@@ -2,10 +2,11 @@
 """Benchmark of the cascade hot path on one MI355X.
 
 A step is one pass of the whole path (letterbox, detector, decode, top-k, NMS, ROI compaction, crop-resize,
-classifier and plate detector, result copy) over one batch of the traffic workload: 8 synthetic 1920x1080 frames
-from 4 cameras, fp16, planted detector heads (Poisson(8) objects per frame).  Several copies of the pipeline
-(instances, as the paper's model instances) take batches in turn on their own streams, so kernels of different
-batches overlap.  Prints one JSON line.
+classifier, result copy) over one batch of the high-resolution workload, the largest single-GPU configuration: 32
+synthetic 3840x2160 frames, m-shaped detector at 1280 x 1280 in bf16, planted detector heads (Pareto object counts,
+top-k truncating), every ROI through the ResNet-18-shaped classifier.  The traffic workload (8 frames of 1920x1080,
+fp16, four pipeline instances on their own streams) runs in the same process and is reported under the key
+"traffic".  Prints one JSON line.
 """
 from __future__ import annotations
 
@@ -83,14 +84,28 @@ TRAFFIC = {
 }
 
 
-def traffic_per_launch(kernel_name: str):
+TRAFFIC_SOURCE = "profiles/*_hbm_counters.md: rocprofv3 --pmc FETCH_SIZE and --pmc WRITE_SIZE runs of this command, scaled by the " \
+                 "same counters on a copy of known size; looked up by the hash of the convolution sources they were taken with"
+
+
+def conv_sources_key() -> str:
     import hashlib
-    src = os.path.join(ROOT, "paper_2502_01277_amd", "csrc", "conv.hip")
-    try:
-        key = hashlib.sha256(open(src, "rb").read()).hexdigest()[:16]
-    except OSError:
-        return None
-    return TRAFFIC.get(key, {}).get(kernel_name)
+    h = hashlib.sha256()
+    for f in ("conv.hip", "convbig.hip", "conv3x3.hip", "stem.hip", "mfma_common.h"):
+        try:
+            h.update(open(os.path.join(ROOT, "paper_2502_01277_amd", "csrc", f), "rb").read())
+        except OSError:
+            pass
+    return h.hexdigest()[:16]
+
+
+def traffic_per_launch(kernel_name: str):
+    """(HBM bytes per launch from the committed counter runs, where they come from), or (None, why not): the figure is
+    only valid for the kernel sources it was measured with."""
+    got = TRAFFIC.get(conv_sources_key(), {}).get(kernel_name)
+    if got is None:
+        return None, "no counter run for the current convolution sources (key %s); see profiles/ for the last one" % conv_sources_key()
+    return got, TRAFFIC_SOURCE
 
 
 def cpu_baseline(spec, scene, heads, min_seconds=10.0, max_batches=8, subset=False, rois_per_frame=None):
@@ -290,18 +305,204 @@ def run_surge(args):
         P.close()
 
 
+def hbm_rooflines(spec, scene, pipe, stage, names, n, measured_copy):
+    """Achieved HBM GB/s of the three large pre/post-processing kernels, from their algorithmic bytes (what the step must
+    move whatever the kernel: unique source pixels tapped + output elements for letterbox, every head element + one
+    record per candidate for decode, min(4 taps per output pixel, the box's own pixels) + output elements per ROI for
+    crop-resize) and the event-timed duration of their stage on the pipeline's stream."""
+    from paper_2502_01277_amd import binding
+    det = spec.models[0]
+    es = 4 if det.dtype == "f32" else 2
+    st = dict(zip(names, stage))
+    out = []
+    # letterbox (K1): the resized image is nw x nh inside the det.in_h x det.in_w canvas
+    r = min(det.in_h / spec.src_h, det.in_w / spec.src_w)
+    nw, nh = int(spec.src_w * r + 0.5), int(spec.src_h * r + 0.5)
+    kx = spec.src_w / nw
+    taps = 1 if (spec.src_w % nw == 0 and spec.src_h % nh == 0 and int(kx) % 2 == 1) else 4     # odd integer ratio: taps fall on pixel centres
+    usrc = min(nw * nh * taps, spec.src_w * spec.src_h)
+    out.append(("letterbox_kernel", "letterbox", n * (3 * usrc + det.in_h * det.in_w * 3 * es)))
+    # decode (K5)
+    cands = sum(int(pipe.get_detections(0, f)[0]) for f in range(n))
+    out.append(("decode_stream_kernel", "decode", n * det.n_cand() * (5 + det.n_classes) * es + 32 * cands))
+    # crop-resize (K9), first edge
+    if spec.edges:
+        child = spec.models[spec.edges[0].child]
+        ces = 4 if child.dtype == "f32" else 2
+        rois = pipe.get_rois(0)
+        w = np.maximum(rois["x2"] - rois["x1"], 1.0); h = np.maximum(rois["y2"] - rois["y1"], 1.0)
+        src = np.minimum(4.0 * child.in_h * child.in_w, np.ceil(w) * np.ceil(h)) * 3
+        out.append(("crop_resize_rows_kernel", "crop0", float(src.sum()) + len(rois) * child.in_h * child.in_w * 3 * ces))
+    res = []
+    for kernel, key, nbytes in out:
+        us = 1e3 * float(st[key])
+        gbps = nbytes / (us * 1e-6) / 1e9 if us > 0 else 0.0
+        res.append({"kernel": kernel, "stage": key, "bound": "hbm", "algorithmic_bytes": float(nbytes), "stage_us": us, "achieved": gbps,
+                    "peak": HBM_PEAK, "unit": "GB/s", "frac": gbps / HBM_PEAK,
+                    "frac_of_measured": gbps / measured_copy if measured_copy else None})
+    return res
+
+
+def bench_cascade(args, workload, steps, warmup, ninst, measured, with_cpu):
+    """One workload: `warmup` untimed and `steps` timed batches of the whole cascade, then the same steps with timing
+    events for the per-kernel figures.  Returns the JSON object of the run."""
+    import torch
+    from paper_2502_01277_amd import binding
+    spec, scene, heads, desc = make_workload(workload)
+    det = spec.models[0]
+    n = scene.frames.shape[0]
+    pipes, keep_heads = [], []
+    for _ in range(ninst):
+        P = binding.Pipeline(spec)
+        if heads is not None:
+            dh = [binding.to_device(h, det.dtype) for h in heads]
+            for l, h in enumerate(dh):
+                P.set_head(0, l, h)
+            keep_heads.append(dh)
+        pipes.append(P)
+    dev = [torch.from_numpy(f).cuda() for f in scene.frames]
+    # one stream per instance, created by the library over all compute units: each gets a hardware queue of its own
+    # (streams from a framework's pool may share one, which serialises the instances that land on it)
+    n_cu = binding.device_cu_count()
+    streams = [binding.stream_create_range(0, n_cu) for _ in range(ninst)]
+    now = binding.lib().octo_now_ms
+
+    def region(k_steps, on_collect, use=None):
+        """`k_steps` batches, taken in turn by the instances in `use`; each instance keeps at most two uncollected
+        batches, so the host prepares and collects while the GPU works."""
+        use = list(range(ninst)) if use is None else use
+        pend = {j: 0 for j in use}
+        for k in range(k_steps):
+            j = use[k % len(use)]
+            if pend[j] >= 2:
+                fr, bx, st = pipes[j].collect()
+                pend[j] -= len(fr) // n
+                on_collect(j, fr)
+            pipes[j].submit(dev, arrival_ms=[now()] * n)
+            pipes[j].run(streams[j])
+            pend[j] += 1
+        for j in use:
+            while pend[j] > 0:
+                fr, bx, st = pipes[j].collect()
+                pend[j] -= len(fr) // n
+                on_collect(j, fr)
+
+    region(warmup, lambda j, fr: None)
+    if args.calib_copy_mib and workload == args.workload:
+        src = torch.full((args.calib_copy_mib << 18,), 1.0, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        torch.add(src, 1.0, out=dst)           # one elementwise kernel: reads and writes calib_copy_mib MiB each
+        torch.cuda.synchronize()
+        del src, dst
+    # ---- timed region: K steps, inputs resident in HBM ----
+    lat, tot = [], {"met": 0, "boxes": 0, "frames": 0}
+
+    def tally(j, fr):
+        lat.extend(fr["latency_ms"].tolist())
+        tot["met"] += int(fr["slo_met"].sum()); tot["boxes"] += int(fr["n_boxes"].sum()); tot["frames"] += len(fr)
+
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    region(steps, tally)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    assert tot["frames"] == n * steps
+    # ---- the same steps again with timing events on every layer: once with one instance alone (a kernel's own
+    # duration, which is what a profiler that serialises dispatches reports) and once with all instances overlapping
+    items = [n] + [0] * (len(spec.models) - 1)          # items each model processes per step (same batch every step)
+    for e, edge in enumerate(spec.edges):
+        items[edge.child] = len(pipes[0].get_rois(e))
+
+    def timing_pass(k_steps, use):
+        agg, stage = {}, []      # kernel id -> [time ms, flops, bytes, launches]
+
+        def per_layer(j, fr):
+            stage.append(pipes[j].stage_ms())            # timings of the newest batch of this collect
+            for mi, m in enumerate(spec.models):
+                ms, kid, fl, by, wb = pipes[j].layer_info(mi)
+                for q in range(len(ms)):
+                    if kid[q] == 0:
+                        continue
+                    a = agg.setdefault(int(kid[q]), [0.0, 0.0, 0.0, 0])
+                    a[0] += float(ms[q]); a[1] += fl[q] * items[mi]; a[2] += by[q] * items[mi] + wb[q]; a[3] += 1
+
+        for P in pipes:
+            P.set_layer_timing(True); P.set_stage_timing(True)
+        region(k_steps, per_layer, use)
+        for P in pipes:
+            P.set_layer_timing(False); P.set_stage_timing(False)
+        return agg, np.mean(np.stack(stage), axis=0), len(stage)
+
+    agg, stage, nsamp = timing_pass(max(4, min(steps, 60)), [0])
+    agg_ov, stage_ov, nsamp_ov = timing_pass(min(steps, 120), None) if ninst > 1 else (agg, stage, nsamp)
+    conv = {k: v for k, v in agg.items() if k >= 1000000000}
+    dom = max(conv, key=lambda k: conv[k][0])
+    t_ms, fl, by, launches = conv[dom]
+    kname = conv_name(dom, det.dtype)
+    achieved = fl / (t_ms * 1e-3) / 1e12
+    traffic, traffic_source = traffic_per_launch(kname)
+    roofline = {"bound": "mfma", "kernel": kname, "achieved": achieved, "peak": PEAK[det.dtype], "unit": "TFLOP/s",
+                "frac": achieved / PEAK[det.dtype], "traffic": traffic, "traffic_source": traffic_source,
+                "frac_of_measured": achieved / measured["mfma_tflops"] if measured.get("mfma_tflops") else None,
+                "avg_launch_us": 1e3 * t_ms / launches, "launches_per_step": launches / nsamp,
+                "avg_launch_us_overlapped": 1e3 * agg_ov[dom][0] / agg_ov[dom][3],
+                "flop_per_launch": fl / launches, "bytes_per_launch": by / launches,
+                "share_of_conv_time": t_ms / sum(v[0] for v in conv.values()),
+                "all_conv_tflops_per_kernel": sum(v[1] for v in conv.values()) / (sum(v[0] for v in conv.values()) * 1e-3) / 1e12,
+                "conv_flop_per_step": sum(v[1] for v in conv.values()) / nsamp,
+                "conv_tflops_whole_step": sum(v[1] for v in conv.values()) / nsamp / (dt / steps) / 1e12}
+    names = ["letterbox", "detector_layers", "decode", "topk", "nms", "compact"]
+    for e in range(len(spec.edges)):
+        names += ["crop%d" % e, "child%d_layers" % e, "child%d_tail" % e]
+    out = {
+        "metric": "pipeline frames/s within 200 ms SLO on 1 GPU", "value": tot["met"] / dt, "unit": "frames/s",
+        "n_gpus": 1, "steps": steps, "warmup": warmup, "ms_per_step": 1e3 * dt / steps,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": det.dtype, "data": "synthetic",
+        "config": {"workload": desc, "batch_frames": n, "slo_ms": spec.slo_ms, "instances": ninst,
+                   "heads": "planted" if heads is not None else "natural"},
+        "total_frames_per_s": n * steps / dt, "objects_per_s": tot["boxes"] / dt,
+        "latency_ms_p50": float(np.percentile(lat, 50)), "latency_ms_p99": float(np.percentile(lat, 99)),
+        "stage_ms": {k: round(float(v), 4) for k, v in zip(names, stage)},
+        "stage_ms_overlapped": {k: round(float(v), 4) for k, v in zip(names, stage_ov)},
+        "roofline": roofline,
+        "roofline_hbm": hbm_rooflines(spec, scene, pipes[0], stage, names, n, measured.get("copy_gbps")),
+        "conv_kernels": [{"kernel": conv_name(k, det.dtype), "ms_per_step": v[0] / nsamp, "tflops": v[1] / max(v[0], 1e-9) / 1e9,
+                          "launches_per_step": v[3] / nsamp} for k, v in sorted(conv.items(), key=lambda kv: -kv[1][0])],
+    }
+    if args.layers:
+        for k, v in sorted(agg.items()):
+            nm = conv_name(k, det.dtype) if k >= 1000000000 else {1: "maxpool", 2: "upsample2x", 3: "copy", 4: "add", 5: "gap"}.get(k, str(k))
+            print("%-80s %8.3f ms/step  %7.1f TFLOP/s  %7.1f GB/s  %5.1f launches/step  %7.1f us/launch" %
+                  (nm, v[0] / nsamp, v[1] / max(v[0], 1e-9) / 1e9, v[2] / max(v[0], 1e-9) / 1e6, v[3] / nsamp, 1e3 * v[0] / max(v[3], 1)), file=sys.stderr)
+    if with_cpu:
+        out["cpu_baseline"], _ = cpu_baseline(spec, scene, heads, subset=workload == "hires",
+                                              rois_per_frame=float(np.mean(items[1:])) / n if len(items) > 1 else 0.0)
+    torch.cuda.synchronize()
+    for P in pipes:
+        P.close()
+    for st in streams:
+        binding.stream_destroy(st)
+    del pipes, keep_heads, dev
+    torch.cuda.empty_cache()
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=None, help="timed batches (default: 4000 for the traffic workload, about 3.5 s; 200 for "
-                    "the high-resolution one, about 8 s; 400 otherwise)")
+    ap.add_argument("--steps", type=int, default=None, help="timed batches (default: 200 for the high-resolution workload, about 7 s; 4000 for "
+                    "the traffic one; 400 otherwise)")
     ap.add_argument("--warmup", type=int, default=None, help="untimed batches before them (default: steps / 20)")
-    ap.add_argument("--workload", default="traffic")
+    ap.add_argument("--workload", default="hires", help="hires (default: 32 x 3840x2160 frames, the largest configuration), traffic, tiny, "
+                    "sweep, colocate, surge")
     ap.add_argument("--instances", type=int, default=None,
                     help="copies of the pipeline (own activations and tables) that take batches in turn, each on its own "
                          "stream, so that kernels of different batches overlap on the GPU (default: 4 for the traffic and "
                          "sweep workloads, 1 for the high-resolution one, whose batches fill the GPU by themselves)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-traffic", action="store_true", help="high-resolution workload: do not also run the traffic workload for the extra key")
+    ap.add_argument("--traffic-steps", type=int, default=400, help="timed batches of the traffic workload run beside the high-resolution one")
     ap.add_argument("--layers", action="store_true", help="print the per-kernel table to stderr")
     ap.add_argument("--calib-copy-mib", type=int, default=0,
                     help="also run one plain device pass over this many MiB before the timed region (a known-size kernel "
@@ -332,135 +533,18 @@ def main():
         return run_colocate(args)
     if args.workload == "surge":
         return run_surge(args)
-    spec, scene, heads, desc = make_workload(args.workload)
-    det = spec.models[0]
-    n = scene.frames.shape[0]
-    ninst = max(1, args.instances)
-    pipes, keep_heads = [], []
-    for _ in range(ninst):
-        P = binding.Pipeline(spec)
-        if heads is not None:
-            dh = [binding.to_device(h, det.dtype) for h in heads]
-            for l, h in enumerate(dh):
-                P.set_head(0, l, h)
-            keep_heads.append(dh)
-        pipes.append(P)
-    dev = [torch.from_numpy(f).cuda() for f in scene.frames]
-    # one stream per instance, created by the library over all compute units: each gets a hardware queue of its own
-    # (streams from a framework's pool may share one, which serialises the instances that land on it)
-    n_cu = binding.device_cu_count()
-    streams = [binding.stream_create_range(0, n_cu) for _ in range(ninst)]
-    now = binding.lib().octo_now_ms
-
-    def region(steps, on_collect, use=None):
-        """`steps` batches, taken in turn by the instances in `use`; each instance keeps at most two uncollected
-        batches, so the host prepares and collects while the GPU works."""
-        use = list(range(ninst)) if use is None else use
-        pend = {j: 0 for j in use}
-        for k in range(steps):
-            j = use[k % len(use)]
-            if pend[j] >= 2:
-                fr, bx, st = pipes[j].collect()
-                pend[j] -= len(fr) // n
-                on_collect(j, fr)
-            pipes[j].submit(dev, arrival_ms=[now()] * n)
-            pipes[j].run(streams[j])
-            pend[j] += 1
-        for j in use:
-            while pend[j] > 0:
-                fr, bx, st = pipes[j].collect()
-                pend[j] -= len(fr) // n
-                on_collect(j, fr)
-
-    region(args.warmup, lambda j, fr: None)
-    if args.calib_copy_mib:
-        src = torch.full((args.calib_copy_mib << 18,), 1.0, dtype=torch.float32, device="cuda")
-        dst = torch.empty_like(src)
-        torch.cuda.synchronize()
-        torch.add(src, 1.0, out=dst)           # one elementwise kernel: reads and writes calib_copy_mib MiB each
-        torch.cuda.synchronize()
-        del src, dst
-    # ---- timed region: K steps, inputs resident in HBM ----
-    lat, tot = [], {"met": 0, "boxes": 0, "frames": 0}
-
-    def tally(j, fr):
-        lat.extend(fr["latency_ms"].tolist())
-        tot["met"] += int(fr["slo_met"].sum()); tot["boxes"] += int(fr["n_boxes"].sum()); tot["frames"] += len(fr)
-
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    region(args.steps, tally)
-    torch.cuda.synchronize()
-    dt = time.perf_counter() - t0
-    assert tot["frames"] == n * args.steps
-    # ---- the same steps again with timing events on every layer: once with one instance alone (a kernel's own
-    # duration, which is what a profiler that serialises dispatches reports) and once with all instances overlapping
-    items = [n] + [0] * (len(spec.models) - 1)          # items each model processes per step (same batch every step)
-    for e, edge in enumerate(spec.edges):
-        items[edge.child] = len(pipes[0].get_rois(e))
-
-    def timing_pass(steps, use):
-        agg, stage = {}, []      # kernel id -> [time ms, flops, bytes, launches]
-
-        def per_layer(j, fr):
-            stage.append(pipes[j].stage_ms())            # timings of the newest batch of this collect
-            for mi, m in enumerate(spec.models):
-                ms, kid, fl, by, wb = pipes[j].layer_info(mi)
-                for q in range(len(ms)):
-                    if kid[q] == 0:
-                        continue
-                    a = agg.setdefault(int(kid[q]), [0.0, 0.0, 0.0, 0])
-                    a[0] += float(ms[q]); a[1] += fl[q] * items[mi]; a[2] += by[q] * items[mi] + wb[q]; a[3] += 1
-
-        for P in pipes:
-            P.set_layer_timing(True); P.set_stage_timing(True)
-        region(steps, per_layer, use)
-        for P in pipes:
-            P.set_layer_timing(False); P.set_stage_timing(False)
-        return agg, np.mean(np.stack(stage), axis=0), len(stage)
-
-    agg, stage, nsamp = timing_pass(min(args.steps, 60), [0])
-    agg_ov, stage_ov, nsamp_ov = timing_pass(min(args.steps, 120), None) if ninst > 1 else (agg, stage, nsamp)
-    conv = {k: v for k, v in agg.items() if k >= 1000000000}
-    dom = max(conv, key=lambda k: conv[k][0])
-    t_ms, fl, by, launches = conv[dom]
-    kname = conv_name(dom, det.dtype)
-    roofline = {"bound": "mfma", "kernel": kname, "achieved": fl / (t_ms * 1e-3) / 1e12, "peak": PEAK[det.dtype], "unit": "TFLOP/s",
-                "frac": fl / (t_ms * 1e-3) / 1e12 / PEAK[det.dtype], "traffic": traffic_per_launch(kname),
-                "avg_launch_us": 1e3 * t_ms / launches, "launches_per_step": launches / nsamp,
-                "avg_launch_us_overlapped": 1e3 * agg_ov[dom][0] / agg_ov[dom][3],
-                "flop_per_launch": fl / launches, "bytes_per_launch": by / launches,
-                "all_conv_tflops_per_kernel": sum(v[1] for v in conv.values()) / (sum(v[0] for v in conv.values()) * 1e-3) / 1e12,
-                "conv_flop_per_step": sum(v[1] for v in conv.values()) / nsamp,
-                "conv_tflops_whole_step": sum(v[1] for v in conv.values()) / nsamp / (dt / args.steps) / 1e12}
-    names = ["letterbox", "detector_layers", "decode", "topk", "nms", "compact"]
-    for e in range(len(spec.edges)):
-        names += ["crop%d" % e, "child%d_layers" % e, "child%d_tail" % e]
-    out = {
-        "metric": "pipeline frames/s within 200 ms SLO on 1 GPU", "value": tot["met"] / dt, "unit": "frames/s",
-        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": 1e3 * dt / args.steps,
-        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": det.dtype, "data": "synthetic",
-        "config": {"workload": desc, "batch_frames": n, "slo_ms": spec.slo_ms, "instances": ninst,
-                   "heads": "planted" if heads is not None else "natural"},
-        "total_frames_per_s": n * args.steps / dt, "objects_per_s": tot["boxes"] / dt,
-        "latency_ms_p50": float(np.percentile(lat, 50)), "latency_ms_p99": float(np.percentile(lat, 99)),
-        "stage_ms": {k: round(float(v), 4) for k, v in zip(names, stage)},
-        "stage_ms_overlapped": {k: round(float(v), 4) for k, v in zip(names, stage_ov)},
-        "roofline": roofline,
-    }
-    if args.layers:
-        for k, v in sorted(agg.items()):
-            nm = conv_name(k, det.dtype) if k >= 1000000000 else {1: "maxpool", 2: "upsample2x", 3: "copy", 4: "add", 5: "gap"}.get(k, str(k))
-            print("%-80s %8.3f ms/step  %7.1f TFLOP/s  %7.1f GB/s  %5.1f launches/step  %7.1f us/launch" %
-                  (nm, v[0] / nsamp, v[1] / max(v[0], 1e-9) / 1e9, v[2] / max(v[0], 1e-9) / 1e6, v[3] / nsamp, 1e3 * v[0] / max(v[3], 1)), file=sys.stderr)
-    if not args.no_cpu_baseline:
-        out["cpu_baseline"], _ = cpu_baseline(spec, scene, heads, subset=args.workload == "hires",
-                                              rois_per_frame=float(np.mean(items[1:])) / n if len(items) > 1 else 0.0)
-    torch.cuda.synchronize()
-    for P in pipes:
-        P.close()
-    for st in streams:
-        binding.stream_destroy(st)
+    # what this machine sustains, measured now: a plain copy and a register-only MFMA loop with random operands
+    measured = {"copy_gbps": binding.probe_copy(512, 5), "mfma_tflops": binding.probe_mfma("bf16", 20000, 3),
+                "note": "library microbenchmarks run before the timed region: 512 MiB device copy (read + write bytes), register-only "
+                        "32x32x16 bf16 MFMA loop with random operand values"}
+    out = bench_cascade(args, args.workload, args.steps, args.warmup, max(1, args.instances), measured, not args.no_cpu_baseline)
+    out["measured_peaks"] = measured
+    if args.workload == "hires" and not args.no_traffic:
+        # the traffic cascade (8 x 1080p, fp16, four instances) in the same run, as an extra key
+        tsteps = max(20, args.traffic_steps)
+        t = bench_cascade(args, "traffic", tsteps, max(8, tsteps // 10), 4, measured, False)
+        out["traffic"] = {k: t[k] for k in ("value", "unit", "steps", "ms_per_step", "dtype", "config", "total_frames_per_s", "objects_per_s",
+                                            "latency_ms_p50", "latency_ms_p99", "stage_ms", "roofline", "roofline_hbm")}
     print(json.dumps(out))
 
 

@@ -236,6 +236,16 @@ octo_status octo_get_layer_info(octo_pipeline* p, int32_t model, float* ms, int3
 octo_status octo_set_stage_timing(octo_pipeline* p, int32_t enable);
 octo_status octo_get_stage_ms(octo_pipeline* p, float* ms, int32_t cap, int32_t* n);
 
+/* Microbenchmarks of the GPU itself, for "fraction of what this machine sustains" beside the datasheet fractions.
+ * octo_probe_copy: a plain 16-byte-per-lane copy of `bytes` from d_src to d_dst (device, 16-byte aligned), `reps`
+ * timed passes after a warm-up; *gb_per_s = (bytes read + bytes written) / median time.
+ * octo_probe_mfma: a register-only loop of the 32x32x16 matrix instruction of `dtype` (OCTO_F16 / OCTO_BF16) with
+ * random operand values, 16 independent accumulators per wavefront, one workgroup of four wavefronts per compute
+ * unit, `iters` x 16 instructions per wavefront; d_scratch (device, at least CUs x 1 KiB) receives checksums;
+ * *tflops = dense FLOP / median time.  Both synchronise `hip_stream`. */
+octo_status octo_probe_copy(const void* d_src, void* d_dst, size_t bytes, int32_t reps, void* hip_stream, double* gb_per_s);
+octo_status octo_probe_mfma(int32_t dtype, float* d_scratch, size_t scratch_bytes, int32_t iters, int32_t reps, void* hip_stream, double* tflops);
+
 /* Copy items [first_item, first_item + n_items) of a tensor of the last run to host as dense NHWC in the tensor's
  * type (fp32 for fc outputs).  tensor_id as in octo_layer.  Synchronises the device. */
 octo_status octo_debug_get_tensor(octo_pipeline* p, int32_t model, int32_t tensor_id, int32_t first_item, int32_t n_items,

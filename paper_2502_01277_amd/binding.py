@@ -87,7 +87,7 @@ EXPORTS = [
     "octo_est_throughput", "octo_run_model", "octo_profile_layers", "octo_set_layer_timing", "octo_get_layer_info", "octo_set_stage_timing", "octo_get_stage_ms",
     "octo_debug_get_tensor", "octo_debug_tensor_shape", "octo_debug_set_head", "octo_debug_run_model",
     "octo_debug_get_detections", "octo_debug_get_rois", "octo_debug_get_labels", "octo_op_letterbox",
-    "octo_op_crop_resize", "octo_op_decode", "octo_op_topk", "octo_op_nms", "octo_op_nms_scratch_bytes", "octo_op_nms_static", "octo_op_compact",
+    "octo_op_crop_resize", "octo_op_decode", "octo_op_topk", "octo_op_nms", "octo_op_nms_scratch_bytes", "octo_op_nms_static", "octo_op_compact", "octo_probe_copy", "octo_probe_mfma",
 ]
 
 _lib = None
@@ -142,6 +142,8 @@ def lib() -> C.CDLL:
         L.octo_op_topk.argtypes = [vp, vp, i32, i32, i32, vp, vp, i32, vp]
         L.octo_op_nms.argtypes = [vp, vp, i32, i32, f32, i32, vp, vp, vp, vp]
         L.octo_op_nms_scratch_bytes.argtypes = [i32, i32]
+        L.octo_probe_copy.argtypes = [vp, vp, C.c_size_t, i32, vp, vp]
+        L.octo_probe_mfma.argtypes = [i32, vp, C.c_size_t, i32, i32, vp, vp]
         L.octo_op_nms_static.argtypes = [vp, vp, i32, i32, f32, i32, vp, vp, vp]
         L.octo_op_compact.argtypes = [vp, i32, vp, vp, i32, i32, i32, i32, i32, i32, vp, vp, vp, i32, vp, vp, vp, vp, vp]
         _lib = L
@@ -518,6 +520,25 @@ def op_compact(top, keep, n_keep, src_hw, in_hw, class_mask: int, cap: int, stre
 
 
 # ---- CU-masked streams --------------------------------------------------------
+def probe_copy(mib: int = 512, reps: int = 5, stream=None) -> float:
+    """GB/s (read + write) of a plain device copy of `mib` MiB, measured by the library's own copy kernel."""
+    t = _torch()
+    src = t.full((mib << 18,), 1.0, dtype=t.float32, device="cuda")
+    dst = t.empty_like(src)
+    out = C.c_double()
+    _st(lib().octo_probe_copy(src.data_ptr(), dst.data_ptr(), src.numel() * 4, reps, _stream_ptr(stream), C.byref(out)))
+    return float(out.value)
+
+
+def probe_mfma(dtype: str = "bf16", iters: int = 20000, reps: int = 3, stream=None) -> float:
+    """TFLOP/s of a register-only MFMA loop with random operand values (what the matrix cores sustain at their real clock)."""
+    t = _torch()
+    scratch = t.empty(1 << 20, dtype=t.float32, device="cuda")
+    out = C.c_double()
+    _st(lib().octo_probe_mfma(DTYPES[dtype], scratch.data_ptr(), scratch.numel() * 4, iters, reps, _stream_ptr(stream), C.byref(out)))
+    return float(out.value)
+
+
 def device_cu_count() -> int:
     n = C.c_int32(0)
     _st(lib().octo_device_cu_count(C.byref(n)))
