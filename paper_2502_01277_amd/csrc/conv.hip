@@ -497,6 +497,12 @@ hipError_t launch_conv(int dtype, const ConvArgs& a0, int num_cu, hipStream_t s,
       if (e3 != hipErrorNotSupported) return e3;
     }
   }
+  // wide 3x3 / stride-1 layers: large tiles with the input patch resident in LDS (the general kernel is paced by its
+  // operand fetch there: every pixel is fetched once per kernel tap)
+  {
+    const hipError_t eb = launch_conv3x3_big(dtype, a, num_cu, s, kernel_id, tm);
+    if (eb != hipErrorNotSupported) return eb;
+  }
   switch (dtype) {
     case OCTO_F16: return launch_typed<_Float16>(a, num_cu, s, kernel_id, tm);
     case OCTO_BF16: return launch_typed<__bf16>(a, num_cu, s, kernel_id, tm);

@@ -51,6 +51,8 @@ hipError_t launch_conv(int dtype, const ConvArgs& a, int num_cu, hipStream_t s, 
 hipError_t launch_stem(int dtype, const ConvArgs& a, int num_cu, hipStream_t s, int* kernel_id, ConvTiming tm);
 // 3x3 stride-1 kernel with the input patch in LDS; hipErrorNotSupported when the layer does not fit it
 hipError_t launch_conv3x3_patch(int dtype, const ConvArgs& a, int num_cu, hipStream_t s, int* kernel_id, ConvTiming tm);
+// 3x3 stride-1 kernel for wide layers (patch in LDS, 192 / 256-channel tiles); hipErrorNotSupported when the layer does not fit it
+hipError_t launch_conv3x3_big(int dtype, const ConvArgs& a, int num_cu, hipStream_t s, int* kernel_id, ConvTiming tm);
 int conv_kernel_id(int bc, int bp, int kv, int minb, bool vec, bool dma = false);
 enum { KID_NONE = 0, KID_MAXPOOL = 1, KID_UPSAMPLE = 2, KID_COPY = 3, KID_ADD = 4, KID_GAP = 5 };
 size_t conv_packed_weight_elems(int cout, int kh, int kw, int cin, int dtype, int* kp_out, int* cout_pad_out);

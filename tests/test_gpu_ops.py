@@ -214,6 +214,49 @@ def test_3x3_64_channel_layers_on_wide_maps(octo, dtype):
         assert rel_err(got[t], ref[t]) <= TOL[dtype], t
 
 
+BIG3X3_CASES = [
+    # (h, w, cin, cout, batch, layers expected on the wide kernel): 3x3 / stride-1 layers with at least 160 output channels, input
+    # channels in slices of 32, and enough pixels
+    (30, 30, 32, 544, 50, 3),     # 192-channel tiles x 3 (ragged last tile: 544 = 2 x 192 + 160), tile 25 x 10, 1 and 17 channel slices
+    (14, 14, 64, 256, 700, 3),    # 256-channel tiles, tiles span image boundaries (18 stack rows of 14-wide images)
+    (7, 7, 96, 192, 2700, 3),     # 7 x 7 images: 36 stack rows per tile = five images and a bit, 192-channel tiles
+    (23, 34, 32, 224, 180, 3),    # odd height, tile width 17, 224 of a 256-channel tile used
+    (20, 20, 64, 208, 330, 1),    # channel tail inside a 32-block (208 = 6 x 32 + 16); the next layers (208 input channels) take the general kernel
+]
+
+
+@pytest.mark.parametrize("dtype", ["f16", "bf16"])
+@pytest.mark.parametrize("case", BIG3X3_CASES)
+def test_wide_3x3_kernel_parity(octo, dtype, case):
+    """The wide 3x3 kernel (input patch in LDS, 192 / 256-channel tiles) against the oracle: SiLU layer, then a ReLU layer
+    with the residual added before the activation, then a SiLU layer with the residual added after it; sampled output
+    positions from every image region (corners, borders, image boundaries inside a tile, the last items)."""
+    h, w, cin, cout, n, n_wide = case
+
+    def build(B):
+        a = B.conv(0, cout, 3, 1, act=zoo.ACT_SILU)
+        b = B.conv(a, cout, 3, 1, act=zoo.ACT_RELU, res=a, res_mode=zoo.RES_BEFORE_ACT, wscale=0.25)
+        return B.conv(b, cout, 3, 1, act=zoo.ACT_SILU, res=a, res_mode=zoo.RES_AFTER_ACT, wscale=0.25)
+    m = _model(dtype, (h, w), cin, build, n)
+    x = zoo.round_to_dtype(np.random.default_rng(31).uniform(-1, 1, (n, h, w, cin)).astype(np.float32), dtype)
+    spec = zoo.PipelineSpec("t", [small_root(dtype), m], [], 200.0, 32, 32, 1, 1)
+    P = octo.Pipeline(spec, keep_all_tensors=True)
+    P.run_model_on(1, octo.to_device(x, dtype))
+    got = [x] + [P.get_tensor(1, t, n) for t in range(1, 4)]
+    kid = P.layer_info(1)[1]
+    P.close()
+    assert all(1700000000 <= int(k) < 1800000000 for k in kid[:n_wide]), kid      # these layers ran on the wide kernel
+    assert all(not (1700000000 <= int(k) < 1800000000) for k in kid[n_wide:3]), kid
+    rng = np.random.default_rng(32)
+    pos = [(0, 0, 0), (0, h - 1, w - 1), (n - 1, 0, w - 1), (n - 1, h - 1, 0), (n - 1, h - 1, w - 1), (1, 0, 0), (n // 2, h - 1, 0)]
+    pos += [(int(rng.integers(0, n)), int(rng.integers(0, h)), int(rng.integers(0, w))) for _ in range(90)]
+    for li, L in enumerate(m.layers[:3]):
+        res = got[L.inputs[1]] if len(L.inputs) > 1 else None
+        want = nn.conv_layer_at(got[L.inputs[0]], L, dtype, pos, res)
+        have = np.stack([got[li + 1][a, b, c] for (a, b, c) in pos])
+        assert rel_err(have, want) <= TOL[dtype], (li, case)
+
+
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 def test_every_tensor_of_a_bottleneck_residual_classifier(octo, dtype):
     """ResNet-50-shaped blocks (1x1 -> 3x3 stride s -> 1x1 with 4x expansion up to 2048 channels, 1x1 stride-s projection
