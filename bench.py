@@ -26,13 +26,13 @@ HBM_PEAK = 8000.0                                        # GB/s
 
 
 def make_workload(name: str):
-    from paper_2502_01277_amd import synth, zoo
+    from paper_2502_01277_amd import binding, synth, zoo
     if name == "traffic":
         spec = zoo.traffic_cascade()
         rng = np.random.default_rng(zoo.SEED0 + 2)
         counts = synth.counts_poisson(rng, 8, 8.0, 64)
         scene = synth.make_scene(rng, 8, 1080, 1920, counts, 24, 360, log_uniform=True)
-        heads = synth.planted_heads(rng, spec.models[0], scene, 1080, 1920)
+        heads = synth.planted_heads(rng, spec.models[0], scene, 1080, 1920, binding.letterbox_geometry(1080, 1920, spec.models[0].in_h, spec.models[0].in_w))
         desc = "traffic cascade: 8x1920x1080 u8 frames (4 cameras x 2), CSP-s detector 640 fp16, planted heads Poisson(8), " \
                "ResNet-18-shaped classifier 224 + 6-layer plate detector 128 on every ROI"
     elif name == "hires":
@@ -40,7 +40,7 @@ def make_workload(name: str):
         rng = np.random.default_rng(zoo.SEED0 + 5)
         counts = synth.counts_pareto(rng, 32)
         scene = synth.make_scene(rng, 32, 2160, 3840, counts, 48, 720, log_uniform=True)
-        heads = synth.planted_heads(rng, spec.models[0], scene, 2160, 3840, n_clutter=1100)
+        heads = synth.planted_heads(rng, spec.models[0], scene, 2160, 3840, binding.letterbox_geometry(2160, 3840, spec.models[0].in_h, spec.models[0].in_w), n_clutter=1100)
         desc = "high-resolution cascade: 32x3840x2160 frames, CSP-m detector 1280 bf16, planted heads Pareto(1.5), ResNet-18-shaped classifier"
     elif name == "tiny":
         spec = zoo.tiny_cascade()
@@ -169,7 +169,7 @@ def run_sweep(args):
         rng = np.random.default_rng(zoo.SEED0 + 3)
         counts = synth.counts_negbin(rng, bz)
         scene = synth.make_scene(rng, bz, 1080, 1920, counts, 24, 200, log_uniform=True)
-        heads = synth.planted_heads(rng, det, scene, 1080, 1920)
+        heads = synth.planted_heads(rng, det, scene, 1080, 1920, binding.letterbox_geometry(1080, 1920, det.in_h, det.in_w))
         dev = [torch.from_numpy(f).cuda() for f in scene.frames]
         pipes, keep = [], []
         for _ in range(ninst):

@@ -154,7 +154,11 @@ octo_status octo_run(octo_pipeline* p, void* hip_stream, int32_t* n_frames_launc
 octo_status octo_collect(octo_pipeline* p, octo_frame_result* frames, int32_t frame_cap, octo_box* boxes, int32_t box_cap,
                          int32_t* n_frames, int32_t* n_boxes, int32_t blocking);
 
-octo_status octo_set_batch_size(octo_pipeline* p, int32_t model, int32_t bz);   /* 1 <= bz <= the model's capacity */
+/* The batch size of the root model: the most frames one batch takes from the queue (1 <= bz <= max_frames).  Downstream
+ * models have no launch batch size: a child runs once per batch on however many ROIs its parent emitted, the count
+ * staying on the device; a scheduler's batch size for a child (Algorithm 1) only sizes its time slot.  model > 0 is
+ * therefore refused with OCTO_EINVAL. */
+octo_status octo_set_batch_size(octo_pipeline* p, int32_t model, int32_t bz);
 /* Every model has a batch size of its own (Sec. III-B, Algorithm 1): with frames_per_execution = b > 0 the detector's
  * layers and post-processing run on b frames at a time, ceil(n / b) executions per batch of n frames, while the
  * downstream models still run once on the ROIs of the whole batch - a detector at batch size b feeding children that
@@ -265,6 +269,12 @@ octo_status octo_debug_get_rois(octo_pipeline* p, int32_t edge, octo_roi* rois, 
 octo_status octo_debug_get_labels(octo_pipeline* p, int32_t edge, int32_t* labels, int32_t cap, int32_t* n);
 
 /* ---- stage-level calls: the same kernels the pipeline launches, on caller-owned device buffers ---- */
+
+/* Where the letterbox puts a src_h x src_w frame inside a dst_h x dst_w input (host only, no GPU): the resized
+ * frame is *nw x *nh pixels (r = min(dst_w / src_w, dst_h / src_h), sizes rounded half up) with its top-left corner
+ * at (*left, *top), centred with the odd pixel going right / down.  Boxes are mapped back with exactly these values. */
+octo_status octo_letterbox_geometry(int32_t src_h, int32_t src_w, int32_t dst_h, int32_t dst_w,
+                                    int32_t* nw, int32_t* nh, int32_t* left, int32_t* top);
 
 /* Letterbox + normalise: aspect-preserving bilinear resize (half-pixel centres, no antialias) of n uint8 HWC
  * frames into dst [n][dst_h][dst_w][3] of `dtype`, centred, padded with pad_value, out = px*scale + bias.

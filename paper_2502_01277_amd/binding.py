@@ -86,7 +86,7 @@ EXPORTS = [
     "octo_stream_destroy", "octo_device_cu_count", "octo_cwd_search", "octo_coral_schedule", "octo_est_latency_ms",
     "octo_est_throughput", "octo_run_model", "octo_profile_layers", "octo_set_layer_timing", "octo_get_layer_info", "octo_set_stage_timing", "octo_get_stage_ms",
     "octo_debug_get_tensor", "octo_debug_tensor_shape", "octo_debug_set_head", "octo_debug_run_model",
-    "octo_debug_get_detections", "octo_debug_get_rois", "octo_debug_get_labels", "octo_op_letterbox",
+    "octo_debug_get_detections", "octo_debug_get_rois", "octo_debug_get_labels", "octo_letterbox_geometry", "octo_op_letterbox",
     "octo_op_crop_resize", "octo_op_decode", "octo_op_topk", "octo_op_nms", "octo_op_nms_scratch_bytes", "octo_op_nms_static", "octo_op_compact", "octo_probe_copy", "octo_probe_mfma",
 ]
 
@@ -136,6 +136,7 @@ def lib() -> C.CDLL:
         L.octo_debug_get_detections.argtypes = [vp, i32, i32, vp, vp, i32, vp, vp, i32, vp]
         L.octo_debug_get_rois.argtypes = [vp, i32, vp, i32, vp]
         L.octo_debug_get_labels.argtypes = [vp, i32, vp, i32, vp]
+        L.octo_letterbox_geometry.argtypes = [i32, i32, i32, i32, vp, vp, vp, vp]
         L.octo_op_letterbox.argtypes = [vp, vp, i32, i32, i32, vp, i32, i32, i32, vp, vp, i32, vp]
         L.octo_op_crop_resize.argtypes = [vp, vp, i32, i32, i32, vp, vp, i32, vp, i32, i32, i32, vp, vp, vp]
         L.octo_op_decode.argtypes = [vp, vp, i32, vp, vp, i32, vp]
@@ -402,6 +403,13 @@ def frame_tables(frames: Sequence):
     ptrs = t.tensor([int(f.data_ptr()) for f in frames], dtype=t.int64, device=frames[0].device)
     pitches = t.tensor([int(f.stride(0)) for f in frames], dtype=t.int64, device=frames[0].device)
     return ptrs, pitches
+
+
+def letterbox_geometry(src_h: int, src_w: int, dst_h: int, dst_w: int):
+    """(nw, nh, left, top) of the resized frame inside the model input, from the library (host only)."""
+    v = [C.c_int32() for _ in range(4)]
+    _st(lib().octo_letterbox_geometry(src_h, src_w, dst_h, dst_w, *[C.byref(x) for x in v]))
+    return tuple(int(x.value) for x in v)
 
 
 def op_letterbox(frames: Sequence, dst_h, dst_w, dtype: str, scale=(1 / 255.0,) * 3, bias=(0.0,) * 3, pad_value=114, stream=None):

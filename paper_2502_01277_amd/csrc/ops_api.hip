@@ -36,6 +36,16 @@ octo_status static_scratch(void** out) {
 
 extern "C" {
 
+octo_status octo_letterbox_geometry(int32_t src_h, int32_t src_w, int32_t dst_h, int32_t dst_w,
+                                    int32_t* nw, int32_t* nh, int32_t* left, int32_t* top) {
+  if (!nw || !nh || !left || !top || src_h <= 0 || src_w <= 0 || dst_h <= 0 || dst_w <= 0 || src_h > 16384 || src_w > 16384 || dst_h > 16384 || dst_w > 16384)
+    return OCTO_EINVAL;
+  int a, b, c, d;
+  letterbox_geometry(src_h, src_w, dst_h, dst_w, &a, &b, &c, &d);
+  *nw = a; *nh = b; *left = c; *top = d;
+  return OCTO_OK;
+}
+
 octo_status octo_op_letterbox(const void* d_frame_ptrs, const void* d_pitches, int32_t n, int32_t src_h, int32_t src_w,
                               void* d_dst, int32_t dst_h, int32_t dst_w, int32_t dtype, const float* scale3, const float* bias3,
                               int32_t pad_value, void* hip_stream) {

@@ -622,6 +622,8 @@ hipEvent_t get_event(octo_pipeline* p) {
 enum { ST_LETTERBOX = 0, ST_DET_LAYERS, ST_DECODE, ST_TOPK, ST_NMS, ST_COMPACT, ST_FIXED };
 // per edge: crop, layers, tail
 
+octo_status enqueue_root(octo_pipeline* p, hipStream_t s, int n);
+
 octo_status start_batch(octo_pipeline* p, hipStream_t s, int* launched) {
   ModelPlan& root = p->models[0];
   const int n = (int)std::min<size_t>(p->queue.size(), (size_t)root.bz);
@@ -630,8 +632,29 @@ octo_status start_batch(octo_pipeline* p, hipStream_t s, int* launched) {
   if ((int)p->inflight.size() >= RING - 1) { *launched = 0; return fail(p, OCTO_ESTATE, "too many uncollected batches (%d)", (int)p->inflight.size()); }
   // activations and ROI tables are single-buffered: a new batch may not start before the previous one is complete
   if (!p->inflight.empty()) HIPCHK(p, hipStreamWaitEvent(s, p->inflight.back().done, 0));
+  // Everything that can fail before work is enqueued happens first: a batch that cannot get its events leaves the
+  // queue, the slot counter and the list of batches in flight untouched.
   Batch b;
-  b.n = n; b.slot = p->next_slot; p->next_slot = (p->next_slot + 1) % RING;
+  b.n = n; b.slot = p->next_slot;
+  auto give_back = [&](Batch& x) {
+    if (x.done) p->event_pool.push_back(x.done);
+    for (hipEvent_t e : x.stage_ev) p->event_pool.push_back(e);
+    for (auto& v : x.layer_ev) for (hipEvent_t e : v) p->event_pool.push_back(e);
+    x.done = nullptr; x.stage_ev.clear(); x.layer_ev.clear();
+  };
+  b.done = get_event(p);
+  bool ok = b.done != nullptr;
+  if (ok && p->stage_timing) {
+    const int ne = 1 + ST_FIXED + 3 * (int)p->edges.size();
+    for (int i = 0; i < ne && ok; ++i) { hipEvent_t e = get_event(p); if (e) b.stage_ev.push_back(e); else ok = false; }
+  }
+  b.layer_ev.resize(p->models.size());
+  if (ok && p->layer_timing)
+    for (size_t k = 0; k < p->models.size() && ok; ++k)
+      for (size_t i = 0; i < 3 * p->models[k].layers.size() + 1 && ok; ++i) {
+        hipEvent_t e = get_event(p); if (e) b.layer_ev[k].push_back(e); else ok = false;
+      }
+  if (!ok) { give_back(b); *launched = 0; return fail(p, OCTO_EHIP, "hipEventCreate failed"); }
   const void** hp = (const void**)p->h_tables[b.slot];
   size_t* hpitch = (size_t*)(p->h_tables[b.slot] + (size_t)p->max_frames * sizeof(void*));
   for (int i = 0; i < n; ++i) {
@@ -639,23 +662,31 @@ octo_status start_batch(octo_pipeline* p, hipStream_t s, int* launched) {
     hp[i] = q.ptr; hpitch[i] = q.pitch;
     b.ids.push_back(q.id); b.arrival.push_back(q.arrival);
   }
-  p->queue.erase(p->queue.begin(), p->queue.begin() + n);
   b.t_launch = octo_now_ms();
   b.model_ran.assign(p->models.size(), false);
-  b.done = get_event(p);
-  if (!b.done) return fail(p, OCTO_EHIP, "hipEventCreate failed");
-  if (p->stage_timing) {
-    const int ne = 1 + ST_FIXED + 3 * (int)p->edges.size();
-    for (int i = 0; i < ne; ++i) { hipEvent_t e = get_event(p); if (!e) return fail(p, OCTO_EHIP, "hipEventCreate failed"); b.stage_ev.push_back(e); }
-  }
-  b.layer_ev.resize(p->models.size());
-  if (p->layer_timing)
-    for (size_t k = 0; k < p->models.size(); ++k)
-      for (size_t i = 0; i < 3 * p->models[k].layers.size() + 1; ++i) {
-        hipEvent_t e = get_event(p); if (!e) return fail(p, OCTO_EHIP, "hipEventCreate failed"); b.layer_ev[k].push_back(e);
-      }
   p->inflight.push_back(std::move(b));
+  // If enqueueing fails half-way, the batch is withdrawn again: its frames stay queued (a later run forms the batch anew;
+  // whatever part was enqueued only wrote this pipeline's own buffers), and the handle stays usable.
+  const octo_status st = enqueue_root(p, s, n);
+  if (st != OCTO_OK) {
+    give_back(p->inflight.back());
+    p->inflight.pop_back();
+    *launched = 0;
+    return st;
+  }
+  p->next_slot = (p->next_slot + 1) % RING;
+  p->queue.erase(p->queue.begin(), p->queue.begin() + n);
+  p->inflight.back().model_ran[0] = true;
+  return OCTO_OK;
+}
+
+// Enqueues the root model's part of the newest batch in flight (copy of the frame table, letterbox, detector, decode,
+// top-k, NMS, ROI compaction) on `s`.
+octo_status enqueue_root(octo_pipeline* p, hipStream_t s, int n) {
+  ModelPlan& root = p->models[0];
   Batch& B = p->inflight.back();
+  const void** hp = (const void**)p->h_tables[B.slot];
+  size_t* hpitch = (size_t*)(p->h_tables[B.slot] + (size_t)p->max_frames * sizeof(void*));
   hipEvent_t* ev = p->stage_timing ? B.stage_ev.data() : nullptr;
   HIPCHK(p, hipMemcpyAsync(p->d_frames[B.slot], hp, n * sizeof(void*), hipMemcpyHostToDevice, s));
   HIPCHK(p, hipMemcpyAsync(p->d_pitch[B.slot], hpitch, n * sizeof(size_t), hipMemcpyHostToDevice, s));
@@ -695,7 +726,6 @@ octo_status start_batch(octo_pipeline* p, hipStream_t s, int* launched) {
   HIPCHK(p, launch_compact(ca, s));
   if (ev) HIPCHK(p, hipEventRecord(ev[1 + ST_COMPACT], s));
   HIPCHK(p, hipEventRecord(p->ev_det, s));
-  B.model_ran[0] = true;
   return OCTO_OK;
 }
 
@@ -794,7 +824,11 @@ octo_status octo_pipeline_create(const octo_pipeline_desc* desc, void* device_wo
 
 octo_status octo_pipeline_destroy(octo_pipeline* p) {
   if (!p) return OCTO_EINVAL;
-  for (Batch& b : p->inflight) { if (b.done) { hipEventSynchronize(b.done); hipEventDestroy(b.done); } for (hipEvent_t e : b.stage_ev) hipEventDestroy(e); }
+  for (Batch& b : p->inflight) {
+    if (b.done) { hipEventSynchronize(b.done); hipEventDestroy(b.done); }
+    for (hipEvent_t e : b.stage_ev) hipEventDestroy(e);
+    for (auto& v : b.layer_ev) for (hipEvent_t e : v) hipEventDestroy(e);
+  }
   for (hipEvent_t e : p->event_pool) hipEventDestroy(e);
   if (p->ev_det) hipEventDestroy(p->ev_det);
   for (hipEvent_t e : p->ev_child) hipEventDestroy(e);
@@ -819,6 +853,9 @@ octo_status octo_submit_frames(octo_pipeline* p, const void* const* d_frames, co
 octo_status octo_set_batch_size(octo_pipeline* p, int32_t model, int32_t bz) {
   if (!p) return OCTO_EINVAL;
   if (model < 0 || model >= (int)p->models.size() || bz < 1 || bz > p->models[model].cap) return fail(p, OCTO_EINVAL, "bad model or batch size");
+  // a downstream model runs once per batch on however many ROIs its parent emitted (the count stays on the device), so
+  // it has no launch batch size to set: a scheduler's batch size for it only sizes its time slot
+  if (model > 0) return fail(p, OCTO_EINVAL, "model %d is a downstream model: it always takes the whole ROI set of a batch", model);
   p->models[model].bz = bz;
   return OCTO_OK;
 }

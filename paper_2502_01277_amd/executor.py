@@ -618,7 +618,7 @@ def make_colocation(duration_s: float, n_cameras=(6, 6, 4), pool_frames: int = 8
         scene = synth.make_scene(rng, pool_frames, h, w, counts, 24, 360, log_uniform=True)
         scenes.append(scene)
         dev = [torch.from_numpy(f).cuda() for f in scene.frames]
-        hh = synth.planted_heads(rng, spec.models[0], scene, h, w)
+        hh = synth.planted_heads(rng, spec.models[0], scene, h, w, binding.letterbox_geometry(h, w, spec.models[0].in_h, spec.models[0].in_w))
         heads_host.append(hh)
         pools.append([binding.to_device(x, spec.models[0].dtype) for x in hh])
         for _ in range(n_cameras[i]):

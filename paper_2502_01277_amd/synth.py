@@ -111,16 +111,12 @@ def _logit(p):
     return math.log(p / (1.0 - p))
 
 
-def letterbox_geometry(src_h, src_w, dst):
-    """(scale r, new width, new height, left, top) of the aspect-preserving fit into dst x dst."""
-    r = min(dst / src_w, dst / src_h)
-    nw = int(math.floor(src_w * r + 0.5))
-    nh = int(math.floor(src_h * r + 0.5))
-    return r, nw, nh, (dst - nw) // 2, (dst - nh) // 2
-
-
-def planted_heads(rng, det: ModelSpec, scene: Scene, src_h, src_w, max_dups=4, n_clutter=0):
+def planted_heads(rng, det: ModelSpec, scene: Scene, src_h, src_w, geom, max_dups=4, n_clutter=0):
     """Head tensors whose decode yields the scene's rectangles (plus near-duplicates and clutter).
+
+    geom = (nw, nh, left, top): size and position of the resized frame inside the detector's input, as the
+    pre-processing under test places it (the caller asks the implementation it feeds: this generator holds no
+    letterbox arithmetic of its own).
 
     Returns a list (one per level) of fp32 arrays [N][G][G][A*(5+C)] holding
     values already representable in the detector's storage type.  Random-init
@@ -138,7 +134,7 @@ def planted_heads(rng, det: ModelSpec, scene: Scene, src_h, src_w, max_dups=4, n
         h[..., 4] = -8.0
         h[..., 5:] = np.minimum(h[..., 5:], 2.0)
         heads.append(h)
-    _, nw, nh, left, top = letterbox_geometry(src_h, src_w, det.in_w)
+    nw, nh, left, top = geom
     rx, ry = nw / src_w, nh / src_h
     used = set()
 

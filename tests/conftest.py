@@ -14,10 +14,12 @@ def pytest_configure(config):
 
 @pytest.fixture(scope="session", autouse=True)
 def _library_is_built():
-    """The tests load the library that is built in-tree; only if there is none (a fresh checkout) it is built once."""
-    from paper_2502_01277_amd import binding
-    if not os.path.exists(binding.LIB_PATH):
-        from paper_2502_01277_amd import build
+    """The tests load the library that is built in-tree.  It is (re)built here only if it is missing or older than one of
+    its sources: a stale library would test yesterday's kernels."""
+    from paper_2502_01277_amd import binding, build
+    srcs = [os.path.join(build.CSRC, f) for f in os.listdir(build.CSRC) if f.endswith((".hip", ".cpp", ".h"))]
+    srcs.append(os.path.join(ROOT, "include", "octo.h"))
+    if not os.path.exists(binding.LIB_PATH) or os.path.getmtime(binding.LIB_PATH) < max(os.path.getmtime(f) for f in srcs):
         build.build(verbose=False)
 
 

@@ -28,6 +28,17 @@ def test_library_exports_every_declared_symbol():
     assert sorted(binding.EXPORTS) == declared
 
 
+def test_letterbox_geometry_matches_the_oracle():
+    from oracle import preprocess as pre
+    rng = np.random.default_rng(5)
+    shapes = [(1080, 1920, 640, 640), (2160, 3840, 1280, 1280), (720, 1280, 640, 640), (320, 320, 320, 320), (100, 37, 64, 64), (45, 83, 64, 64)]
+    shapes += [tuple(int(v) for v in rng.integers(8, 900, 4)) for _ in range(200)]
+    for (sh, sw, dh, dw) in shapes:
+        assert binding.letterbox_geometry(sh, sw, dh, dw) == tuple(pre.letterbox_geometry(sh, sw, dh, dw)[1:]), (sh, sw, dh, dw)
+    with pytest.raises(binding.OctoError):
+        binding.letterbox_geometry(0, 10, 10, 10)
+
+
 def test_record_sizes_match_header():
     assert binding.CAND_DTYPE.itemsize == 32 and binding.ROI_DTYPE.itemsize == 32 and binding.BOX_DTYPE.itemsize == 32
     assert binding.FRAME_DTYPE.itemsize == 32

@@ -116,6 +116,9 @@ def test_error_returns_leave_the_pipeline_usable(octo):
     assert P.run() == 2 and len(P.collect()[0]) == 2
     with pytest.raises(octo.OctoError):
         P.set_batch_size(0, 3)                                    # beyond the detector's capacity
+    with pytest.raises(octo.OctoError) as ei:
+        P.set_batch_size(1, 1)                                    # a downstream model always takes the whole ROI set
+    assert ei.value.status == octo.EINVAL
     P.close()
 
 

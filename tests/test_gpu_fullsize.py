@@ -150,7 +150,7 @@ def test_sweep_workload_at_full_batch_on_samples(octo, bz):
     rng = np.random.default_rng(zoo.SEED0 + 3)
     counts = synth.counts_negbin(rng, bz)
     scene = synth.make_scene(rng, bz, 1080, 1920, counts, 24, 200, log_uniform=True)
-    heads = synth.planted_heads(rng, det, scene, 1080, 1920)
+    heads = synth.planted_heads(rng, det, scene, 1080, 1920, pre.letterbox_geometry(1080, 1920, det.in_h, det.in_w)[1:])
     P = octo.Pipeline(spec, keep_all_tensors=True)
     d_heads = [octo.to_device(h, det.dtype) for h in heads]
     for l, h in enumerate(d_heads):

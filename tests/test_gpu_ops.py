@@ -30,6 +30,14 @@ def test_letterbox_parity(octo, dtype, sh, sw, dst):
     ref = pre.letterbox(frames, dst, dst, dtype)
     ulp = {"f32": 2e-6, "f16": 1e-3, "bf16": 8e-3}[dtype]       # one unit in the last place at 1.0, plus fp32 interpolation error
     assert np.abs(got - ref).max() <= ulp
+    # How many values may differ at all.  The kernel interpolates in fp32 (four multiply-adds per value), the oracle in
+    # fp64 with one rounding to the storage type.  In fp32 storage that leaves the last bit of most values open (an
+    # earlier bound of "fewer than half differ" was wrong by construction and was dropped); what must hold is the 2e-6
+    # above.  In the 16-bit types both sides round an almost identical value once, so they can only differ where the exact
+    # value lies within the fp32 error (about 1e-7) of a rounding boundary (spacing 2^-11 / 2^-8 relative): a handful
+    # of values per million at most.
+    if dtype != "f32":
+        assert (got != ref).mean() < 2e-3
 
 
 def test_letterbox_strided_rows_and_normalisation(octo):
@@ -297,7 +305,7 @@ def _planted(dtype, n=3, seed=11, dups=4, clutter=0, det=None, hw=(270, 480)):
     det = det or zoo.csp_detector("d", dtype, 320, zoo.S_WIDTHS, zoo.S_DEPTHS, 80, seed=3, topk=300, max_det=50)
     counts = synth.counts_poisson(rng, n, 8, 64)
     scene = synth.make_scene(rng, n, hw[0], hw[1], counts, 12, 120, log_uniform=True)
-    heads = synth.planted_heads(rng, det, scene, hw[0], hw[1], max_dups=dups, n_clutter=clutter)
+    heads = synth.planted_heads(rng, det, scene, hw[0], hw[1], pre.letterbox_geometry(hw[0], hw[1], det.in_h, det.in_w)[1:], max_dups=dups, n_clutter=clutter)
     return det, scene, heads
 
 

@@ -51,7 +51,7 @@ def test_planted_boxes_round_trip_through_decode(dtype):
     det = zoo.csp_detector("d", dtype, 640, zoo.S_WIDTHS, zoo.S_DEPTHS, 80, seed=3)
     counts = np.array([5, 0, 9])
     scene = synth.make_scene(rng, 3, 270, 480, counts, 12, 120, log_uniform=True)
-    heads = synth.planted_heads(rng, det, scene, 270, 480, max_dups=0)
+    heads = synth.planted_heads(rng, det, scene, 270, 480, pre.letterbox_geometry(270, 480, det.in_h, det.in_w)[1:], max_dups=0)
     _, nw, nh, left, top = pre.letterbox_geometry(270, 480, 640, 640)
     tol = {"f32": 0.01, "f16": 0.5, "bf16": 4.0}[dtype]
     for f in range(3):
@@ -193,7 +193,7 @@ def test_postprocess_pipeline_on_planted_heads_with_duplicates():
     det = zoo.csp_detector("d", "f16", 640, zoo.S_WIDTHS, zoo.S_DEPTHS, 80, seed=3, topk=1000, max_det=64)
     counts = synth.counts_poisson(rng, 4)
     scene = synth.make_scene(rng, 4, 1080, 1920, counts, 24, 360, log_uniform=True)
-    heads = synth.planted_heads(rng, det, scene, 1080, 1920, max_dups=4)
+    heads = synth.planted_heads(rng, det, scene, 1080, 1920, pre.letterbox_geometry(1080, 1920, det.in_h, det.in_w)[1:], max_dups=4)
     dets = postprocess_heads(heads, det)
     for f, d in enumerate(dets):
         assert d.cand_count >= counts[f]
