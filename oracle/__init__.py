@@ -2,7 +2,8 @@
 
 TEST INFRASTRUCTURE ONLY.  Plain, slow, obviously-correct implementations of
 every stage (letterbox, conv graph, decode, top-k, NMS, ROI compaction,
-crop-resize, classifier tail, batch-size search, portion scheduling).  It shares
+crop-resize, classifier tail, batch-size search, portion scheduling, the
+run-time rules of the serving loop).  It shares
 no code with the HIP path and must never be imported by the product package;
 only tests, the smoke check and the benchmark's CPU-baseline leg use it.
 
@@ -15,5 +16,8 @@ brute force, closed forms or invariants, except
   * sched.cwd_lite  - parity unpinned against the paper (no worked example is
     printed); pinned only by invariants and exhaustive search on small cases;
   * sched.coral     - parity unpinned against the paper; pinned by a
-    hand-computed two-pipeline example and a schedule validator.
+    hand-computed two-pipeline example and a schedule validator;
+  * runtime.*       - parity unpinned against the paper (burstiness, lazy
+    dropping and the horizontal scaler are named there without a formula or an
+    example); pinned by hand-computed cases in tests/test_oracle_runtime.py.
 """
