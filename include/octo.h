@@ -208,6 +208,38 @@ octo_status octo_coral_schedule(octo_sched_pipeline* ps, int32_t n_pipelines, do
 float octo_est_latency_ms(const octo_sched_pipeline* p);
 float octo_est_throughput(const octo_sched_pipeline* p);
 
+/* ---- run-time rules of the serving loop (host only) ----
+ * The paper names them in prose; each comment states the reading this library takes. */
+
+/* Burstiness of a request stream (Sec. III-B: the coefficient of variation of inter-request arrival times): population
+ * standard deviation / mean of the gaps between the n arrival times taken in ascending order; 0 for fewer than three
+ * arrivals or a zero mean gap. */
+octo_status octo_burstiness(const double* times, int32_t n, double* cv);
+/* Back-to-back batches a model's portion must hold with one instance per model (Sec. III-C: a portion is as long as the
+ * model's execution): ceil(rate x duty cycle / bz), at least 1. */
+octo_status octo_batches_per_cycle(double rate_per_s, double duty_ms, int32_t bz, int32_t* k);
+/* Portion width (share of the GPU's compute, Sec. III-C) -> compute units: rounded up to whole multiples of `grain`
+ * (8 on this GPU: one unit per die), at least one grain, at most total_cus. */
+octo_status octo_width_to_cus(double util, int32_t total_cus, int32_t grain, int32_t* n_cu);
+/* Width of a model from its batch latency on streams of n widths (compute units).  by_cost != 0: the narrowest width
+ * whose cost width x latency is within tol of the cheapest (a model that does not speed up on more units should not
+ * hold them); by_cost == 0: the narrowest width whose latency is within tol of the widest width's. */
+octo_status octo_choose_width(const int32_t* widths, const double* latency_ms, int32_t n, int32_t by_cost, double tol, int32_t* width);
+/* Lazy dropping (Sec. IV-A): how many requests at the head of an arrival-ordered queue are already older than the
+ * objective when a batch is formed (now - arrival > slo; exactly the objective old is still served; counting stops
+ * at the first request that is not late). */
+octo_status octo_late_prefix(const double* arrival_ms, int32_t n, double now_ms, double slo_ms, int32_t* n_late);
+/* Horizontal scaling between two runs of the scheduler (Sec. III-D).  One object per pipeline; once per duty cycle
+ * octo_scaler_observe is told how many requests arrived and how many are queued, with n_active instances running, each
+ * serving `capacity` requests per cycle.  Over the last `window` cycles: *decision = +1 if n_active < max_instances and
+ * (mean arrivals > up x capacity x n_active, or the queue never fell to capacity x n_active or below); else -1 if
+ * n_active > 1, mean arrivals < down x capacity x (n_active - 1) and the current queue fits capacity x (n_active - 1);
+ * else 0.  A non-zero decision empties the window; before the window is full the decision is 0.  down < up. */
+typedef struct octo_scaler octo_scaler;
+octo_status octo_scaler_create(double capacity, int32_t window, double up, double down, int32_t max_instances, octo_scaler** out);
+octo_status octo_scaler_observe(octo_scaler* s, int64_t arrived, int64_t backlog, int32_t n_active, int32_t* decision);
+octo_status octo_scaler_destroy(octo_scaler* s);
+
 /* Temporal sharing: run only model `model` of the pipeline on `hip_stream` (used by a slot executor that places
  * each model's portion itself).  Model 0 forms the batch as octo_run does and stops after ROI compaction;
  * a child model consumes the ROIs of the most recent model-0 run; after the last child the batch becomes

@@ -84,7 +84,8 @@ EXPORTS = [
     "octo_pipeline_workspace_size", "octo_pipeline_create", "octo_pipeline_destroy", "octo_submit_frames", "octo_run",
     "octo_collect", "octo_set_batch_size", "octo_set_detector_batch", "octo_last_error", "octo_now_ms", "octo_stream_create_masked", "octo_stream_create_range",
     "octo_stream_destroy", "octo_device_cu_count", "octo_cwd_search", "octo_coral_schedule", "octo_est_latency_ms",
-    "octo_est_throughput", "octo_run_model", "octo_profile_layers", "octo_set_layer_timing", "octo_get_layer_info", "octo_set_stage_timing", "octo_get_stage_ms",
+    "octo_est_throughput", "octo_burstiness", "octo_batches_per_cycle", "octo_width_to_cus", "octo_choose_width", "octo_late_prefix",
+    "octo_scaler_create", "octo_scaler_observe", "octo_scaler_destroy", "octo_run_model", "octo_profile_layers", "octo_set_layer_timing", "octo_get_layer_info", "octo_set_stage_timing", "octo_get_stage_ms",
     "octo_debug_get_tensor", "octo_debug_tensor_shape", "octo_debug_set_head", "octo_debug_run_model",
     "octo_debug_get_detections", "octo_debug_get_rois", "octo_debug_get_labels", "octo_letterbox_geometry", "octo_op_letterbox",
     "octo_op_crop_resize", "octo_op_decode", "octo_op_topk", "octo_op_nms", "octo_op_nms_scratch_bytes", "octo_op_nms_static", "octo_op_compact", "octo_probe_copy", "octo_probe_mfma",
@@ -124,6 +125,15 @@ def lib() -> C.CDLL:
         L.octo_coral_schedule.argtypes = [vp, i32, C.c_double, C.c_double, i32, vp]
         L.octo_est_latency_ms.argtypes = [vp]
         L.octo_est_throughput.argtypes = [vp]
+        f64 = C.c_double
+        L.octo_burstiness.argtypes = [vp, i32, vp]
+        L.octo_batches_per_cycle.argtypes = [f64, f64, i32, vp]
+        L.octo_width_to_cus.argtypes = [f64, i32, i32, vp]
+        L.octo_choose_width.argtypes = [vp, vp, i32, i32, f64, vp]
+        L.octo_late_prefix.argtypes = [vp, i32, f64, f64, vp]
+        L.octo_scaler_create.argtypes = [f64, i32, f64, f64, i32, vp]
+        L.octo_scaler_observe.argtypes = [vp, C.c_int64, C.c_int64, i32, vp]
+        L.octo_scaler_destroy.argtypes = [vp]
         L.octo_profile_layers.argtypes = [vp, i32, i32, i32, vp, vp, vp, vp, i32]
         L.octo_set_stage_timing.argtypes = [vp, i32]
         L.octo_set_layer_timing.argtypes = [vp, i32]
@@ -565,6 +575,65 @@ def stream_destroy(stream: int):
 
 
 # ---- scheduling ---------------------------------------------------------------
+# ---- run-time rules of the serving loop (host only) ----
+def burstiness(times) -> float:
+    a = np.ascontiguousarray(times, np.float64)
+    out = C.c_double()
+    _st(lib().octo_burstiness(a.ctypes.data if a.size else None, int(a.size), C.byref(out)))
+    return float(out.value)
+
+
+def batches_per_cycle(rate_per_s: float, duty_ms: float, bz: int) -> int:
+    out = C.c_int32()
+    _st(lib().octo_batches_per_cycle(float(rate_per_s), float(duty_ms), int(bz), C.byref(out)))
+    return int(out.value)
+
+
+def width_to_cus(util: float, total_cus: int, grain: int = 8) -> int:
+    out = C.c_int32()
+    _st(lib().octo_width_to_cus(float(util), int(total_cus), int(grain), C.byref(out)))
+    return int(out.value)
+
+
+def choose_width(latency_by_width: dict, rule: str = "efficient", tol: float = 0.10) -> int:
+    ws = np.asarray(list(latency_by_width), np.int32)
+    lat = np.asarray([latency_by_width[int(w)] for w in ws], np.float64)
+    out = C.c_int32()
+    _st(lib().octo_choose_width(ws.ctypes.data, lat.ctypes.data, int(ws.size), 0 if rule == "latency" else 1, float(tol), C.byref(out)))
+    return int(out.value)
+
+
+def late_prefix(arrival_ms, now_ms: float, slo_ms: float) -> int:
+    a = np.ascontiguousarray(arrival_ms, np.float64)
+    out = C.c_int32()
+    _st(lib().octo_late_prefix(a.ctypes.data if a.size else None, int(a.size), float(now_ms), float(slo_ms), C.byref(out)))
+    return int(out.value)
+
+
+class Scaler:
+    """octo_scaler: the horizontal-scaling decision of one pipeline."""
+
+    def __init__(self, capacity: float, window: int = 5, up: float = 1.0, down: float = 0.75, max_instances: int = 2):
+        self.h = C.c_void_p()
+        _st(lib().octo_scaler_create(float(capacity), int(window), float(up), float(down), int(max_instances), C.byref(self.h)))
+
+    def observe(self, arrived: int, backlog: int, n_active: int) -> int:
+        out = C.c_int32()
+        _st(lib().octo_scaler_observe(self.h, int(arrived), int(backlog), int(n_active), C.byref(out)))
+        return int(out.value)
+
+    def close(self):
+        if self.h:
+            lib().octo_scaler_destroy(self.h)
+            self.h = C.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
 def sched_pipeline(models: Sequence[dict], slo_ms: float, keep: list) -> OctoSchedPipeline:
     """models: dicts with parent, profile {bz: ms}, rate, burstiness, util, weight_mem, inter_mem, bz."""
     arr = (OctoSchedModel * len(models))()

@@ -38,66 +38,15 @@ def _pow2_upto(cap: int, limit: int = 8) -> List[int]:
     return out
 
 
+# Every decision of the serving loop is the library's (include/octo.h, "run-time rules of the serving loop"); this module
+# only moves data between the pipelines, the scheduler calls and those rules.
 def width_to_cus(util: float, total: int) -> int:
-    """Portion width (share of compute, 0..1) -> number of compute units, rounded up to the stream granularity."""
-    n = int(math.ceil(util * total / CU_GRAIN - 1e-9)) * CU_GRAIN
-    return max(CU_GRAIN, min(total, n))
+    return binding.width_to_cus(util, total, CU_GRAIN)
 
 
-def coefficient_of_variation(times: np.ndarray) -> float:
-    """Burstiness of an arrival sequence: std / mean of the inter-arrival times (Sec. III-B)."""
-    if len(times) < 3:
-        return 0.0
-    d = np.diff(np.sort(np.asarray(times, np.float64)))
-    return float(d.std() / d.mean()) if d.mean() > 0 else 0.0
-
-
-def late_prefix(arrival_ms: Sequence[float], now_ms: float, slo_ms: float) -> int:
-    """Lazy dropping of late requests (Sec. IV-A, baselines): how many requests at the head of an arrival-ordered queue
-    are already older than the latency objective when a batch is formed.  They are dropped instead of served: their
-    results could not count any more, and the batch slots go to requests that can still make it."""
-    n = 0
-    for a in arrival_ms:
-        if now_ms - a <= slo_ms:
-            break
-        n += 1
-    return n
-
-
-class SurgeDetector:
-    """Run-time horizontal scaling decision for one pipeline (Sec. III-D): between two runs of the scheduler, a surge
-    of the workload adds an instance and a dip removes it again.
-
-    Once per duty cycle it is told how many requests arrived and how many are still queued.  One instance serves
-    `capacity` requests per cycle (the batches its slot may launch x the batch size).  An instance is added when the mean arrivals of the
-    last `window` cycles exceed `up` x the capacity of the active instances, or the queue stayed longer than that
-    capacity through the whole window; one is removed when the mean falls below `down` x the capacity of one instance
-    fewer and what is queued fits that capacity (at a cycle boundary the queue holds what arrived since the last slot,
-    so it is rarely empty).  down < up keeps the two decisions apart, and every decision empties the window, so
-    the next one is based on cycles observed after it."""
-
-    def __init__(self, capacity: float, window: int = 5, up: float = 1.0, down: float = 0.75, max_instances: int = 2):
-        assert capacity > 0 and window >= 1 and 0 < down < up and max_instances >= 1
-        self.capacity, self.window, self.up, self.down, self.max_instances = float(capacity), window, up, down, max_instances
-        self.arrived: List[int] = []
-        self.backlog: List[int] = []
-
-    def observe(self, arrived: int, backlog: int, n_active: int) -> int:
-        """+1: add an instance, -1: remove one, 0: leave as is."""
-        self.arrived.append(int(arrived))
-        self.backlog.append(int(backlog))
-        if len(self.arrived) < self.window:
-            return 0
-        self.arrived, self.backlog = self.arrived[-self.window:], self.backlog[-self.window:]
-        mean = sum(self.arrived) / self.window
-        have = self.capacity * n_active
-        if n_active < self.max_instances and (mean > self.up * have or min(self.backlog) > have):
-            self.arrived, self.backlog = [], []
-            return 1
-        if n_active > 1 and mean < self.down * self.capacity * (n_active - 1) and self.backlog[-1] <= self.capacity * (n_active - 1):
-            self.arrived, self.backlog = [], []
-            return -1
-        return 0
+coefficient_of_variation = binding.burstiness
+late_prefix = binding.late_prefix
+SurgeDetector = binding.Scaler
 
 
 @dataclass
@@ -108,19 +57,8 @@ class ModelProfile:
 
 
 def choose_width(by_width: Dict[int, Dict[int, float]], ref_bz: int, total: int, rule: str = "efficient", tol: float = 0.10) -> int:
-    """Portion width of a model from its latency at several stream widths (the paper takes a model's measured GPU
-    utilisation as the width, Sec. III-C; here widths are enforced, so the choice is made from the latency curve).
-    'latency': the narrowest width whose latency is within tol of the whole GPU's.  'efficient': the narrowest width
-    whose cost in compute-unit-milliseconds is within tol of the cheapest - a model that does not speed up on more
-    units should not hold them; whether its latency still fits is checked by the batch-size search, which is given
-    the profile measured at this width."""
-    ws = sorted(by_width)
-    if rule == "latency":
-        full = by_width[max(ws)][ref_bz]
-        return next(w for w in ws if by_width[w][ref_bz] <= (1.0 + tol) * full)
-    cost = {w: w * by_width[w][ref_bz] for w in ws}
-    best = min(cost.values())
-    return next(w for w in ws if cost[w] <= (1.0 + tol) * best)
+    """Portion width of a model from its latency at several stream widths (octo_choose_width) at batch size ref_bz."""
+    return binding.choose_width({w: by_width[w][ref_bz] for w in by_width}, rule, tol)
 
 
 def profile_pipeline(P: binding.Pipeline, widths: Sequence[int] = (64, 128, 256), iters: int = 2,
@@ -200,7 +138,7 @@ def plan(specs, profiles: List[List[ModelProfile]], frame_rates: Sequence[float]
                 models.append(dict(parent=parent.get(mi, -1), profile=dict(lat), rate=max(rate, 1e-3),
                                    burstiness=burstiness[i][mi], util=w / total, weight_mem=wmem, inter_mem=0.0, bz=1))
             bzs = binding.cwd_search(models, spec.slo_ms) if fixed_bz is None else list(fixed_bz[i])
-            ks = [max(1, int(math.ceil(m["rate"] * duty / 1000.0 / b - 1e-9))) for m, b in zip(models, bzs)]
+            ks = [binding.batches_per_cycle(m["rate"], duty, b) for m, b in zip(models, bzs)]
             work = sum(k * m["profile"][b] for m, b, k in zip(models, bzs, ks))
             if work <= cycle_share * duty or w_floor == widths[-1]:
                 break

@@ -1,9 +1,55 @@
-"""Host logic of the slot executor that needs no GPU: lazy dropping of late requests, the run-time scaling decision,
-the property of the portion scheduler the scaler relies on, and the surge in the synthetic arrivals."""
+"""Host logic of the slot executor that needs no GPU, through the C ABI: the run-time rules (burstiness, batches per
+cycle, widths, lazy dropping, the scaling decision) equal the oracle's on hand cases and on random inputs; the property
+of the portion scheduler the scaler relies on; the surge in the synthetic arrivals."""
 import numpy as np
 
-from oracle import sched
+from oracle import runtime as ort, sched
 from paper_2502_01277_amd import binding, executor, synth
+
+
+# ---- the library's run-time rules against the oracle's (exact equality) ----
+def test_runtime_rules_equal_the_oracle_on_random_inputs():
+    rng = np.random.default_rng(11)
+    for _ in range(300):
+        n = int(rng.integers(0, 40))
+        t = np.round(rng.uniform(0, 10, n), 3)
+        if n and rng.random() < 0.3:
+            t[rng.integers(0, n, n // 2)] = t[0]                     # bursts: equal arrival times
+        assert abs(binding.burstiness(t) - ort.burstiness(t.tolist())) <= 1e-12
+        rate, duty, bz = float(rng.uniform(0, 2000)), float(rng.choice([25.0, 50.0, 100.0])), int(2 ** rng.integers(0, 7))
+        assert binding.batches_per_cycle(rate, duty, bz) == ort.batches_per_cycle(rate, duty, bz)
+        util, total = float(rng.uniform(0, 1.2)), int(rng.choice([64, 256, 304]))
+        assert binding.width_to_cus(util, total, 8) == ort.width_to_cus(util, total, 8)
+        lat = {int(w): float(rng.uniform(0.5, 20)) for w in rng.choice([8, 16, 32, 64, 128, 256], size=int(rng.integers(1, 5)), replace=False)}
+        for rule in ("efficient", "latency"):
+            assert binding.choose_width(lat, rule, 0.1) == ort.choose_width(lat, rule, 0.1), (lat, rule)
+        arr = np.sort(rng.uniform(0, 1000, n))
+        now, slo = float(rng.uniform(0, 1200)), float(rng.choice([50.0, 200.0]))
+        assert binding.late_prefix(arr, now, slo) == ort.late_prefix(arr.tolist(), now, slo)
+    assert binding.batches_per_cycle(160.0, 100.0, 16) == 1 and binding.batches_per_cycle(161.0, 100.0, 16) == 2
+    assert binding.width_to_cus(0.26, 256) == 72 and binding.choose_width({64: 10.0, 128: 3.0, 256: 3.0}) == 128
+
+
+def test_scaler_equals_the_oracle_on_random_sequences():
+    rng = np.random.default_rng(12)
+    for _ in range(60):
+        cap, win = float(rng.integers(4, 64)), int(rng.integers(1, 7))
+        up, down, mx = float(rng.uniform(0.8, 1.3)), float(rng.uniform(0.3, 0.79)), int(rng.integers(1, 4))
+        a, b = binding.Scaler(cap, win, up, down, mx), ort.Scaler(cap, win, up, down, mx)
+        n_active = 1
+        for _ in range(80):
+            arrived, backlog = int(rng.integers(0, 3 * cap)), int(rng.integers(0, 3 * cap))
+            da, db = a.observe(arrived, backlog, n_active), b.observe(arrived, backlog, n_active)
+            assert da == db
+            n_active += da
+            assert 1 <= n_active <= max(1, mx)
+        a.close()
+    for bad in ((0.0, 5, 1.0, 0.75, 2), (8.0, 0, 1.0, 0.75, 2), (8.0, 5, 0.5, 0.75, 2), (8.0, 5, 1.0, 0.75, 0)):
+        try:
+            binding.Scaler(*bad)
+            assert False, bad
+        except binding.OctoError:
+            pass
 
 
 # ---- lazy dropping (Sec. IV-A) ----
