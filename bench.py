@@ -57,8 +57,10 @@ def conv_name(kid: int, dtype: str) -> str:
     """Template instance behind a conv kernel id (digits 1 BBB PPP K M V), as rocprofv3 prints it."""
     d = kid - 1000000000
     ctype = {"f16": "_Float16", "bf16": "__bf16", "f32": "float"}[dtype]
-    if 700000000 <= d < 800000000:                       # wide 3x3 kernel: digits BBB TTT (channel tile, tile width)
-        return "octo::conv3x3_big_kernel<%s, %d, 4>" % (ctype, ((d - 700000000) // 1000) // 64)
+    if 700000000 <= d < 800000000:                       # wide 3x3 kernel: digits P BBB TTT (512-pixel tile, channel tile, tile width)
+        bc = ((d - 700000000) // 1000) % 1000
+        tc, tp, wc = (3, 4, 1) if bc == 96 else (bc // 64, 4, 2)
+        return "octo::conv3x3_big_kernel<%s, %d, %d, %d, 4>" % (ctype, tc, tp, wc)
     if 800000000 <= d < 900000000:                       # 3x3 kernel with the input patch in LDS: channel slice
         return "octo::conv3x3_patch_kernel<%s, %d, %d>" % (ctype, (d - 800000000) % 1000, (d - 800000000) // 1000)
     if d >= 900000000:                                   # first-layer kernel: digits BBB KK P

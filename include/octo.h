@@ -259,7 +259,7 @@ octo_status octo_profile_layers(octo_pipeline* p, int32_t model, int32_t n, int3
  * duration, from events attached to its dispatch; other layers: end of layer i-1 to end of layer i on the stream,
  * which includes the launch gap), kernel_id[i] = which kernel ran it (general convolution: decimal digits
  * 1 BBB PPP K M V = channel tile, pixel tile, 16-byte vectors per K step, workgroups per CU, V = vectorised gather
- * + 2 if operands go straight to LDS; 17 00 BBB TTT: wide 3x3 kernel, channel tile BBB, tile width TTT;
+ * + 2 if operands go straight to LDS; 17 0P BBB TTT: wide 3x3 kernel, channel tile BBB, tile width TTT, P = 1 for 512-pixel tiles (else 256);
  * 18 00 BBB 0 SS: 3x3 kernel with the input patch in LDS, channel tile BBB and
  * channel slice SS; 19 00 BBB KK P: first-layer kernel, channel tile, kernel height, kernel width in pixel pairs;
  * 1 max-pool, 2 upsample, 3 channel copy, 4 add, 5 global average pool, 0 none), per ITEM dense FLOPs and activation

@@ -1,12 +1,12 @@
-// 3x3 / stride-1 convolution for wide layers (128 and more output channels) on the matrix cores, with the input
+// 3x3 / stride-1 convolution for wide layers (about 96 and more output channels) on the matrix cores, with the input
 // patch of a tile resident in LDS.
 //
 // What paces the general implicit-GEMM kernel (conv.hip) on such layers is the vector-memory path: measured on
 // MI355X, global -> LDS loads of scattered 64..128-byte pieces run at 23..30 bytes per clock and compute unit however
 // deep they are queued, while a 128 x 128 tile needs 64 bytes per clock at the full MFMA rate (a 256 x 256 tile 32).
 // A 3x3 layer fetches every input pixel nine times there, once per kernel tap.  Here
-//   * a tile is TH x TW output pixels (up to 256) of the image stack - the images of the batch stacked vertically, so a
-//     tile may span several small images - times BC = 128 / 192 / 256 output channels;
+//   * a tile is TH x TW output pixels (up to 256, or 512 with the narrow channel tile) of the image stack - the images
+//     of the batch stacked vertically, so a tile may span several small images - times BC = 96 / 192 / 256 output channels;
 //   * the K loop runs slice-major: for every slice of 32 input channels, the nine taps in turn.  The input patch of a
 //     slice (the tile's rows and columns plus a one-pixel border, 64 bytes per pixel, zero outside the images) is
 //     loaded once into one of two LDS buffers and the MFMA pixel operand of every tap is read from it with a shifted
@@ -15,8 +15,8 @@
 //   * loads run NST steps ahead of the arithmetic and continuously across tiles (while the last steps of a tile are
 //     multiplied the ring already receives the next tile's weights and patch), the one barrier per step sits in the
 //     middle of the step's MFMAs, and the epilogue writes from registers, so LDS never has to drain between tiles;
-//   * four wavefronts per workgroup, each on (BC / 2) x 128 outputs: up to 16 accumulator blocks of 32 x 32 in the AGPR
-//     half of the register file, 8 operand fragments per 16 MFMAs;
+//   * four wavefronts per workgroup, each on (BC / 2) x 128 outputs (96 x 128 with the 96-channel tile): up to 16
+//     accumulator blocks of 32 x 32 in the AGPR half of the register file, 7 or 8 operand fragments per 12 or 16 MFMAs;
 //   * the bias of a tile arrives in LDS through the same load stream (one 4-byte load per lane and step).
 // LDS rows (weights: one output channel; patch: one pixel) are 64 bytes = four 16-byte vectors; vector v of row r sits
 // in slot v ^ ((r / 4) % 4), which makes both the 1 KB-contiguous fills and the fragment reads (32 consecutive rows,
@@ -56,28 +56,34 @@ template <> struct Mfma16<__bf16> {
 };
 }  // namespace
 
-// TC: 32-channel blocks per wavefront (two wavefronts along the channels: BC = 64 * TC); every wavefront covers 128
-// pixels (4 blocks; two wavefronts along the pixels: 256 per tile).  NST: stages of the weight ring.
-template <typename T, int TC, int NST>
+// A wavefront computes TC x TP blocks of 32 channels x 32 pixels; the four wavefronts of a workgroup are laid out WC along
+// the channels and 4 / WC along the pixels, so a tile has BC = 32 * TC * WC channels and BP = 32 * TP * 4 / WC pixels
+// (256 or 512).  NST: stages of the weight ring.
+template <typename T, int TC, int TP, int WC, int NST>
 __global__ __launch_bounds__(THREADS, 1) void conv3x3_big_kernel(const ConvArgs a, const BigGeom gm) {
   static_assert(sizeof(T) == 2, "16-bit storage types");
-  constexpr int VN = 8, ES = 2, KV = 4, BK = KV * VN, TP = 4, WC = 2;
-  constexpr int BC = TC * WC * 32, BP = 256;
+  constexpr int VN = 8, ES = 2, KV = 4, BK = KV * VN, WP = 4 / WC;
+  constexpr int BC = TC * WC * 32, BP = TP * WP * 32;
+  static_assert(BP == 256 || BP == 512, "tile of 256 or 512 pixels");
   constexpr int RP = THREADS / KV;         // 64 rows per 4 KB pass of the 256 loader lanes
-  constexpr int LA = BC / RP;
-  // loads per wavefront in the step whose loader tap is t: LA of weights; at taps NST .. NST + 3 two passes of the next
-  // slice's patch (8 passes cover the largest patch); at the last tap the tile's bias
-  constexpr auto nlt = [](int t) constexpr { return LA + ((t >= NST && t < NST + 4) ? 2 : 0) + (t == 8 ? 1 : 0); };
-  constexpr unsigned ROW_BYTES = KV * 16, STAGE_BYTES = BC * ROW_BYTES, PASS_BYTES = RP * ROW_BYTES;
+  constexpr int LA = (BC + RP - 1) / RP;
+  // patch passes per step (PPT) at the four loader taps NST .. NST + 3: 8 passes (32 KB) cover the largest patch of a
+  // 256-pixel tile, 16 that of a 512-pixel tile
+  constexpr int PPT = BP / 128, MAXP = 4 * PPT;
+  // loads per wavefront in the step whose loader tap is t: LA of weights; at taps NST .. NST + 3 PPT passes of the next
+  // slice's patch; at the last tap the tile's bias
+  constexpr auto nlt = [](int t) constexpr { return LA + ((t >= NST && t < NST + 4) ? PPT : 0) + (t == 8 ? 1 : 0); };
+  constexpr unsigned ROW_BYTES = KV * 16, STAGE_BYTES = LA * RP * ROW_BYTES, PASS_BYTES = RP * ROW_BYTES;
   constexpr int N_TAPS = 9;
-  static_assert(NST >= 3 && NST <= 4 && (NST - 1) * (LA + 2) + 8 <= 63, "patch passes at taps NST .. NST + 3; vmcnt has six bits");
+  static_assert(NST >= 3 && NST <= 4 && (NST - 1) * (LA + PPT) + MAXP <= 63, "patch passes at taps NST .. NST + 3; vmcnt has six bits");
+  static_assert(TC * TP >= TC + TP + 1, "a half step has room for its operand reads");
 
   extern __shared__ __attribute__((aligned(1024))) unsigned char dyn_lds[];
   unsigned char* ring = dyn_lds;                                   // NST stages of BC x 64 bytes
   unsigned char* patch = dyn_lds + NST * STAGE_BYTES;              // 2 buffers of gm.patch_bytes
   float* sBias = (float*)(patch + 2 * gm.patch_bytes);             // 2 x 256 floats
-  int* sPoff = (int*)(sBias + 2 * THREADS);                        // [8][256]: every lane's patch offsets (own column only)
-  unsigned char* dump = (unsigned char*)(sPoff + 8 * THREADS);     // 4 KB that the placeholder loads (zeros) land in
+  int* sPoff = (int*)(sBias + 2 * THREADS);                        // [MAXP][256]: every lane's patch offsets (own column only)
+  unsigned char* dump = (unsigned char*)(sPoff + MAXP * THREADS);  // 4 KB that the placeholder loads (zeros) land in
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -150,7 +156,8 @@ __global__ __launch_bounds__(THREADS, 1) void conv3x3_big_kernel(const ConvArgs 
     int c0, x0, v0;
     tile_origin(lt, c0, x0, v0);
 #pragma unroll
-    for (int i = 0; i < LA; ++i) woff[i] = ((c0 + ld_row + RP * i) * a.Kp + lkv * VN) * ES;     // rows past the matrix: out of range, zeros
+    for (int i = 0; i < LA; ++i)             // rows past the tile or the matrix: out of range, zeros
+      woff[i] = ld_row + RP * i < BC ? ((c0 + ld_row + RP * i) * a.Kp + lkv * VN) * ES : OOB;
     boff = tid < BC ? (c0 + tid) * 4 : OOB;
   };
 
@@ -159,11 +166,13 @@ __global__ __launch_bounds__(THREADS, 1) void conv3x3_big_kernel(const ConvArgs 
   int pslice = 0, ppar = 0;                // its slice, and the patch buffer it goes to
   // sPoff[i][tid]: byte offset of this lane's vector of pass i from the tile's first image (or OOB); kept in LDS, every
   // lane reads only what it wrote itself, so no barrier is involved
-  __amdgpu_buffer_rsrc_t rsrc_p = rsrc_w;
+  // the patch's buffer descriptor (base: the first image the patch touches) is rebuilt from these three uniform words
+  // where a load is issued, which keeps them in scalar registers whatever the register pressure
+  int p_lo = 0, p_hi = 0, p_len = 0;
   auto ploader_setup = [&]() {
     if (pt >= t_end) {
 #pragma unroll
-      for (int i = 0; i < 8; ++i) sPoff[i * THREADS + tid] = OOB;
+      for (int i = 0; i < MAXP; ++i) sPoff[i * THREADS + tid] = OOB;
       return;
     }
     int c0, x0, v0;
@@ -173,9 +182,10 @@ __global__ __launch_bounds__(THREADS, 1) void conv3x3_big_kernel(const ConvArgs 
     const int patch_px = (P1 - P0 + 1) * gm.PW;
     const int img0 = (int)fast_div((unsigned)P0, gm.div_hp2);
     const long long rem_bytes = ((long long)(a.n - img0) * img_elems - a.x_coff) * ES;
-    rsrc_p = __builtin_amdgcn_make_buffer_rsrc((void*)(xg + (long long)img0 * img_elems), 0, (int)(rem_bytes < BUF_MAX ? rem_bytes : BUF_MAX), BUF_FLAGS);
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
+    const uintptr_t pbase = (uintptr_t)(xg + (long long)img0 * img_elems);
+    p_lo = (int)(unsigned)pbase; p_hi = (int)(unsigned)(pbase >> 32); p_len = (int)(rem_bytes < BUF_MAX ? rem_bytes : BUF_MAX);
+#pragma unroll 1
+    for (int i = 0; i < MAXP; ++i) {
       const int j = i * THREADS + tid;     // vector of the patch buffer this lane fills in pass i
       const int pp = j >> 2;               // patch pixel; its slot j & 3 holds logical vector slot ^ ((pp / 4) % 4)
       const int vec = (j & 3) ^ ((pp >> 2) & 3);
@@ -209,8 +219,10 @@ __global__ __launch_bounds__(THREADS, 1) void conv3x3_big_kernel(const ConvArgs 
   auto issue_patch_pass = [&](int pass, int off) {
     // a load to LDS always writes (zeros when out of range): placeholders go to the dump
     const unsigned dst = pass >= 0 && pass < gm.PL ? lds_patch + (unsigned)ppar * (unsigned)gm.patch_bytes + (unsigned)pass * 4096u : lds_dump;
+    const uintptr_t base = (uintptr_t)(unsigned)__builtin_amdgcn_readfirstlane(p_lo) | ((uintptr_t)(unsigned)__builtin_amdgcn_readfirstlane(p_hi) << 32);
+    const __amdgpu_buffer_rsrc_t rsrc_p = __builtin_amdgcn_make_buffer_rsrc((void*)base, 0, __builtin_amdgcn_readfirstlane(p_len), BUF_FLAGS);
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
-                 :: "s"(dst), "v"(off), "s"(rsrc_p) : "memory");
+                 :: "s"(__builtin_amdgcn_readfirstlane((int)dst)), "v"(off), "s"(rsrc_p) : "memory");
   };
   auto issue_bias = [&]() {
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dword %1, %2, 0 offen lds"
@@ -229,8 +241,8 @@ __global__ __launch_bounds__(THREADS, 1) void conv3x3_big_kernel(const ConvArgs 
   wloader_setup();
   // patch of (first tile, slice 0): all passes up front, then the patch loader moves on to slice 1
   ploader_setup();
-#pragma unroll
-  for (int i = 0; i < 8; ++i) issue_patch_pass(i, patch_offset(i));
+#pragma unroll 1
+  for (int i = 0; i < MAXP; ++i) issue_patch_pass(i, patch_offset(i));
   ploader_next();
 #pragma unroll
   for (int d = 0; d < NST; ++d) {          // taps 0 .. NST - 1 of the first tile: weights only (nk >= 9 > NST)
@@ -254,7 +266,7 @@ __global__ __launch_bounds__(THREADS, 1) void conv3x3_big_kernel(const ConvArgs 
     const int tile_px = gm.TH * gm.TW;
 #pragma unroll
     for (int j = 0; j < TP; ++j) {
-      const int q = wp * (BP / 2) + j * 32 + l32;
+      const int q = wp * (TP * 32) + j * 32 + l32;
       const int ty = (int)fast_div((unsigned)q, gm.div_tw), tx = q - ty * gm.TW;
       const int v = v0 + ty;
       const bool ok = q < tile_px && v < n_rows;
@@ -269,7 +281,7 @@ __global__ __launch_bounds__(THREADS, 1) void conv3x3_big_kernel(const ConvArgs 
   };
   consumer_setup();
 
-  const unsigned fa_base = (unsigned)((wc * (BC / WC) + l32) * ROW_BYTES);
+  const unsigned fa_base = (unsigned)((wc * (TC * 32) + l32) * ROW_BYTES);
   const unsigned sl0 = (((unsigned)g) ^ rsw) * 16u, sl1 = ((2u + (unsigned)g) ^ rsw) * 16u;
   floatx16 acc[TC][TP];
   u32x4 fa0[TC], fb0[TP], fa1[TC], fb1[TP];
@@ -304,7 +316,7 @@ __global__ __launch_bounds__(THREADS, 1) void conv3x3_big_kernel(const ConvArgs 
     // loads still allowed in flight when the next step's operands must have landed: those of the NST - 2 steps after it
     constexpr int IN_FLIGHT = nlt((TAP + 2) % N_TAPS) + (NST > 3 ? nlt((TAP + 3) % N_TAPS) : 0);
     constexpr bool PATCH = LTAP >= NST && LTAP < NST + 4;
-    constexpr int PASS0 = PATCH ? 2 * (LTAP - NST) : -2;
+    constexpr int PASS0 = PATCH ? PPT * (LTAP - NST) : -PPT;
     constexpr int LAST = TC * TP - 1;
     auto slot = [](int i) constexpr { return TC + TP + i < LAST ? TC + TP + i : LAST; };    // MFMA after which load i of the step is issued
     {
@@ -334,8 +346,9 @@ __global__ __launch_bounds__(THREADS, 1) void conv3x3_big_kernel(const ConvArgs 
       }
     }
     {
-      int poff0 = OOB, poff1 = OOB;
-      if (PATCH) { poff0 = patch_offset(PASS0); poff1 = patch_offset(PASS0 + 1); }
+      int poff[PPT];
+#pragma unroll
+      for (int i = 0; i < PPT; ++i) poff[i] = PATCH ? patch_offset(PASS0 + i) : OOB;
       __builtin_amdgcn_sched_barrier(0);
       const unsigned char* sa = ring + (unsigned)rd * STAGE_BYTES + fa_base + sl0;
       const unsigned char* sb = patch + (unsigned)cbuf * (unsigned)gm.patch_bytes;
@@ -347,8 +360,9 @@ __global__ __launch_bounds__(THREADS, 1) void conv3x3_big_kernel(const ConvArgs 
 #pragma unroll
         for (int i = 0; i < LA; ++i)
           if (m == slot(i)) issue_weight(st_free, LTAP, i);
-        if (PATCH && m == slot(LA)) issue_patch_pass(PASS0, poff0);
-        if (PATCH && m == slot(LA + 1)) issue_patch_pass(PASS0 + 1, poff1);
+#pragma unroll
+        for (int i = 0; i < PPT; ++i)
+          if (PATCH && m == slot(LA + i)) issue_patch_pass(PASS0 + i, poff[i]);
         if (LTAP == N_TAPS - 1 && m == slot(LA)) issue_bias();
         __builtin_amdgcn_sched_barrier(0);
       }
@@ -384,7 +398,7 @@ __global__ __launch_bounds__(THREADS, 1) void conv3x3_big_kernel(const ConvArgs 
       const size_t p = (size_t)epix[j];
 #pragma unroll
       for (int i = 0; i < TC; ++i) {
-        const int cblk = wc * (BC / WC) + i * 32 + g * 4;
+        const int cblk = wc * (TC * 32) + i * 32 + g * 4;
         const T* rp = a.res ? (const T*)a.res + p * a.res_ld + a.res_coff + ec0 + cblk : nullptr;
         T* yp = (T*)a.y + p * a.y_ld + a.y_coff + ec0 + cblk;
         if (vec_ok && ec0 + cblk + 28 <= a.Cout) {
@@ -434,29 +448,29 @@ __global__ __launch_bounds__(THREADS, 1) void conv3x3_big_kernel(const ConvArgs 
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 }
 
-// Tile shape for a W-wide image: a divisor TW of W (at most 64) with TH = 256 / TW; among the shapes that fill the
-// 256-pixel tile to within 10 % of the best one, the one with the smallest patch.  False if no shape fills at least
-// 3/4 of the tile or the patch would not fit.
-inline bool big_geometry(int H, int W, int tiles_c, BigGeom* gm) {
+// Tile shape for a W-wide image and a tile of BP pixels: a divisor TW of W (at most 64) with TH = BP / TW; among the
+// shapes that fill the tile to within 10 % of the best one, the one with the smallest patch.  False if no shape fills
+// at least 3/4 of the tile or the patch needs more than BP / 32 passes of 4 KB.
+inline bool big_geometry(int H, int W, int tiles_c, int BP, BigGeom* gm) {
   int best_px = 0;
   for (int tw = W < 64 ? W : 64; tw >= 4; --tw)
-    if (W % tw == 0 && (256 / tw) * tw > best_px) best_px = (256 / tw) * tw;
-  if (best_px < 192) return false;
+    if (W % tw == 0 && (BP / tw) * tw > best_px) best_px = (BP / tw) * tw;
+  if (best_px * 4 < BP * 3) return false;
   int best_tw = 0, best_patch = 1 << 30;
   for (int tw = W < 64 ? W : 64; tw >= 4; --tw) {
     if (W % tw) continue;
-    const int th = 256 / tw;
+    const int th = BP / tw;
     if (th * tw * 10 < best_px * 9) continue;
     const int patch = (th + 2 + 2 * ((th - 1 + H - 1) / H)) * (tw + 2);
     if (patch < best_patch) { best_patch = patch; best_tw = tw; }
   }
-  gm->TW = best_tw; gm->TH = 256 / best_tw; gm->PW = best_tw + 2; gm->tiles_x = W / best_tw;
+  gm->TW = best_tw; gm->TH = BP / best_tw; gm->PW = best_tw + 2; gm->tiles_x = W / best_tw;
   // most patch rows a tile can need: its TH rows, one above and below, and two more per image boundary inside it
   const int crossings = (gm->TH - 1 + H - 1) / H;
   const int rows = gm->TH + 2 + 2 * crossings;
   const int vecs = rows * gm->PW * 4;
   gm->PL = (vecs + THREADS - 1) / THREADS;
-  if (gm->PL > 8) return false;
+  if (gm->PL > BP / 32) return false;
   gm->patch_bytes = gm->PL * 4096;
   gm->div_tw = make_fastdiv((unsigned)gm->TW); gm->div_pw = make_fastdiv((unsigned)gm->PW);
   gm->div_h = make_fastdiv((unsigned)H); gm->div_hp2 = make_fastdiv((unsigned)(H + 2));
@@ -464,36 +478,43 @@ inline bool big_geometry(int H, int W, int tiles_c, BigGeom* gm) {
   return true;
 }
 
+// dynamic LDS of a configuration: weight ring, two patch buffers, two bias buffers, the lanes' patch offsets, the dump
+inline size_t big_lds_bytes(int BC, int BP, int NST, const BigGeom& gm) {
+  return (size_t)NST * ((BC + 63) / 64 * 64) * 64 + 2 * (size_t)gm.patch_bytes + 2 * THREADS * sizeof(float) +
+         (size_t)(BP / 32) * THREADS * sizeof(int) + 4096;
+}
+
 #ifndef OCTO_CONV_NO_LAUNCHERS
 namespace {
 
-template <typename T, int TC, int NST>
+template <typename T, int TC, int TP, int WC, int NST>
 hipError_t launch_big_cfg(const ConvArgs& a, int num_cu, hipStream_t s, int* kernel_id, const ConvTiming& tm) {
-  constexpr int BC = TC * 64;
+  constexpr int BC = TC * WC * 32, BP = TP * (4 / WC) * 32;
   const int tiles_c = (a.Cout + BC - 1) / BC;
   BigGeom gm{};
-  if (!big_geometry(a.H, a.W, tiles_c, &gm)) return hipErrorNotSupported;
+  if (!big_geometry(a.H, a.W, tiles_c, BP, &gm)) return hipErrorNotSupported;
   const long long n_rows = (long long)a.n * a.H;
   const long long tiles = ((n_rows + gm.TH - 1) / gm.TH) * gm.tiles_x * tiles_c;
   if (tiles <= 0) return hipSuccess;
   if (tiles >= 0x7FFFFFF0LL || n_rows * a.W >= 0x7FFFFFFFLL) return hipErrorNotSupported;
   // a patch is addressed with 32-bit byte offsets from the first image it touches
   if (((long long)(gm.TH + 2) / a.H + 3) * a.H * a.W * a.x_ld * 2 > 0x7FFFFFF0LL) return hipErrorNotSupported;
-  const size_t lds = (size_t)NST * BC * 64 + 2 * (size_t)gm.patch_bytes + 2 * THREADS * sizeof(float) + 8 * THREADS * sizeof(int) + 4096;
+  const size_t lds = big_lds_bytes(BC, BP, NST, gm);
+  if (lds > 160 * 1024) return hipErrorNotSupported;
   static bool attr_set = false;            // more than 64 KB of dynamic LDS needs the attribute (once per instantiation)
   if (!attr_set) {
-    (void)hipFuncSetAttribute((const void*)conv3x3_big_kernel<T, TC, NST>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+    (void)hipFuncSetAttribute((const void*)conv3x3_big_kernel<T, TC, TP, WC, NST>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
     (void)hipGetLastError();
     attr_set = true;
   }
-  if (kernel_id) *kernel_id = 1700000000 + BC * 1000 + gm.TW;
+  if (kernel_id) *kernel_id = 1700000000 + (BP / 512) * 1000000 + BC * 1000 + gm.TW;
   long long grid = (tiles + 7) / 8 * 8;
   const long long cap = ((long long)num_cu + 7) / 8 * 8;
   if (grid > cap) grid = cap;
   if (tm.start && tm.stop)
-    hipExtLaunchKernelGGL((conv3x3_big_kernel<T, TC, NST>), dim3((unsigned)grid), dim3(THREADS), (unsigned)lds, s, tm.start, tm.stop, 0, a, gm);
+    hipExtLaunchKernelGGL((conv3x3_big_kernel<T, TC, TP, WC, NST>), dim3((unsigned)grid), dim3(THREADS), (unsigned)lds, s, tm.start, tm.stop, 0, a, gm);
   else
-    hipLaunchKernelGGL((conv3x3_big_kernel<T, TC, NST>), dim3((unsigned)grid), dim3(THREADS), (unsigned)lds, s, a, gm);
+    hipLaunchKernelGGL((conv3x3_big_kernel<T, TC, TP, WC, NST>), dim3((unsigned)grid), dim3(THREADS), (unsigned)lds, s, a, gm);
   return hipGetLastError();
 }
 
@@ -501,16 +522,20 @@ template <typename T>
 hipError_t launch_big_typed(const ConvArgs& a, int num_cu, hipStream_t s, int* kernel_id, const ConvTiming& tm) {
   // channel tile: the one that pads the channel count least, ties to the larger
   int best_bc = 0, best_pad = 1 << 30;
-  for (int bc : {256, 192, 128}) {
+  for (int bc : {256, 192, 96}) {
     const int pad = (a.Cout + bc - 1) / bc * bc;
     if (pad < best_pad) { best_pad = pad; best_bc = bc; }
   }
   if (best_pad * 4 > a.Cout * 5) return hipErrorNotSupported;     // more than a fifth of the MFMAs would be padding
-  // measured on MI355X: with 128-channel tiles (64 x 128 outputs per wavefront) this kernel does not beat the general one
+  // enough tiles to give every compute unit two rounds (below that the general kernel's smaller tiles spread better)
+  const long long m_hint = (long long)(a.n_hint > 0 && a.n_hint < a.n ? a.n_hint : a.n) * a.H * a.W;
+  const long long tiles_hint = m_hint / (best_bc == 96 ? 512 : 256) * ((a.Cout + best_bc - 1) / best_bc);
+  if (tiles_hint < 2LL * num_cu) return hipErrorNotSupported;
+  // measured on MI355X: 128 channels x 512 pixels (and 64 x 512) do not beat the general kernel, 96 x 512 does
   switch (best_bc) {
-    case 256: return launch_big_cfg<T, 4, 4>(a, num_cu, s, kernel_id, tm);
-    case 192: return launch_big_cfg<T, 3, 4>(a, num_cu, s, kernel_id, tm);
-    default: return hipErrorNotSupported;
+    case 256: return launch_big_cfg<T, 4, 4, 2, 4>(a, num_cu, s, kernel_id, tm);
+    case 192: return launch_big_cfg<T, 3, 4, 2, 4>(a, num_cu, s, kernel_id, tm);
+    default: return launch_big_cfg<T, 3, 4, 1, 4>(a, num_cu, s, kernel_id, tm);       // 96 channels x 512 pixels
   }
 }
 
@@ -520,11 +545,8 @@ hipError_t launch_big_typed(const ConvArgs& a, int num_cu, hipStream_t s, int* k
 hipError_t launch_conv3x3_big(int dtype, const ConvArgs& a, int num_cu, hipStream_t s, int* kernel_id, ConvTiming tm) {
   if (dtype != OCTO_F16 && dtype != OCTO_BF16) return hipErrorNotSupported;
   if (a.out_f32 || a.pair_view || a.kh != 3 || a.kw != 3 || a.stride_h != 1 || a.stride_w != 1 || a.pad_h != 1 || a.pad_w != 1) return hipErrorNotSupported;
-  if (a.Cin % 32 || a.x_ld % 8 || a.x_coff % 8 || ((uintptr_t)a.x & 15) || a.Cout < 160) return hipErrorNotSupported;
+  if (a.Cin % 32 || a.x_ld % 8 || a.x_coff % 8 || ((uintptr_t)a.x & 15) || a.Cout < 80) return hipErrorNotSupported;
   if (a.Ho != a.H || a.Wo != a.W) return hipErrorNotSupported;
-  // enough tiles to give every compute unit two rounds (below that the general kernel's smaller tiles spread better)
-  const long long m_hint = (long long)(a.n_hint > 0 && a.n_hint < a.n ? a.n_hint : a.n) * a.H * a.W;
-  if (m_hint * ((a.Cout + 255) / 256) < 2LL * num_cu * 256) return hipErrorNotSupported;
   switch (dtype) {
     case OCTO_F16: return launch_big_typed<_Float16>(a, num_cu, s, kernel_id, tm);
     case OCTO_BF16: return launch_big_typed<__bf16>(a, num_cu, s, kernel_id, tm);

@@ -223,20 +223,22 @@ def test_3x3_64_channel_layers_on_wide_maps(octo, dtype):
 
 
 BIG3X3_CASES = [
-    # (h, w, cin, cout, batch, layers expected on the wide kernel): 3x3 / stride-1 layers with at least 160 output channels, input
-    # channels in slices of 32, and enough pixels
+    # (h, w, cin, cout, batch, layers expected on the wide kernel): 3x3 / stride-1 layers with 80..96 or at least 160 output
+    # channels, input channels in slices of 32, and enough pixels
     (30, 30, 32, 544, 50, 3),     # 192-channel tiles x 3 (ragged last tile: 544 = 2 x 192 + 160), tile 25 x 10, 1 and 17 channel slices
     (14, 14, 64, 256, 700, 3),    # 256-channel tiles, tiles span image boundaries (18 stack rows of 14-wide images)
     (7, 7, 96, 192, 2700, 3),     # 7 x 7 images: 36 stack rows per tile = five images and a bit, 192-channel tiles
     (23, 34, 32, 224, 180, 3),    # odd height, tile width 17, 224 of a 256-channel tile used
     (20, 20, 64, 208, 330, 1),    # channel tail inside a 32-block (208 = 6 x 32 + 16); the next layers (208 input channels) take the general kernel
+    (40, 40, 32, 96, 330, 3),     # 96-channel tiles of 512 pixels (25 x 20), one wavefront column
+    (18, 36, 64, 88, 460, 1),     # 88 of a 96-channel tile, 28 stack rows x 18 columns: a tile spans image boundaries
 ]
 
 
 @pytest.mark.parametrize("dtype", ["f16", "bf16"])
 @pytest.mark.parametrize("case", BIG3X3_CASES)
 def test_wide_3x3_kernel_parity(octo, dtype, case):
-    """The wide 3x3 kernel (input patch in LDS, 192 / 256-channel tiles) against the oracle: SiLU layer, then a ReLU layer
+    """The wide 3x3 kernel (input patch in LDS, 96 / 192 / 256-channel tiles) against the oracle: SiLU layer, then a ReLU layer
     with the residual added before the activation, then a SiLU layer with the residual added after it; sampled output
     positions from every image region (corners, borders, image boundaries inside a tile, the last items)."""
     h, w, cin, cout, n, n_wide = case
