@@ -64,8 +64,8 @@ def conv_name(kid: int, dtype: str) -> str:
     if 800000000 <= d < 900000000:                       # 3x3 kernel with the input patch in LDS: channel slice
         return "octo::conv3x3_patch_kernel<%s, %d, %d>" % (ctype, (d - 800000000) % 1000, (d - 800000000) // 1000)
     if d >= 900000000:                                   # first-layer kernel: digits BBB KK P
-        d -= 900000000
-        return "octo::stem_conv_kernel<%s, %d, %d, %d>" % (ctype, d // 1000, (d // 10) % 100, d % 10)
+        d -= 900000000                                   # F BBB KK P: F = 1 with the following max-pool fused
+        return "octo::stem_conv_kernel<%s, %d, %d, %d, %s>" % (ctype, (d // 1000) % 1000, (d // 10) % 100, d % 10, "true" if d >= 1000000 else "false")
     bc, bp, kv, minb, v = d // 1000000, (d // 1000) % 1000, (d // 100) % 10, (d // 10) % 10, d % 10
     vec, dma = v & 1, v >> 1
     wc, wp = (1, 4) if (bc == 32 or bp == 256) else (2, 2)

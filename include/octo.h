@@ -115,7 +115,11 @@ typedef struct {
   int32_t max_rois_per_frame;                         /* per-edge ROI capacity = max_frames * max_rois_per_frame */
   int32_t max_queue;                                  /* submitted-but-not-run frames; 0 = 4 * max_frames */
   int32_t keep_all_tensors;                           /* != 0: every tensor gets its own memory, so octo_debug_get_tensor can
-                                                         read any of them after a run (otherwise only model outputs are safe) */
+                                                         read any of them after a run (otherwise only model outputs are safe).
+                                                         1: and every layer runs on its own, so every tensor is written;
+                                                         2: layers are fused as in normal operation (a first layer followed by
+                                                         a 3x3 / stride-2 max-pool writes only the pooled tensor; the tensor
+                                                         in between then holds nothing) */
 } octo_pipeline_desc;
 
 typedef struct octo_pipeline octo_pipeline;
@@ -261,7 +265,8 @@ octo_status octo_profile_layers(octo_pipeline* p, int32_t model, int32_t n, int3
  * 1 BBB PPP K M V = channel tile, pixel tile, 16-byte vectors per K step, workgroups per CU, V = vectorised gather
  * + 2 if operands go straight to LDS; 17 0P BBB TTT: wide 3x3 kernel, channel tile BBB, tile width TTT, P = 1 for 512-pixel tiles (else 256);
  * 18 00 BBB 0 SS: 3x3 kernel with the input patch in LDS, channel tile BBB and
- * channel slice SS; 19 00 BBB KK P: first-layer kernel, channel tile, kernel height, kernel width in pixel pairs;
+ * channel slice SS; 19 0F BBB KK P: first-layer kernel, channel tile, kernel height, kernel width in pixel pairs,
+ * F = 1 when it also computes the 3x3 / stride-2 max-pool that follows (that layer then reports kernel 0 and 0 ms);
  * 1 max-pool, 2 upsample, 3 channel copy, 4 add, 5 global average pool, 0 none), per ITEM dense FLOPs and activation
  * bytes (input, output and residual elements), and per LAUNCH weight and bias bytes. */
 octo_status octo_set_layer_timing(octo_pipeline* p, int32_t enable);

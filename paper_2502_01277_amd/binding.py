@@ -244,7 +244,7 @@ def pipeline_desc(p: zoo.PipelineSpec, keep: list, keep_all_tensors=False) -> Oc
     d.models = models; d.n_models = len(p.models); d.edges = edges; d.n_edges = len(p.edges)
     d.slo_ms = p.slo_ms; d.src_h, d.src_w = p.src_h, p.src_w
     d.max_frames, d.max_rois_per_frame = p.max_frames, p.max_rois_per_frame
-    d.max_queue = 0; d.keep_all_tensors = 1 if keep_all_tensors else 0
+    d.max_queue = 0; d.keep_all_tensors = int(keep_all_tensors)
     return d
 
 

@@ -486,7 +486,7 @@ hipError_t launch_conv(int dtype, const ConvArgs& a0, int num_cu, hipStream_t s,
   ConvArgs a = a0;
   if (!conv_prepare(a, dtype)) return hipErrorInvalidValue;
   const hipError_t es = launch_stem(dtype, a, num_cu, s, kernel_id, tm);
-  if (es != hipErrorNotSupported) return es;
+  if (es != hipErrorNotSupported || a.pool_y) return es;      // only the first-layer kernel can pool its own output
   // 3x3 layers with at most 64 output channels on wide images: the input patch of a tile lives in LDS (measured
   // +20% on 56x56x64 layers; the 8x32 pixel tile wastes lanes on narrow feature maps, and with more output channels
   // the general kernel's 128-channel tile re-uses the pixel operand enough)

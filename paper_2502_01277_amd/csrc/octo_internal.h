@@ -38,6 +38,10 @@ struct ConvArgs {
   int out_f32;          // write fp32 instead of the storage type
   int n_hint;           // host only: expected item count when it is taken on the device (0: assume n); picks the tile shape
   int pair_view;        // the layer is a 3-channel first layer run on pixel pairs of a 4-channel-padded input
+  // Fused 3x3 / stride-2 / pad-1 max-pool (first-layer kernel only): when pool_y is set, only the pooled tensor is
+  // written and y is not touched; launch_conv returns hipErrorNotSupported if no kernel can do that for the layer.
+  void* pool_y;
+  int pool_ho, pool_wo, pool_ld, pool_coff;
 };
 
 // element size of a storage type

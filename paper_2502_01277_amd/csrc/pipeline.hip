@@ -48,6 +48,10 @@ struct LayerPlan {
   // stride 1 and horizontal padding pair_pad, on an image of half the width.
   bool pair_view = false;
   int pair_kw = 0, pair_pad = 0, pair_shift = 0;
+  // The next layer is a 3x3 / stride-2 / pad-1 max-pool and the only reader of this first layer's output: the
+  // convolution kernel pools its own tile and writes the pooled tensor, the pool layer does nothing (its kernel id
+  // then reads KID_NONE).  Cleared for good the first time no kernel accepts the fused form.
+  bool fuse_pool = false;
 };
 
 struct TensorPlan {
@@ -249,7 +253,7 @@ octo_status plan_shapes(ModelPlan& m, std::string& why) {
 }
 
 // ---- activation memory: concat aliasing + liveness-based reuse --------------
-void plan_activations(ModelPlan& m, bool keep_all) {
+void plan_activations(ModelPlan& m, bool keep_all, bool allow_fusion) {
   const int nt = (int)m.tensors.size();
   for (int t = 0; t < nt; ++t) { m.tensors[t].root = t; m.tensors[t].coff = 0; m.tensors[t].ld = m.tensors[t].c; }
   // producers of these ops can write into a channel slice of a wider buffer
@@ -304,6 +308,18 @@ void plan_activations(ModelPlan& m, bool keep_all) {
         lp.pair_pad = (lp.L.pad + lp.pair_shift) / 2;
       }
   }
+  // first layer followed by a 3x3 / stride-2 / pad-1 max-pool that is the only reader of its output: fused
+  for (int i = 0; i + 1 < (int)m.layers.size(); ++i) {
+    LayerPlan& lp = m.layers[i];
+    const octo_layer& P = m.layers[i + 1].L;
+    lp.fuse_pool = false;
+    if (!allow_fusion || !lp.pair_view || lp.L.op != OCTO_CONV || lp.L.n_in != 1 || is_output[i + 1] || m.tensors[i + 1].root != i + 1) continue;
+    if (P.op != OCTO_MAXPOOL || P.in[0] != i + 1 || P.kh != 3 || P.stride != 2 || P.pad != 1) continue;
+    int readers = 0;
+    for (const LayerPlan& q : m.layers)
+      for (int k = 0; k < q.L.n_in; ++k) readers += q.L.in[k] == i + 1;
+    lp.fuse_pool = readers == 1;
+  }
   // lifetimes of root buffers in layer steps: tensor t is written at step t-1 (input: -1)
   std::vector<int> birth(nt, 1 << 30), death(nt, -2);
   for (int t = 0; t < nt; ++t) {
@@ -311,6 +327,11 @@ void plan_activations(ModelPlan& m, bool keep_all) {
     birth[r] = std::min(birth[r], t - 1);
     death[r] = std::max(death[r], t - 1);
   }
+  for (int i = 0; i < (int)m.layers.size(); ++i)
+    if (m.layers[i].fuse_pool) {             // the pooled tensor is written one step early, by the convolution
+      const int r = m.tensors[i + 2].root;
+      birth[r] = std::min(birth[r], i);
+    }
   for (int i = 0; i < (int)m.layers.size(); ++i)
     for (int k = 0; k < m.layers[i].L.n_in; ++k) {
       const int r = m.tensors[m.layers[i].L.in[k]].root;
@@ -425,9 +446,18 @@ hipError_t run_layer(octo_pipeline* p, ModelPlan& m, int i, int n, const int* n_
       a.act = L.act; a.res_mode = L.res_mode; a.out_f32 = m.tensors[i + 1].f32 ? 1 : 0;
       if (L.n_in == 2) { const TensorView r = view_of(m, L.in[1]); a.res = r.ptr; a.res_ld = r.ld; a.res_coff = r.coff; }
       if (n_dyn && m.items_hint > 0) a.n_hint = std::max(1, (int)(m.items_hint + 0.999));
+      if (lp.fuse_pool) {
+        const TensorView py = view_of(m, i + 2);
+        ConvArgs f = a;
+        f.pool_y = py.ptr; f.pool_ho = py.h; f.pool_wo = py.w; f.pool_ld = py.ld; f.pool_coff = py.coff;
+        const hipError_t e = launch_conv(m.d.dtype, f, p->num_cu, s, &lp.kernel_id, tm);
+        if (e != hipErrorNotSupported) return e;
+        lp.fuse_pool = false;
+      }
       return launch_conv(m.d.dtype, a, p->num_cu, s, &lp.kernel_id, tm);
     }
     case OCTO_MAXPOOL: {
+      if (i > 0 && m.layers[i - 1].fuse_pool) { lp.kernel_id = KID_NONE; return hipSuccess; }
       PoolArgs a{x.ptr, y.ptr, n_dyn, n, x.h, x.w, x.c, x.ld, x.coff, y.h, y.w, y.ld, y.coff, L.kh, L.stride, L.pad};
       lp.kernel_id = KID_MAXPOOL;
       return launch_maxpool(m.d.dtype, a, s);
@@ -551,7 +581,7 @@ octo_status build(octo_pipeline* p, const octo_pipeline_desc* desc, Arena& ar) {
       m.cap = std::max(1, m.d.batch_size);
       m.bz = m.cap;
     }
-    plan_activations(m, desc->keep_all_tensors != 0);
+    plan_activations(m, desc->keep_all_tensors != 0, desc->keep_all_tensors != 1);
   }
   // ---- carve the workspace ----
   for (int k = 0; k < desc->n_models; ++k) {

@@ -179,6 +179,40 @@ def test_residual_concat_pool_upsample_graph(octo, dtype):
 
 
 @pytest.mark.parametrize("dtype", ["f16", "bf16"])
+@pytest.mark.parametrize("case", [(70, 90, 64, 5), (224, 224, 64, 3), (64, 36, 44, 4), (30, 124, 24, 7)])
+def test_first_layer_with_fused_max_pool(octo, dtype, case):
+    """7x7 / stride-2 first layer whose only reader is a 3x3 / stride-2 max-pool: the convolution kernel pools its own
+    tiles and the unpooled tensor is never written.  SiLU, so that negative values take part in the maximum.  Sizes: odd
+    output sizes (35 x 45 -> 18 x 23: a last tile of three rows, a second strip of eight pooled columns), the classifier's
+    own 224 x 224, a map narrower than one strip, a ragged channel vector (44) and a wide map of five strips.  The pooled
+    tensor is compared with the oracle and, bit for bit, with the unfused path (same convolution arithmetic, separate
+    pool kernel)."""
+    h, w, cout, n = case
+
+    def build(B):
+        a = B.conv(0, cout, 7, 2, 3, act=zoo.ACT_SILU)
+        return B.conv(B.maxpool(a, 3, 2, 1), 16, 1, 1)
+    m = _model(dtype, (h, w), 3, build, n)
+    x = zoo.round_to_dtype(np.random.default_rng(21).uniform(-1, 1, (n, h, w, 3)).astype(np.float32), dtype)
+    spec = zoo.PipelineSpec("t", [small_root(dtype), m], [], 200.0, 32, 32, 1, 1)
+    got, kids = {}, {}
+    for keep in (0, 1, 2):                          # normal operation; every layer on its own; fused, with every buffer kept
+        P = octo.Pipeline(spec, keep_all_tensors=keep)
+        P.run_model_on(1, octo.to_device(x, dtype))
+        got[keep] = (P.get_tensor(1, 2, n) if keep else None, P.get_tensor(1, m.outputs[0], n))
+        kids[keep] = [int(k) for k in P.layer_info(1)[1][:2]]
+        P.close()
+    assert kids[0] == kids[2] == [1901064074, 0] and kids[1] == [1900064074, 1], kids      # fused: the pool layer launches nothing
+    ref = nn.run_model(m, x, keep_all=True)
+    assert got[2][0].shape == ref[2].shape
+    assert rel_err(got[2][0], ref[2]) <= TOL[dtype]
+    assert np.array_equal(got[2][0], got[1][0])
+    for keep in (0, 1, 2):
+        assert rel_err(got[keep][1], ref[m.outputs[0]]) <= TOL[dtype]
+    assert np.array_equal(got[0][1], got[1][1]) and np.array_equal(got[2][1], got[1][1])
+
+
+@pytest.mark.parametrize("dtype", ["f16", "bf16"])
 def test_wide_3x3_layers_with_residuals(octo, dtype):
     """Large enough for the 3x3 kernel that keeps the input patch in LDS: both residual modes, SiLU and ReLU."""
     def build(B):
