@@ -229,6 +229,26 @@ octo_status octo_width_to_cus(double util, int32_t total_cus, int32_t grain, int
  * whose cost width x latency is within tol of the cheapest (a model that does not speed up on more units should not
  * hold them); by_cost == 0: the narrowest width whose latency is within tol of the widest width's. */
 octo_status octo_choose_width(const int32_t* widths, const double* latency_ms, int32_t n, int32_t by_cost, double tol, int32_t* width);
+/* Load-aware widths around Algorithm 1 (Sec. III-C takes a model's measured utilisation as its width and does not say
+ * what happens when a pipeline's work does not fit its duty cycle at those widths).  models[i].width is the width the
+ * model's own profile chose (octo_choose_width; one of widths[]), profile_ms[j][k] its batch latency at widths[j] and
+ * batch size profile_bz[k].  For every profiled width taken as a floor, in ascending order: each model runs at
+ * max(floor, its own width); octo_cwd_search picks the batch sizes with the latencies of those widths (fixed_bz != NULL:
+ * these are taken instead); a model needs octo_batches_per_cycle batches per cycle; the floor is accepted if the
+ * pipeline's work per duty cycle, sum k x L(bz), is at most cycle_share x duty_ms, and the widest floor whatever its work.
+ * out[i]: the model as Algorithm 2 takes it - util = width / total_cus, bz, and the batch latency at bz multiplied by
+ * k (its portion holds k back-to-back batches); the two estimates are taken before that multiplication. */
+#define OCTO_MAX_WIDTHS 4
+typedef struct {
+  int32_t parent;
+  float rate, burstiness, weight_mem, inter_mem;
+  int32_t width;
+  int32_t n_profile; int32_t profile_bz[8];
+  float profile_ms[OCTO_MAX_WIDTHS][8];
+} octo_plan_model;
+octo_status octo_plan_pipeline(const octo_plan_model* models, int32_t n_models, float slo_ms, double duty_ms, double cycle_share,
+                               const int32_t* widths, int32_t n_widths, int32_t total_cus, const int32_t* fixed_bz,
+                               octo_sched_model* out, int32_t* batches_per_cycle, float* est_latency_ms, float* est_throughput);
 /* Lazy dropping (Sec. IV-A): how many requests at the head of an arrival-ordered queue are already older than the
  * objective when a batch is formed (now - arrival > slo; exactly the objective old is still served; counting stops
  * at the first request that is not late). */
@@ -249,6 +269,84 @@ octo_status octo_scaler_destroy(octo_scaler* s);
  * a child model consumes the ROIs of the most recent model-0 run; after the last child the batch becomes
  * collectable.  octo_run is the same sequence on one stream. */
 octo_status octo_run_model(octo_pipeline* p, int32_t model, void* hip_stream, int32_t* n_items_launched);
+
+/* ---- slot executor (Sec. III-C "Inference Stream", Sec. III-D, Sec. IV-A) ----
+ * Serves several pipelines on one GPU from a schedule: every duty cycle, at the start of an instance's portion
+ * (slot_ms), its detector is launched on what is queued for it - at most bz frames per batch and batches_per_cycle + 1
+ * batches per slot - and its downstream models follow on the streams of their own portions (octo_run_model).  Requests
+ * come from cameras: arrival times in seconds from the start of serving and a pool of device frames each camera cycles
+ * through.  All descriptor arrays are host memory and are copied at create; frames, head pools and head buffers are
+ * device memory the caller keeps alive until destroy.  One executor per host thread. */
+typedef struct {
+  int32_t bz;                     /* frames per detector batch (Algorithm 1's choice for the root model) */
+  int32_t batches_per_cycle;      /* octo_batches_per_cycle of the root model */
+  float slo_ms;
+  /* planted heads (parity and benchmark mode; n_levels = 0: none): head_pool[l] is [pool items][head_item_bytes[l]]; before
+   * a batch runs, the items of the batch's frames are copied into the instance's head_buffers, which decode reads */
+  const void* const* head_pool;
+  const size_t* head_item_bytes;
+  int32_t n_levels;
+  /* scaler of the queue's stand-by instance (0: window 5, up 1.0, down 0.75); capacity = (batches_per_cycle + 1) * bz */
+  int32_t scaler_window;
+  float scaler_up, scaler_down;
+} octo_exec_queue;
+
+typedef struct {
+  octo_pipeline* pipe;
+  int32_t queue;                  /* the request queue it serves */
+  int32_t standby;                /* != 0: a stand-by copy, switched on and off by the queue's scaler (slotted mode only) */
+  void* const* streams;           /* [n_models]: HIP stream of each model's portion */
+  int32_t n_models;
+  float slot_ms;                  /* start of its first model's portion inside the duty cycle */
+  void* const* head_buffers;      /* [n_levels] device buffers installed with octo_debug_set_head, or NULL */
+  int32_t max_frames, max_batch, max_det;   /* of its pipeline: frame capacity, largest detector batch, boxes kept per frame */
+} octo_exec_instance;
+
+typedef struct {
+  int32_t queue;
+  const double* arrivals_s; int32_t n_arrivals;       /* ascending */
+  const void* const* d_frames; const size_t* pitch_bytes; int32_t n_frames;   /* request k shows frame k % n_frames */
+  int32_t pool_offset;            /* index of its first frame in the queue's head pool */
+} octo_exec_camera;
+
+typedef struct {
+  const octo_exec_queue* queues; int32_t n_queues;
+  const octo_exec_instance* instances; int32_t n_instances;      /* scheduled instances first (one per queue), then stand-by copies */
+  const octo_exec_camera* cameras; int32_t n_cameras;
+  float duty_ms;
+  int32_t slotted;                /* 0: no portions - every instance launches as soon as something is queued */
+  int32_t drop_late;              /* lazy dropping (octo_late_prefix) when a batch is formed */
+  int32_t keep_results;           /* keep every served frame's boxes for octo_executor_results */
+  /* for placing stand-by copies (NULL / 0 without them): Algorithm 2's inputs for the scheduled pipelines, one per queue,
+   * and the streams its placements refer to (schedule stream index -> handle and compute-unit range) */
+  const octo_sched_pipeline* sched; double gpu_mem; int32_t n_streams;
+  const int32_t* stream_index; void* const* stream_handle; const int32_t* stream_first_cu; const int32_t* stream_n_cu; int32_t n_sched_streams;
+  int32_t masked;                 /* != 0: a newly placed copy's stream is restricted to its compute-unit range; 0: plain_stream is used */
+  void* plain_stream;
+} octo_exec_desc;
+
+typedef struct {
+  int64_t submitted, served, slo_met, boxes, dropped;   /* dropped: late requests removed at batch formation */
+  float latency_ms_p50, latency_ms_p99, latency_ms_max;
+} octo_exec_stats;
+typedef struct { float t_s; int32_t queue; int32_t change; } octo_scale_event;   /* +1 copy switched on, -1 off, 0 no room for it */
+
+typedef struct octo_executor octo_executor;
+/* Also runs one frame through every instance (warm-up).  OCTO_EINVAL for an inconsistent description. */
+octo_status octo_executor_create(const octo_exec_desc* desc, octo_executor** out);
+/* Serve the arrivals earlier than duration_s, then wait up to drain_s for the queues to empty; blocking.
+ * *wall_s = time from the first slot to the end of the loop.  Statistics add up over calls. */
+octo_status octo_executor_serve(octo_executor* ex, double duration_s, double drain_s, double* wall_s);
+octo_status octo_executor_stats(const octo_executor* ex, int32_t queue, octo_exec_stats* out);
+octo_status octo_executor_scale_events(const octo_executor* ex, octo_scale_event* out, int32_t cap, int32_t* n);
+/* Streams in use: those of the schedule plus the ones created for placed copies (schedule stream index, compute-unit range). */
+octo_status octo_executor_streams(const octo_executor* ex, int32_t* stream_index, int32_t* first_cu, int32_t* n_cu, int32_t cap, int32_t* n);
+/* keep_results: every served frame of a queue - request id (arrival order), index in the head pool / camera pools, and its
+ * boxes boxes[box_offset .. box_offset + n_boxes).  OCTO_ECAP (with the needed sizes in *n_frames, *n_boxes_total) if too small. */
+octo_status octo_executor_results(const octo_executor* ex, int32_t queue, int64_t* frame_ids, int32_t* pool_index, int32_t* box_offset,
+                                  int32_t* n_boxes, int32_t frame_cap, octo_box* boxes, int32_t box_cap, int32_t* n_frames, int32_t* n_boxes_total);
+const char* octo_executor_last_error(const octo_executor* ex);
+octo_status octo_executor_destroy(octo_executor* ex);
 
 /* ---- profiling and parity hooks ---- */
 

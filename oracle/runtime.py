@@ -103,3 +103,38 @@ class Scaler:
             self.arrived, self.backlog = [], []
             return -1
         return 0
+
+
+def plan_pipeline(models: List[dict], slo_ms: float, duty_ms: float, cycle_share: float, widths: Sequence[int], total_cus: int,
+                  fixed_bz: Sequence[int] = None):
+    """Load-aware widths around Algorithm 1's batch-size search (READING: the paper takes a model's measured utilisation
+    as its width U_m and does not say what happens when a pipeline's work does not fit its duty cycle at those widths).
+
+    models: dicts with parent, rate, burstiness, weight_mem, inter_mem, width (the compute units the model's own profile
+    chose) and by_width {compute units: {batch size: latency ms}}.  For every profiled width taken as a floor, in
+    ascending order: each model runs at max(floor, its own width); Algorithm 1 picks the batch sizes with the latencies
+    of those widths (or fixed_bz is taken); a model needs k = batches_per_cycle batches per cycle; the floor is accepted
+    if the pipeline's work per duty cycle, sum k x L(bz), is at most cycle_share x duty, and the widest floor is accepted
+    whatever its work.  Returns (models as oracle.sched.SModel with bz set and the batch latency at bz multiplied by k -
+    the portion holds k back-to-back batches -, k per model, estimated latency, estimated throughput); the two
+    estimates are taken before the multiplication."""
+    from . import sched
+    ws = sorted(widths)
+    for floor in ws:
+        sm = []
+        for i, m in enumerate(models):
+            w = max(floor, m["width"])
+            sm.append(sched.SModel("m%d" % i, m["parent"], dict(m["by_width"][w]), max(m["rate"], 1e-3), m["burstiness"], w / total_cus,
+                                   m["weight_mem"], m["inter_mem"], 1))
+        p = sched.SPipeline("p", sm, slo_ms)
+        bzs = sched.cwd_lite(p) if fixed_bz is None else list(fixed_bz)
+        for m, b in zip(sm, bzs):
+            m.bz = b
+        ks = [batches_per_cycle(m.rate, duty_ms, m.bz) for m in sm]
+        work = sum(k * m.profile[m.bz] for m, k in zip(sm, ks))
+        if work <= cycle_share * duty_ms or floor == ws[-1]:
+            break
+    lat, thr = sched.est_latency(p), sched.est_throughput(p)
+    for m, k in zip(sm, ks):
+        m.profile[m.bz] = k * m.profile[m.bz]
+    return sm, ks, lat, thr

@@ -9,7 +9,8 @@ from __future__ import annotations
 
 import ctypes as C
 import os
-from typing import List, Optional, Sequence
+from dataclasses import dataclass, field
+from typing import Dict, List, Optional, Sequence, Tuple
 
 import numpy as np
 
@@ -79,13 +80,58 @@ class OctoPlacement(C.Structure):
                 ("start_ms", C.c_float), ("end_ms", C.c_float), ("duty_cycle_ms", C.c_float)]
 
 
+class OctoPlanModel(C.Structure):
+    _fields_ = [("parent", C.c_int32), ("rate", C.c_float), ("burstiness", C.c_float), ("weight_mem", C.c_float), ("inter_mem", C.c_float),
+                ("width", C.c_int32), ("n_profile", C.c_int32), ("profile_bz", C.c_int32 * 8), ("profile_ms", (C.c_float * 8) * 4)]
+
+
+class OctoExecQueue(C.Structure):
+    _fields_ = [("bz", C.c_int32), ("batches_per_cycle", C.c_int32), ("slo_ms", C.c_float),
+                ("head_pool", C.POINTER(C.c_void_p)), ("head_item_bytes", C.POINTER(C.c_size_t)), ("n_levels", C.c_int32),
+                ("scaler_window", C.c_int32), ("scaler_up", C.c_float), ("scaler_down", C.c_float)]
+
+
+class OctoExecInstance(C.Structure):
+    _fields_ = [("pipe", C.c_void_p), ("queue", C.c_int32), ("standby", C.c_int32), ("streams", C.POINTER(C.c_void_p)),
+                ("n_models", C.c_int32), ("slot_ms", C.c_float), ("head_buffers", C.POINTER(C.c_void_p)),
+                ("max_frames", C.c_int32), ("max_batch", C.c_int32), ("max_det", C.c_int32)]
+
+
+class OctoExecCamera(C.Structure):
+    _fields_ = [("queue", C.c_int32), ("arrivals_s", C.POINTER(C.c_double)), ("n_arrivals", C.c_int32),
+                ("d_frames", C.POINTER(C.c_void_p)), ("pitch_bytes", C.POINTER(C.c_size_t)), ("n_frames", C.c_int32),
+                ("pool_offset", C.c_int32)]
+
+
+class OctoExecDesc(C.Structure):
+    _fields_ = [("queues", C.POINTER(OctoExecQueue)), ("n_queues", C.c_int32),
+                ("instances", C.POINTER(OctoExecInstance)), ("n_instances", C.c_int32),
+                ("cameras", C.POINTER(OctoExecCamera)), ("n_cameras", C.c_int32),
+                ("duty_ms", C.c_float), ("slotted", C.c_int32), ("drop_late", C.c_int32), ("keep_results", C.c_int32),
+                ("sched", C.POINTER(OctoSchedPipeline)), ("gpu_mem", C.c_double), ("n_streams", C.c_int32),
+                ("stream_index", C.POINTER(C.c_int32)), ("stream_handle", C.POINTER(C.c_void_p)),
+                ("stream_first_cu", C.POINTER(C.c_int32)), ("stream_n_cu", C.POINTER(C.c_int32)), ("n_sched_streams", C.c_int32),
+                ("masked", C.c_int32), ("plain_stream", C.c_void_p)]
+
+
+class OctoExecStats(C.Structure):
+    _fields_ = [("submitted", C.c_int64), ("served", C.c_int64), ("slo_met", C.c_int64), ("boxes", C.c_int64), ("dropped", C.c_int64),
+                ("latency_ms_p50", C.c_float), ("latency_ms_p99", C.c_float), ("latency_ms_max", C.c_float)]
+
+
+class OctoScaleEvent(C.Structure):
+    _fields_ = [("t_s", C.c_float), ("queue", C.c_int32), ("change", C.c_int32)]
+
+
 # Every symbol include/octo.h declares.
 EXPORTS = [
     "octo_pipeline_workspace_size", "octo_pipeline_create", "octo_pipeline_destroy", "octo_submit_frames", "octo_run",
     "octo_collect", "octo_set_batch_size", "octo_set_detector_batch", "octo_last_error", "octo_now_ms", "octo_stream_create_masked", "octo_stream_create_range",
     "octo_stream_destroy", "octo_device_cu_count", "octo_cwd_search", "octo_coral_schedule", "octo_est_latency_ms",
     "octo_est_throughput", "octo_burstiness", "octo_batches_per_cycle", "octo_width_to_cus", "octo_choose_width", "octo_late_prefix",
-    "octo_scaler_create", "octo_scaler_observe", "octo_scaler_destroy", "octo_run_model", "octo_profile_layers", "octo_set_layer_timing", "octo_get_layer_info", "octo_set_stage_timing", "octo_get_stage_ms",
+    "octo_plan_pipeline", "octo_scaler_create", "octo_scaler_observe", "octo_scaler_destroy", "octo_run_model",
+    "octo_executor_create", "octo_executor_serve", "octo_executor_stats", "octo_executor_scale_events", "octo_executor_streams",
+    "octo_executor_results", "octo_executor_last_error", "octo_executor_destroy", "octo_profile_layers", "octo_set_layer_timing", "octo_get_layer_info", "octo_set_stage_timing", "octo_get_stage_ms",
     "octo_debug_get_tensor", "octo_debug_tensor_shape", "octo_debug_set_head", "octo_debug_run_model",
     "octo_debug_get_detections", "octo_debug_get_rois", "octo_debug_get_labels", "octo_letterbox_geometry", "octo_op_letterbox",
     "octo_op_crop_resize", "octo_op_decode", "octo_op_topk", "octo_op_nms", "octo_op_nms_scratch_bytes", "octo_op_nms_static", "octo_op_compact", "octo_probe_copy", "octo_probe_mfma",
@@ -131,9 +177,19 @@ def lib() -> C.CDLL:
         L.octo_width_to_cus.argtypes = [f64, i32, i32, vp]
         L.octo_choose_width.argtypes = [vp, vp, i32, i32, f64, vp]
         L.octo_late_prefix.argtypes = [vp, i32, f64, f64, vp]
+        L.octo_plan_pipeline.argtypes = [vp, i32, f32, f64, f64, vp, i32, i32, vp, vp, vp, vp, vp]
         L.octo_scaler_create.argtypes = [f64, i32, f64, f64, i32, vp]
         L.octo_scaler_observe.argtypes = [vp, C.c_int64, C.c_int64, i32, vp]
         L.octo_scaler_destroy.argtypes = [vp]
+        L.octo_executor_create.argtypes = [vp, vp]
+        L.octo_executor_serve.argtypes = [vp, f64, f64, vp]
+        L.octo_executor_stats.argtypes = [vp, i32, vp]
+        L.octo_executor_scale_events.argtypes = [vp, vp, i32, vp]
+        L.octo_executor_streams.argtypes = [vp, vp, vp, vp, i32, vp]
+        L.octo_executor_results.argtypes = [vp, i32, vp, vp, vp, vp, i32, vp, i32, vp, vp]
+        L.octo_executor_last_error.argtypes = [vp]
+        L.octo_executor_last_error.restype = C.c_char_p
+        L.octo_executor_destroy.argtypes = [vp]
         L.octo_profile_layers.argtypes = [vp, i32, i32, i32, vp, vp, vp, vp, i32]
         L.octo_set_stage_timing.argtypes = [vp, i32]
         L.octo_set_layer_timing.argtypes = [vp, i32]
@@ -634,6 +690,32 @@ class Scaler:
             pass
 
 
+def plan_pipeline(models: Sequence[dict], slo_ms: float, duty_ms: float, cycle_share: float, widths: Sequence[int], total_cus: int,
+                  fixed_bz: Optional[Sequence[int]] = None):
+    """octo_plan_pipeline.  models: dicts with parent, rate, burstiness, weight_mem, inter_mem, width and by_width {compute
+    units: {batch size: ms}}.  Returns (model dicts as sched_pipeline takes them, batches per cycle, est. latency, est. throughput)."""
+    ws = list(widths)
+    arr = (OctoPlanModel * len(models))()
+    for i, m in enumerate(models):
+        a = arr[i]
+        a.parent, a.rate, a.burstiness, a.weight_mem, a.inter_mem, a.width = m["parent"], m["rate"], m["burstiness"], m["weight_mem"], m["inter_mem"], m["width"]
+        bzs = sorted(m["by_width"][ws[0]])
+        a.n_profile = len(bzs)
+        for k, b in enumerate(bzs):
+            a.profile_bz[k] = b
+            for j, w in enumerate(ws):
+                a.profile_ms[j][k] = m["by_width"][w][b]
+    out = (OctoSchedModel * len(models))()
+    ks = (C.c_int32 * len(models))()
+    lat, thr = C.c_float(), C.c_float()
+    wa = (C.c_int32 * len(ws))(*ws)
+    fb = (C.c_int32 * len(models))(*fixed_bz) if fixed_bz is not None else None
+    _st(lib().octo_plan_pipeline(arr, len(models), slo_ms, duty_ms, cycle_share, wa, len(ws), total_cus, fb, out, ks, C.byref(lat), C.byref(thr)))
+    res = [dict(parent=o.parent, profile={o.profile_bz[k]: o.profile_ms[k] for k in range(o.n_profile)}, rate=o.rate, burstiness=o.burstiness,
+                util=o.util, weight_mem=o.weight_mem, inter_mem=o.inter_mem, bz=o.bz) for o in out]
+    return res, [int(k) for k in ks], float(lat.value), float(thr.value)
+
+
 def sched_pipeline(models: Sequence[dict], slo_ms: float, keep: list) -> OctoSchedPipeline:
     """models: dicts with parent, profile {bz: ms}, rate, burstiness, util, weight_mem, inter_mem, bz."""
     arr = (OctoSchedModel * len(models))()
@@ -667,3 +749,161 @@ def coral_schedule(pipelines: Sequence[tuple], mem: float, util_max: float, n_st
     out = (OctoPlacement * total)()
     _st(lib().octo_coral_schedule(ps, len(pipelines), mem, util_max, n_streams, out))
     return [(o.pipeline, o.model, o.stream, o.start_ms, o.end_ms, o.duty_cycle_ms) for o in out]
+
+
+# ---- slot executor (octo_executor_*) -----------------------------------------
+@dataclass
+class PipelineStats:
+    submitted: int = 0
+    served: int = 0
+    slo_met: int = 0
+    boxes: int = 0
+    dropped: int = 0                    # requests dropped at batch formation because they were already late
+    latency_ms: Tuple[float, float, float] = (0.0, 0.0, 0.0)       # p50, p99, max
+    results: Dict[int, Tuple[int, np.ndarray]] = field(default_factory=dict)   # frame id -> (pool index, boxes)
+
+
+class SlotExecutor:
+    """The library's slot executor (octo_executor_*; Sec. III-C 'Inference Stream', Sec. III-D, Sec. IV-A) fed from a
+    Schedule: this class creates the schedule's streams, installs the planted-head buffers, marshals the description and
+    reads the statistics back.  The serving loop, batch formation, lazy dropping and scaling all run in the library.
+
+    spares: one stand-by copy per pipeline (or None) for the run-time scaler; scaler: dict(window, up, down)."""
+
+    def __init__(self, pipes: List["Pipeline"], schedule, cameras: List,
+                 head_pools: Optional[List[Optional[List]]] = None, slotted: bool = True, masked: bool = True,
+                 keep_results: bool = False, drop_late: bool = False,
+                 spares: Optional[List[Optional[Pipeline]]] = None, scaler: Optional[dict] = None):
+        import torch
+        L = lib()
+        self.pipes, self.sch, self.keep_results = pipes, schedule, keep_results
+        self._keep: list = [cameras, head_pools]
+        self._owned: List[int] = []
+        self._plain = torch.cuda.Stream()
+        plain = int(self._plain.cuda_stream)
+        streams = {}
+        for st, (first, n) in schedule.stream_cus.items():
+            streams[st] = plain
+            if masked:
+                streams[st] = stream_create_range(first, n)
+                self._owned.append(streams[st])
+        head_pools = head_pools or [None] * len(pipes)
+
+        def stream_of(i, m):
+            """A model Algorithm 2 could not place follows its parent's stream (a root: the first stream)."""
+            st = schedule.placement(i, m)[2]
+            if st >= 0:
+                return streams[st]
+            parent = {e.child: e.parent for e in pipes[i].spec.edges}.get(m, -1)
+            return stream_of(i, parent) if parent >= 0 else (streams[min(streams)] if streams else plain)
+
+        def vp_array(vals):
+            arr = (C.c_void_p * max(1, len(vals)))(*vals)
+            self._keep.append(arr)
+            return arr
+
+        queues = (OctoExecQueue * len(pipes))()
+        for i, P in enumerate(pipes):
+            q, hp = queues[i], head_pools[i]
+            q.bz, q.batches_per_cycle, q.slo_ms = schedule.bz[i][0], schedule.batches_per_cycle[i][0], P.spec.slo_ms
+            if hp is not None:
+                q.n_levels = len(hp)
+                q.head_pool = vp_array([int(h.data_ptr()) for h in hp])
+                sizes = (C.c_size_t * len(hp))(*[int(h[0].numel() * h.element_size()) for h in hp])
+                self._keep.append(sizes)
+                q.head_item_bytes = sizes
+            sc = scaler or {}
+            q.scaler_window, q.scaler_up, q.scaler_down = sc.get("window", 0), sc.get("up", 0.0), sc.get("down", 0.0)
+        copies = [(i, P) for i, P in enumerate(spares or []) if P is not None and slotted]
+        self._override = []
+        inst = (OctoExecInstance * (len(pipes) + len(copies)))()
+        for k, (i, P, standby) in enumerate([(i, P, 0) for i, P in enumerate(pipes)] + [(i, P, 1) for i, P in copies]):
+            I, nm = inst[k], len(P.spec.models)
+            I.pipe, I.queue, I.standby, I.n_models = P.h.value, i, standby, nm
+            I.streams = vp_array([stream_of(i, m) for m in range(nm)])
+            I.slot_ms = schedule.placement(i, 0)[3]
+            I.max_frames, I.max_batch, I.max_det = P.spec.max_frames, P.spec.models[0].batch_size, P.spec.models[0].max_det
+            if head_pools[i] is not None:
+                bufs = [torch.empty((P.spec.max_frames,) + tuple(h.shape[1:]), dtype=h.dtype, device=h.device) for h in head_pools[i]]
+                for l, b in enumerate(bufs):
+                    P.set_head(0, l, b)
+                self._override.append((P, bufs))
+                I.head_buffers = vp_array([int(b.data_ptr()) for b in bufs])
+        cams = (OctoExecCamera * max(1, len(cameras)))()
+        for k, c in enumerate(cameras):
+            arr = np.ascontiguousarray(c.arrivals_s, np.float64)
+            pit = (C.c_size_t * len(c.pool))(*[int(f.stride(0)) for f in c.pool])
+            self._keep += [arr, pit]
+            cams[k].queue, cams[k].n_arrivals, cams[k].n_frames, cams[k].pool_offset = c.pipeline, arr.size, len(c.pool), c.pool_offset
+            cams[k].arrivals_s = arr.ctypes.data_as(C.POINTER(C.c_double))
+            cams[k].d_frames = vp_array([int(f.data_ptr()) for f in c.pool])
+            cams[k].pitch_bytes = pit
+        d = OctoExecDesc()
+        d.queues, d.n_queues, d.instances, d.n_instances, d.cameras, d.n_cameras = queues, len(pipes), inst, len(inst), cams, len(cameras)
+        d.duty_ms, d.slotted, d.drop_late, d.keep_results = schedule.duty_ms, int(slotted), int(drop_late), int(keep_results)
+        d.masked, d.plain_stream = int(masked), plain
+        if copies:
+            ps = (OctoSchedPipeline * len(pipes))(*[sched_pipeline(m, slo, self._keep) for m, slo in schedule.coral_inputs])
+            d.sched, d.gpu_mem, d.n_streams = ps, schedule.gpu_mem_mb, schedule.n_streams
+        idx = sorted(streams)
+        d.n_sched_streams = len(idx)
+        i32s = lambda v: (C.c_int32 * max(1, len(v)))(*v)
+        d.stream_index, d.stream_handle = i32s(idx), vp_array([streams[s] for s in idx])
+        d.stream_first_cu, d.stream_n_cu = i32s([schedule.stream_cus[s][0] for s in idx]), i32s([schedule.stream_cus[s][1] for s in idx])
+        self._keep += [queues, inst, cams, d]
+        self.h = C.c_void_p()
+        _st(L.octo_executor_create(C.byref(d), C.byref(self.h)))
+        self.stats = [PipelineStats() for _ in pipes]
+        self.stream_cus: Dict[int, Tuple[int, int]] = dict(schedule.stream_cus)
+        self.scale_events: List[Tuple[float, int, int]] = []
+
+    def close(self):
+        if self.h:
+            lib().octo_executor_destroy(self.h)
+            self.h = C.c_void_p()
+        for h in self._owned:
+            stream_destroy(h)
+        self._owned = []
+        for P, bufs in self._override:
+            for l in range(len(bufs)):
+                P.set_head(0, l, None)
+        self._override = []
+
+    def serve(self, duration_s: float, drain_s: float = 2.0) -> dict:
+        L = lib()
+        wall = C.c_double()
+        st = L.octo_executor_serve(self.h, float(duration_s), float(drain_s), C.byref(wall))
+        if st != OK:
+            raise OctoError(st, L.octo_executor_last_error(self.h).decode())
+        per = []
+        for i, S in enumerate(self.stats):
+            r = OctoExecStats()
+            _st(L.octo_executor_stats(self.h, i, C.byref(r)))
+            S.submitted, S.served, S.slo_met, S.boxes, S.dropped = r.submitted, r.served, r.slo_met, r.boxes, r.dropped
+            S.latency_ms = (r.latency_ms_p50, r.latency_ms_p99, r.latency_ms_max)
+            per.append(dict(pipeline=self.pipes[i].spec.name, submitted=S.submitted, served=S.served, slo_met=S.slo_met,
+                            dropped=S.dropped, objects=S.boxes, latency_ms_p50=r.latency_ms_p50,
+                            latency_ms_p99=r.latency_ms_p99, latency_ms_max=r.latency_ms_max))
+            if self.keep_results:
+                nf, nb = C.c_int32(), C.c_int32()
+                L.octo_executor_results(self.h, i, None, None, None, None, 0, None, 0, C.byref(nf), C.byref(nb))      # sizes
+                ids, pool = np.zeros(max(1, nf.value), np.int64), np.zeros(max(1, nf.value), np.int32)
+                off, cnt = np.zeros(max(1, nf.value), np.int32), np.zeros(max(1, nf.value), np.int32)
+                bx = np.zeros(max(1, nb.value), BOX_DTYPE)
+                _st(L.octo_executor_results(self.h, i, ids.ctypes.data, pool.ctypes.data, off.ctypes.data, cnt.ctypes.data, ids.size,
+                                                    bx.ctypes.data, bx.size, C.byref(nf), C.byref(nb)))
+                S.results = {int(ids[k]): (int(pool[k]), bx[off[k]: off[k] + cnt[k]].copy()) for k in range(nf.value)}
+        n = C.c_int32()
+        ev = (OctoScaleEvent * 256)()
+        L.octo_executor_scale_events(self.h, ev, 256, C.byref(n))
+        self.scale_events = [(round(ev[k].t_s, 3), ev[k].queue, ev[k].change) for k in range(min(256, n.value))]
+        si, sf, sn = (C.c_int32 * 64)(), (C.c_int32 * 64)(), (C.c_int32 * 64)()
+        L.octo_executor_streams(self.h, si, sf, sn, 64, C.byref(n))
+        self.stream_cus = {si[k]: (sf[k], sn[k]) for k in range(min(64, n.value))}
+        span = max(duration_s, 1e-9)
+        return dict(duration_s=duration_s, wall_s=wall.value, per_pipeline=per,
+                    effective_frames_per_s=sum(S.slo_met for S in self.stats) / span,
+                    total_frames_per_s=sum(S.served for S in self.stats) / span,
+                    objects_per_s=sum(S.boxes for S in self.stats) / span,
+                    slo_attainment=sum(S.slo_met for S in self.stats) / max(1, sum(S.submitted for S in self.stats)),
+                    dropped=sum(S.dropped for S in self.stats), scale_events=self.scale_events)

@@ -89,6 +89,61 @@ octo_status octo_late_prefix(const double* arrival_ms, int32_t n, double now_ms,
   return OCTO_OK;
 }
 
+octo_status octo_plan_pipeline(const octo_plan_model* models, int32_t n_models, float slo_ms, double duty_ms, double cycle_share,
+                               const int32_t* widths, int32_t n_widths, int32_t total_cus, const int32_t* fixed_bz,
+                               octo_sched_model* out, int32_t* batches_per_cycle, float* est_latency_ms, float* est_throughput) {
+  if (!models || !widths || !out || !batches_per_cycle || n_models < 1 || n_widths < 1 || n_widths > OCTO_MAX_WIDTHS || total_cus < 1 ||
+      !(duty_ms > 0.0) || !(cycle_share > 0.0))
+    return OCTO_EINVAL;
+  std::vector<int> order(n_widths);
+  std::iota(order.begin(), order.end(), 0);
+  std::sort(order.begin(), order.end(), [&](int a, int b) { return widths[a] < widths[b]; });
+  auto column_of = [&](int w) { for (int j = 0; j < n_widths; ++j) if (widths[j] == w) return j; return -1; };
+  for (int i = 0; i < n_models; ++i)
+    if (models[i].n_profile < 1 || models[i].n_profile > 8 || column_of(models[i].width) < 0) return OCTO_EINVAL;
+  std::vector<octo_sched_model> trial(n_models);
+  octo_sched_pipeline p{trial.data(), n_models, slo_ms};
+  for (int f = 0; f < n_widths; ++f) {
+    const int floor_w = widths[order[f]];
+    for (int i = 0; i < n_models; ++i) {
+      const octo_plan_model& m = models[i];
+      const int w = std::max(floor_w, m.width);          // a profiled width: the floor or the model's own
+      const int col = column_of(w);
+      octo_sched_model& t = trial[i];
+      t = octo_sched_model{};
+      t.parent = m.parent; t.n_profile = m.n_profile;
+      for (int k = 0; k < m.n_profile; ++k) { t.profile_bz[k] = m.profile_bz[k]; t.profile_ms[k] = m.profile_ms[col][k]; }
+      t.rate = std::max(m.rate, 1e-3f); t.burstiness = m.burstiness; t.util = (float)w / (float)total_cus;
+      t.weight_mem = m.weight_mem; t.inter_mem = m.inter_mem; t.bz = 1;
+    }
+    if (fixed_bz) {
+      for (int i = 0; i < n_models; ++i) trial[i].bz = fixed_bz[i];
+    } else {
+      const octo_status st = octo_cwd_search(&p);
+      if (st != OCTO_OK) return st;
+    }
+    double work = 0.0;
+    for (int i = 0; i < n_models; ++i) {
+      const octo_sched_model& t = trial[i];
+      int slot = -1;
+      for (int k = 0; k < t.n_profile; ++k) if (t.profile_bz[k] == t.bz) slot = k;
+      if (slot < 0) return OCTO_EINVAL;                   // a batch size without a profile entry
+      const octo_status st = octo_batches_per_cycle(t.rate, duty_ms, t.bz, &batches_per_cycle[i]);
+      if (st != OCTO_OK) return st;
+      work += (double)batches_per_cycle[i] * (double)t.profile_ms[slot];
+    }
+    if (work <= cycle_share * duty_ms) break;             // the widest floor is taken whatever its work
+  }
+  if (est_latency_ms) *est_latency_ms = octo_est_latency_ms(&p);
+  if (est_throughput) *est_throughput = octo_est_throughput(&p);
+  for (int i = 0; i < n_models; ++i) {
+    out[i] = trial[i];
+    for (int k = 0; k < out[i].n_profile; ++k)
+      if (out[i].profile_bz[k] == out[i].bz) out[i].profile_ms[k] *= (float)batches_per_cycle[i];      // the portion holds k back-to-back batches
+  }
+  return OCTO_OK;
+}
+
 octo_status octo_scaler_create(double capacity, int32_t window, double up, double down, int32_t max_instances, octo_scaler** out) {
   if (!out || !(capacity > 0.0) || window < 1 || !(down > 0.0) || !(down < up) || max_instances < 1) return OCTO_EINVAL;
   octo_scaler* s = new (std::nothrow) octo_scaler;

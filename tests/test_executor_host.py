@@ -30,6 +30,57 @@ def test_runtime_rules_equal_the_oracle_on_random_inputs():
     assert binding.width_to_cus(0.26, 256) == 72 and binding.choose_width({64: 10.0, 128: 3.0, 256: 3.0}) == 128
 
 
+def _random_plan_case(rng):
+    """A pipeline of 1-3 models with latencies (multiples of 1/8 ms, exact in fp32) that fall with the width and grow with the batch."""
+    n = int(rng.integers(1, 4))
+    widths = [64, 128, 256][: int(rng.integers(1, 4))]
+    bzs = [1, 2, 4, 8, 16, 32][: int(rng.integers(2, 7))]
+    models = []
+    for i in range(n):
+        base = float(rng.integers(2, 40)) / 8.0
+        by_width = {}
+        for j, w in enumerate(widths):
+            speed = 1.0 + 0.6 * j * float(rng.uniform(0.2, 1.0))
+            by_width[w] = {b: round(8 * base * (1 + 0.35 * np.log2(b) * b ** 0.5) / speed) / 8.0 + 0.125 for b in bzs}
+        models.append(dict(parent=-1 if i == 0 else int(rng.integers(0, i)), rate=float(rng.integers(5, 4000)), burstiness=float(rng.integers(0, 30)) / 8.0,
+                           weight_mem=float(rng.integers(1, 200)), inter_mem=0.0, width=int(rng.choice(widths)), by_width=by_width))
+    return models, widths, bzs
+
+
+def test_plan_pipeline_equals_the_oracle_and_its_hand_case():
+    """Load-aware widths around Algorithm 1 through the C ABI against oracle/runtime.plan_pipeline: batch sizes, batches per
+    cycle, accepted widths, the k-fold portion lengths and both estimates on random pipelines; then a case worked by hand."""
+    rng = np.random.default_rng(14)
+    moved = 0
+    for _ in range(200):
+        models, widths, bzs = _random_plan_case(rng)
+        slo, share = float(rng.choice([50.0, 100.0, 200.0])), float(rng.choice([0.25, 0.5, 0.8]))
+        fixed = None if rng.random() < 0.7 else [int(rng.choice(bzs)) for _ in models]
+        got, ks, lat, thr = binding.plan_pipeline(models, slo, slo / 2, share, widths, 256, fixed)
+        ref, rks, rlat, rthr = ort.plan_pipeline(models, slo, slo / 2, share, widths, 256, fixed)
+        assert ks == rks and [g["bz"] for g in got] == [r.bz for r in ref]
+        assert [round(g["util"] * 256) for g in got] == [round(r.util * 256) for r in ref]
+        for g, r in zip(got, ref):
+            assert all(abs(g["profile"][b] - r.profile[b]) <= 1e-4 * r.profile[b] for b in r.profile)
+        assert abs(lat - rlat) <= 1e-4 * rlat and abs(thr - rthr) <= 1e-4 * rthr
+        moved += any(round(g["util"] * 256) > m["width"] for g, m in zip(got, models))
+    assert moved > 10                                        # the width floor really moved in some of the cases
+    # by hand: one model, 1000 requests/s, duty 100 ms -> 100 requests per cycle.  At 64 units L(8) = 10 ms, L(16) = 30 ms; Algorithm 1
+    # (SLO 200: latency bound 100 ms; wait of a batch's first request (bz - 1) ms) doubles 1 -> 2 -> 4 -> 8 while throughput
+    # grows (L/bz: 2, 1.5, 1.25 at bz 1, 2, 4; 1.25 at 8 is no better, so it stops at 4): k = ceil(100 / 4) = 25 batches of 5 ms =
+    # 125 ms of work > 0.5 x 100 -> next width.  At 128 units L = 1, 1.5, 2, 3, 8 ms: L/bz = 1, .75, .5, .375, .5 -> bz 8, k = 13,
+    # work 39 ms <= 50: accepted; the portion is 13 x 3 = 39 ms long.
+    m = [dict(parent=-1, rate=1000.0, burstiness=0.0, weight_mem=1.0, inter_mem=0.0, width=64,
+              by_width={64: {1: 2.0, 2: 3.0, 4: 5.0, 8: 10.0, 16: 30.0}, 128: {1: 1.0, 2: 1.5, 4: 2.0, 8: 3.0, 16: 8.0}})]
+    for plan in (binding.plan_pipeline, ort.plan_pipeline):
+        out, ks, lat, thr = plan(m, 200.0, 100.0, 0.5, [64, 128], 256)
+        o = out[0] if isinstance(out[0], dict) else dict(bz=out[0].bz, util=out[0].util, profile=out[0].profile)
+        assert o["bz"] == 8 and ks == [13] and abs(o["util"] - 0.5) < 1e-6 and abs(o["profile"][8] - 39.0) < 1e-4
+        assert abs(lat - (3.0 + 7.0)) < 1e-4 and abs(thr - 1000.0 / (3.0 / 8)) < 0.1
+    out, ks, _, _ = binding.plan_pipeline(m, 200.0, 100.0, 2.0, [64, 128], 256)           # a generous share keeps the narrow width
+    assert out[0]["bz"] == 4 and ks == [25] and abs(out[0]["util"] - 0.25) < 1e-6
+
+
 def test_scaler_equals_the_oracle_on_random_sequences():
     rng = np.random.default_rng(12)
     for _ in range(60):
