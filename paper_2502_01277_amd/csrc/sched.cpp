@@ -4,6 +4,7 @@
 #include <algorithm>
 #include <cmath>
 #include <limits>
+#include <set>
 #include <vector>
 
 #include "octo_internal.h"
@@ -77,66 +78,96 @@ int cwd_search(octo_sched_pipeline* p) {
 }
 
 namespace {
-struct Portion { int stream; double start, end; };
-struct StreamState { double duty = 0.0, inter = 0.0, max_util = 0.0; };
 const double kInf = std::numeric_limits<double>::infinity();
 
-bool portion_less(const Portion& a, const Portion& b) {
-  // tightest portion first ("best fit"): by length, then start, then stream
-  const double la = a.end - a.start, lb = b.end - b.start;
-  if (la != lb) return la < lb;
-  if (a.start != b.start) return a.start < b.start;
-  return a.stream < b.stream;
-}
+// A free stretch of an inference stream's duty cycle.  Ordered by tightness, so that walking the set visits the
+// smallest gap that can hold a window first ("best fit"); ties by start, then stream.
+struct Gap {
+  int lane; double begin, end;
+  double length() const { return end - begin; }
+  bool operator<(const Gap& o) const {
+    if (length() != o.length()) return length() < o.length();
+    if (begin != o.begin) return begin < o.begin;
+    return lane < o.lane;
+  }
+};
+
+// What a model asks of the GPU: a window inside the duty cycle of its pipeline, memory, and a share of compute.
+struct Need { double begin, end, cycle, weights, scratch, width; };
+
+// One GPU as Algorithm 2 sees it (Sec. III-C): inference streams ("lanes"), each with the duty cycle of the first
+// pipeline placed on it, the widest portion it holds (a stream reserves that width for its whole cycle) and the largest
+// intermediate buffer of its models (models of one stream run one after the other and share it); weights add up.
+class GpuLedger {
+ public:
+  GpuLedger(int n_lanes, double mem_cap, double width_cap) : lanes_(n_lanes), mem_cap_(mem_cap), width_cap_(width_cap) {
+    for (int l = 0; l < n_lanes; ++l) gaps_.insert({l, 0.0, kInf});
+  }
+  // the tightest gap that can take the need, or end()
+  std::set<Gap>::const_iterator find(const Need& n) const {
+    for (auto it = gaps_.begin(); it != gaps_.end(); ++it)
+      if (admits(*it, n)) return it;
+    return gaps_.end();
+  }
+  std::set<Gap>::const_iterator none() const { return gaps_.end(); }
+  // book the need into the gap; returns the duty cycle of the gap's lane
+  double book(std::set<Gap>::const_iterator it, const Need& n) {
+    Gap g = *it;
+    gaps_.erase(it);
+    Lane& lane = lanes_[g.lane];
+    if (lane.cycle == 0.0) {                 // first portion of this lane: the lane takes the pipeline's cycle, open ends close there
+      lane.cycle = n.cycle;
+      std::vector<Gap> open;
+      for (auto q = gaps_.begin(); q != gaps_.end();)
+        if (q->lane == g.lane && q->end == kInf) { open.push_back(*q); q = gaps_.erase(q); } else ++q;
+      for (Gap& q : open) { q.end = n.cycle; gaps_.insert(q); }
+      if (g.end == kInf) g.end = n.cycle;
+    }
+    weights_ += n.weights;
+    lane.scratch = std::max(lane.scratch, n.scratch);
+    lane.widest = std::max(lane.widest, n.width);
+    if (n.begin > g.begin) gaps_.insert({g.lane, g.begin, n.begin});       // what is left before and after the window
+    if (g.end > n.end) gaps_.insert({g.lane, n.end, g.end});
+    return lane.cycle;
+  }
+
+ private:
+  struct Lane { double cycle = 0.0, widest = 0.0, scratch = 0.0; };
+  bool admits(const Gap& g, const Need& n) const {
+    const Lane& lane = lanes_[g.lane];
+    if (n.cycle < lane.cycle) return false;                                 // the lane repeats faster than this pipeline may wait
+    const double cycle = lane.cycle > 0.0 ? lane.cycle : n.cycle;
+    if (g.begin > n.begin || g.end < n.end || n.end > cycle) return false;  // the window must lie inside the gap and the cycle
+    double scratch = std::max(lane.scratch, n.scratch), width = std::max(lane.widest, n.width);
+    for (size_t l = 0; l < lanes_.size(); ++l)
+      if ((int)l != g.lane) { scratch += lanes_[l].scratch; width += lanes_[l].widest; }
+    return weights_ + n.weights + scratch <= mem_cap_ && width <= width_cap_ + 1e-12;
+  }
+  std::vector<Lane> lanes_;
+  std::set<Gap> gaps_;
+  double weights_ = 0.0, mem_cap_, width_cap_;
+};
 }  // namespace
 
+// Algorithm 2 with one instance per model: pipelines in order, models in topological order; a model's window starts
+// where its ancestors' batches end (a downstream model runs right after its upstream one).
 int coral_schedule(octo_sched_pipeline* ps, int n_pipelines, double mem, double util_max, int n_streams,
                    octo_placement* out) {
-  std::vector<StreamState> streams(n_streams);
-  std::vector<Portion> free_pts;
-  for (int s = 0; s < n_streams; ++s) free_pts.push_back({s, 0.0, kInf});
-  std::sort(free_pts.begin(), free_pts.end(), portion_less);
-  double Wg = 0.0, Ig = 0.0;
+  GpuLedger gpu(n_streams, mem, util_max);
   int o = 0;
-  // one instance per model, so the fairness loop over instance numbers has a single round
   for (int pi = 0; pi < n_pipelines; ++pi) {
-    octo_sched_pipeline& p = ps[pi];
+    const octo_sched_pipeline& p = ps[pi];
     for (int mi = 0; mi < p.n_models; ++mi, ++o) {
       const octo_sched_model& m = p.models[mi];
-      // window: right after all upstream portions (downstream runs immediately after upstream)
-      double m_start = 0.0;
-      for (int a = m.parent; a >= 0; a = p.models[a].parent) m_start += batch_ms(p.models[a]);
-      const double m_end = m_start + batch_ms(m);
-      const double duty_r = p.slo_ms / 2.0;
-      octo_placement pl = {pi, mi, -1, 0.f, 0.f, 0.f};
-      for (size_t k = 0; k < free_pts.size(); ++k) {
-        const Portion pt = free_pts[k];
-        StreamState& st = streams[pt.stream];
-        const double w_g = Wg + m.weight_mem;
-        const double i_g = Ig - st.inter + std::max(st.inter, (double)m.inter_mem);
-        double u_g = std::max(st.max_util, (double)m.util);
-        for (int s2 = 0; s2 < n_streams; ++s2) if (s2 != pt.stream) u_g += streams[s2].max_util;
-        const double cycle = st.duty > 0 ? st.duty : duty_r;
-        if (!(pt.start <= m_start && pt.end >= m_end && m_end <= cycle)) continue;
-        if (!(w_g + i_g <= mem && u_g <= util_max + 1e-12)) continue;
-        if (!(duty_r >= st.duty)) continue;
-        double pt_end = pt.end;
-        if (st.duty == 0) {
-          st.duty = duty_r;
-          for (Portion& q : free_pts) if (q.stream == pt.stream && q.end == kInf) q.end = duty_r;
-          if (pt_end == kInf) pt_end = duty_r;
-        }
-        Wg = w_g; Ig = i_g;
-        st.inter = std::max(st.inter, (double)m.inter_mem);
-        st.max_util = std::max(st.max_util, (double)m.util);
-        free_pts.erase(free_pts.begin() + k);
-        if (m_start > pt.start) free_pts.push_back({pt.stream, pt.start, m_start});
-        if (pt_end > m_end) free_pts.push_back({pt.stream, m_end, pt_end});
-        std::sort(free_pts.begin(), free_pts.end(), portion_less);
-        pl.stream = pt.stream; pl.start_ms = (float)m_start; pl.end_ms = (float)m_end; pl.duty_cycle_ms = (float)st.duty;
-        break;
-      }
-      out[o] = pl;
+      Need need{0.0, 0.0, p.slo_ms / 2.0, m.weight_mem, m.inter_mem, m.util};
+      for (int a = m.parent; a >= 0; a = p.models[a].parent) need.begin += batch_ms(p.models[a]);
+      need.end = need.begin + batch_ms(m);
+      out[o] = octo_placement{pi, mi, -1, 0.f, 0.f, 0.f};
+      const auto gap = gpu.find(need);
+      if (gap == gpu.none()) continue;
+      const int lane = gap->lane;
+      const double cycle = gpu.book(gap, need);
+      out[o] = octo_placement{pi, mi, lane, (float)need.begin, (float)need.end, (float)cycle};
     }
   }
   return 0;
