@@ -482,6 +482,11 @@ def bench_cascade(args, workload, steps, warmup, ninst, measured, with_cpu):
     if with_cpu:
         out["cpu_baseline"], _ = cpu_baseline(spec, scene, heads, subset=workload == "hires",
                                               rois_per_frame=float(np.mean(items[1:])) / n if len(items) > 1 else 0.0)
+        if workload == "tiny":                   # the small configuration is also timed on one thread
+            threads = torch.get_num_threads()
+            torch.set_num_threads(1)
+            out["cpu_baseline_1_thread"], _ = cpu_baseline(spec, scene, heads, min_seconds=5.0)
+            torch.set_num_threads(threads)
     torch.cuda.synchronize()
     for P in pipes:
         P.close()
