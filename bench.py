@@ -76,14 +76,28 @@ def conv_name(kid: int, dtype: str) -> str:
 
 # HBM traffic per launch of the dominant kernel, from `rocprofv3 --pmc FETCH_SIZE` and `--pmc WRITE_SIZE` runs of
 # `bench.py --calib-copy-mib 256` (counters in KiB per dispatch, scaled by what the same counter reads for the
-# calibration pass of known size).  Valid only for the kernel source it was taken with: keyed by a hash of conv.hip.
+# calibration pass of known size).  Valid only for the kernel sources it was taken with: keyed by their hash.
 TRAFFIC = {
-    # sha256(conv.hip)[:16]: {kernel name: bytes per launch}
-    "dae568f40f073d9b": {
-        "octo::conv_mfma_kernel<_Float16, 128, 128, 2, 2, 8, 1, 2, true, true>": 28915761,
-        "octo::conv_mfma_kernel<_Float16, 64, 128, 2, 2, 8, 1, 3, true, true>": 17868058,
-        "octo::conv_mfma_kernel<_Float16, 64, 64, 2, 2, 8, 1, 4, true, true>": 7607163,
-        "octo::conv_mfma_kernel<_Float16, 32, 128, 1, 4, 4, 2, 4, true, false>": 23949629,
+    # hash of the convolution sources (conv_sources_key): {kernel name: HBM bytes per launch}
+    "0c021c99e876861f": {
+        "octo::conv_mfma_kernel<__bf16, 128, 128, 2, 2, 8, 1, 2, true, true>": 604261385,
+        "octo::conv3x3_patch_kernel<__bf16, 64, 64>": 4243579530,
+        "octo::conv3x3_big_kernel<__bf16, 4, 4, 2, 4>": 1169916604,
+        "octo::conv_mfma_kernel<__bf16, 64, 128, 2, 2, 8, 1, 3, true, true>": 292585672,
+        "octo::conv_mfma_kernel<__bf16, 64, 256, 1, 4, 4, 1, 3, true, true>": 868573743,
+        "octo::stem_conv_kernel<__bf16, 64, 7, 4, true>": 3364542274,
+        "octo::conv3x3_big_kernel<__bf16, 3, 4, 1, 4>": 523449603,
+        "octo::conv3x3_big_kernel<__bf16, 3, 4, 2, 4>": 243465383,
+        "octo::stem_conv_kernel<__bf16, 64, 6, 3, false>": 1808681601,
+        "octo::conv_mfma_kernel<_Float16, 128, 128, 2, 2, 8, 1, 2, true, true>": 28911888,
+        "octo::conv_mfma_kernel<_Float16, 64, 128, 2, 2, 8, 1, 3, true, true>": 17880487,
+        "octo::conv3x3_patch_kernel<_Float16, 64, 64>": 69328096,
+        "octo::conv_mfma_kernel<_Float16, 32, 128, 1, 4, 4, 2, 4, true, false>": 23960966,
+        "octo::conv_mfma_kernel<_Float16, 64, 64, 2, 2, 8, 1, 4, true, true>": 7608197,
+        "octo::stem_conv_kernel<_Float16, 32, 6, 3, false>": 78884047,
+        "octo::stem_conv_kernel<_Float16, 64, 7, 4, true>": 55154737,
+        "octo::conv3x3_patch_kernel<_Float16, 32, 64>": 39924660,
+        "octo::stem_conv_kernel<_Float16, 32, 3, 2, false>": 18001021,
     },
 }
 

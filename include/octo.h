@@ -249,6 +249,31 @@ typedef struct {
 octo_status octo_plan_pipeline(const octo_plan_model* models, int32_t n_models, float slo_ms, double duty_ms, double cycle_share,
                                const int32_t* widths, int32_t n_widths, int32_t total_cus, const int32_t* fixed_bz,
                                octo_sched_model* out, int32_t* batches_per_cycle, float* est_latency_ms, float* est_throughput);
+/* Cross-device placement of one pipeline (Algorithm 1, function ToEdge, Sec. III-B) for two devices: the server and the
+ * edge device at the data source, joined by a link of bandwidth_bytes_per_s.  In: every model on the server with the
+ * batch size octo_cwd_search chose (bz, one of profile_bz).  Depth first from the root: a model moves to the edge if a
+ * configuration for it exists there, its downstream models are then tried (least bursty first), and on the way back it
+ * returns to the server if alpha x (bytes/s entering it) < (bytes/s leaving it) while none of its downstream models is
+ * on the edge (Insights 2 and 3).  Out: on_edge and bz per model, and the two estimates of the result.
+ * Readings of what the paper leaves open: the estimates are octo_est_latency_ms / octo_est_throughput plus Eq. (1)'s
+ * network term - a model fed from the other device (the root is fed by the data source, at the edge) pays
+ * in_bytes / bandwidth per request; "a configuration on the edge" changes only that model's device and batch size and
+ * takes, among the profiled batch sizes that keep the latency estimate within slo_ms / 2 and the edge device within its
+ * compute (sum over edge models of rate x L(bz) / bz <= one second per second), the one with the largest throughput
+ * estimate, the smallest on ties; bytes/s leaving a model = sum over its downstream models of rate x in_bytes, for a
+ * leaf rate x result_bytes. */
+typedef struct {
+  int32_t parent;                 /* -1 for the root (model 0); parents precede children */
+  float rate, burstiness;
+  int32_t n_profile; int32_t profile_bz[8];      /* ascending */
+  float server_ms[8], edge_ms[8]; /* batch latency on either device */
+  double in_bytes;                /* size of one request entering the model */
+  double result_bytes;            /* size of one result leaving the pipeline at this model (leaves) */
+  int32_t bz;                     /* in/out */
+  int32_t on_edge;                /* out */
+} octo_place_model;
+octo_status octo_to_edge(octo_place_model* models, int32_t n_models, float slo_ms, double bandwidth_bytes_per_s, double alpha,
+                         float* est_latency_ms, float* est_throughput);
 /* Lazy dropping (Sec. IV-A): how many requests at the head of an arrival-ordered queue are already older than the
  * objective when a batch is formed (now - arrival > slo; exactly the objective old is still served; counting stops
  * at the first request that is not late). */

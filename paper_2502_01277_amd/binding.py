@@ -85,6 +85,12 @@ class OctoPlanModel(C.Structure):
                 ("width", C.c_int32), ("n_profile", C.c_int32), ("profile_bz", C.c_int32 * 8), ("profile_ms", (C.c_float * 8) * 4)]
 
 
+class OctoPlaceModel(C.Structure):
+    _fields_ = [("parent", C.c_int32), ("rate", C.c_float), ("burstiness", C.c_float), ("n_profile", C.c_int32), ("profile_bz", C.c_int32 * 8),
+                ("server_ms", C.c_float * 8), ("edge_ms", C.c_float * 8), ("in_bytes", C.c_double), ("result_bytes", C.c_double),
+                ("bz", C.c_int32), ("on_edge", C.c_int32)]
+
+
 class OctoExecQueue(C.Structure):
     _fields_ = [("bz", C.c_int32), ("batches_per_cycle", C.c_int32), ("slo_ms", C.c_float),
                 ("head_pool", C.POINTER(C.c_void_p)), ("head_item_bytes", C.POINTER(C.c_size_t)), ("n_levels", C.c_int32),
@@ -129,7 +135,7 @@ EXPORTS = [
     "octo_collect", "octo_set_batch_size", "octo_set_detector_batch", "octo_last_error", "octo_now_ms", "octo_stream_create_masked", "octo_stream_create_range",
     "octo_stream_destroy", "octo_device_cu_count", "octo_cwd_search", "octo_coral_schedule", "octo_est_latency_ms",
     "octo_est_throughput", "octo_burstiness", "octo_batches_per_cycle", "octo_width_to_cus", "octo_choose_width", "octo_late_prefix",
-    "octo_plan_pipeline", "octo_scaler_create", "octo_scaler_observe", "octo_scaler_destroy", "octo_run_model",
+    "octo_plan_pipeline", "octo_to_edge", "octo_scaler_create", "octo_scaler_observe", "octo_scaler_destroy", "octo_run_model",
     "octo_executor_create", "octo_executor_serve", "octo_executor_stats", "octo_executor_scale_events", "octo_executor_streams",
     "octo_executor_results", "octo_executor_last_error", "octo_executor_destroy", "octo_profile_layers", "octo_set_layer_timing", "octo_get_layer_info", "octo_set_stage_timing", "octo_get_stage_ms",
     "octo_debug_get_tensor", "octo_debug_tensor_shape", "octo_debug_set_head", "octo_debug_run_model",
@@ -177,6 +183,7 @@ def lib() -> C.CDLL:
         L.octo_width_to_cus.argtypes = [f64, i32, i32, vp]
         L.octo_choose_width.argtypes = [vp, vp, i32, i32, f64, vp]
         L.octo_late_prefix.argtypes = [vp, i32, f64, f64, vp]
+        L.octo_to_edge.argtypes = [vp, i32, f32, f64, f64, vp, vp]
         L.octo_plan_pipeline.argtypes = [vp, i32, f32, f64, f64, vp, i32, i32, vp, vp, vp, vp, vp]
         L.octo_scaler_create.argtypes = [f64, i32, f64, f64, i32, vp]
         L.octo_scaler_observe.argtypes = [vp, C.c_int64, C.c_int64, i32, vp]
@@ -714,6 +721,22 @@ def plan_pipeline(models: Sequence[dict], slo_ms: float, duty_ms: float, cycle_s
     res = [dict(parent=o.parent, profile={o.profile_bz[k]: o.profile_ms[k] for k in range(o.n_profile)}, rate=o.rate, burstiness=o.burstiness,
                 util=o.util, weight_mem=o.weight_mem, inter_mem=o.inter_mem, bz=o.bz) for o in out]
     return res, [int(k) for k in ks], float(lat.value), float(thr.value)
+
+
+def to_edge(models: Sequence[dict], slo_ms: float, bandwidth_bytes_per_s: float, alpha: float = 1.0):
+    """octo_to_edge.  models: dicts with parent, rate, burstiness, server_ms {bz: ms}, edge_ms {bz: ms}, in_bytes, result_bytes, bz.
+    Returns ([(on_edge, bz)] per model, estimated latency ms, estimated throughput per second)."""
+    arr = (OctoPlaceModel * len(models))()
+    for i, m in enumerate(models):
+        a = arr[i]
+        a.parent, a.rate, a.burstiness, a.in_bytes, a.result_bytes, a.bz = m["parent"], m["rate"], m["burstiness"], m["in_bytes"], m.get("result_bytes", 0.0), m["bz"]
+        bzs = sorted(m["server_ms"])
+        a.n_profile = len(bzs)
+        for k, b in enumerate(bzs):
+            a.profile_bz[k], a.server_ms[k], a.edge_ms[k] = b, m["server_ms"][b], m["edge_ms"][b]
+    lat, thr = C.c_float(), C.c_float()
+    _st(lib().octo_to_edge(arr, len(models), slo_ms, bandwidth_bytes_per_s, alpha, C.byref(lat), C.byref(thr)))
+    return [(bool(a.on_edge), int(a.bz)) for a in arr], float(lat.value), float(thr.value)
 
 
 def sched_pipeline(models: Sequence[dict], slo_ms: float, keep: list) -> OctoSchedPipeline:
