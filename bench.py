@@ -283,6 +283,48 @@ def run_colocate(args):
         P.close()
 
 
+def run_placement(args):
+    """Cross-device placement (Algorithm 1, ToEdge) as a host simulation: the traffic cascade with its batch latencies
+    measured on this GPU - the "edge device" is a stream of --edge-cus compute units (default 8), the "server" one of the rest - and a synthetic
+    bandwidth trace; for every bandwidth the batch sizes are searched on the server (octo_cwd_search) and the models then
+    moved towards the edge (octo_to_edge).  Nothing is served across devices: the line reports placements and estimates."""
+    from paper_2502_01277_amd import binding, executor, zoo
+    spec = zoo.traffic_cascade(dtype="bf16", det_batch=16)
+    P = binding.Pipeline(spec)
+    grid = [1, 2, 4, 8, 16]
+    ecu = args.edge_cus
+    scu = binding.device_cu_count() - ecu
+    prof = executor.profile_pipeline(P, widths=(ecu, scu), iters=3, det_batches=grid, child_batches=[1, 2, 4, 8, 16, 32, 64, 128])
+    P.close()
+    fps, objs = 15.0 * args.camera_scale, 8.0
+    h, w = spec.src_h, spec.src_w
+    parent = {e.child: e.parent for e in spec.edges}
+    models = []
+    for mi, m in enumerate(spec.models):
+        in_bytes = float(h * w * 3) if mi == 0 else float(m.in_h * m.in_w * 3)
+        models.append(dict(parent=parent.get(mi, -1), rate=fps * (objs if mi else 1.0), burstiness=0.0 if mi == 0 else 1.0,
+                           server_ms=dict(prof[mi].by_width[scu]), edge_ms=dict(prof[mi].by_width[ecu]), in_bytes=in_bytes,
+                           result_bytes=32.0 * (objs if mi == 0 else 1.0), weight_mem=1.0, inter_mem=0.0, util=1.0))
+    rows = []
+    for mbit in (5, 20, 50, 100, 200, 500, 1000, 2000, 5000, 20000):
+        bw = mbit * 1e6 / 8.0
+        sm = [dict(parent=m["parent"], profile=m["server_ms"], rate=m["rate"], burstiness=m["burstiness"], util=1.0, bz=1) for m in models]
+        bzs = binding.cwd_search(sm, spec.slo_ms)
+        placed, lat, thr = binding.to_edge([dict(m, bz=b) for m, b in zip(models, bzs)], spec.slo_ms, bw, args.alpha)
+        rows.append({"mbit_per_s": mbit, "server_bz": bzs, "on_edge": [int(e) for e, _ in placed], "bz": [b for _, b in placed],
+                     "est_latency_ms": lat, "est_throughput_per_s": thr})
+        print("%6d Mbit/s  edge %s  bz %s  latency %.1f ms  throughput %.1f /s" % (mbit, rows[-1]["on_edge"], rows[-1]["bz"], lat, thr), file=sys.stderr)
+    best = max(rows, key=lambda r: r["est_throughput_per_s"])
+    print(json.dumps({
+        "metric": "pipeline frames/s within 200 ms SLO on 1 GPU", "value": best["est_throughput_per_s"], "unit": "frames/s (estimate, Eq. 2)",
+        "n_gpus": 1, "steps": len(rows), "warmup": 0, "ms_per_step": 0.0, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "placement simulation: traffic cascade, edge = %d compute units, server = %d, %g frames/s x %g objects, "
+                               "synthetic bandwidth trace, alpha %g" % (ecu, scu, fps, objs, args.alpha), "slo_ms": spec.slo_ms},
+        "profiles_ms": {"edge": [p.by_width[ecu] for p in prof], "server": [p.by_width[scu] for p in prof]},
+        "placement": rows}))
+
+
 def run_surge(args):
     """A workload surge between two runs of the scheduler (Sec. III-D, IV-A): traffic cascade + detector-only pipeline
     on half of the GPU; the cameras of the first send --surge-factor x as many frames during the middle third.  Served by
@@ -517,7 +559,7 @@ def main():
     ap.add_argument("--steps", type=int, default=None, help="timed batches (default: 200 for the high-resolution workload, about 7 s; 4000 for "
                     "the traffic one; 400 otherwise)")
     ap.add_argument("--warmup", type=int, default=None, help="untimed batches before them (default: steps / 20)")
-    ap.add_argument("--workload", default="hires", help="hires (default: 32 x 3840x2160 frames, the largest configuration), traffic, tiny, "
+    ap.add_argument("--workload", default="hires", help="hires (default: 32 x 3840x2160 frames, the largest configuration), traffic, tiny, placement, "
                     "sweep, colocate, surge")
     ap.add_argument("--instances", type=int, default=None,
                     help="copies of the pipeline (own activations and tables) that take batches in turn, each on its own "
@@ -534,6 +576,8 @@ def main():
     ap.add_argument("--camera-scale", type=int, default=1, help="co-location workload: multiply the sixteen cameras")
     ap.add_argument("--det-batch", type=int, default=16, help="co-location workload: largest detector batch")
     ap.add_argument("--slo-ms", type=float, default=200.0, help="co-location workload: the pipelines' latency objective")
+    ap.add_argument("--edge-cus", type=int, default=8, help="placement simulation: compute units of the stream that stands in for the edge device")
+    ap.add_argument("--alpha", type=float, default=1.0, help="placement simulation: how much more network a model's output may cost than its input")
     ap.add_argument("--surge-factor", type=float, default=2.5, help="surge workload: rate multiplier during the middle third")
     args = ap.parse_args()
     if args.instances is None:
@@ -554,6 +598,8 @@ def main():
         return run_sweep(args)
     if args.workload == "colocate":
         return run_colocate(args)
+    if args.workload == "placement":
+        return run_placement(args)
     if args.workload == "surge":
         return run_surge(args)
     # what this machine sustains, measured now: a plain copy and a register-only MFMA loop with random operands
