@@ -100,8 +100,6 @@ __global__ __launch_bounds__(THREADS, MINB) void conv_mfma_kernel(const ConvArgs
   const bool vec_ok = ((a.y_ld | a.y_coff) & 3) == 0 && (!a.res || ((a.res_ld | a.res_coff) & 3) == 0);
   const bool is_silu = a.act == OCTO_ACT_SILU;
   const float act_lo = a.act == OCTO_ACT_RELU ? 0.0f : -INFINITY;
-  const float res_pre = a.res_mode == OCTO_RES_BEFORE_ACT ? 1.0f : 0.0f;
-  const float res_post = a.res_mode == OCTO_RES_AFTER_ACT ? 1.0f : 0.0f;
 
   // weights: one buffer for the whole packed matrix (padded, so never out of range)
   const long long w_bytes = (long long)a.w_rows * a.Kp * ES;
@@ -299,6 +297,10 @@ __global__ __launch_bounds__(THREADS, MINB) void conv_mfma_kernel(const ConvArgs
     // epilogue: a lane holds pixel column l32 of each 32x32 block and 4 groups of 4 consecutive channels
     const bool staged = STAGED && !a.out_f32 && ((a.y_ld | a.y_coff) & (VN - 1)) == 0 && (((uintptr_t)a.y & 15) == 0);
     if (staged) __syncthreads();       // every wavefront is done reading the operand tiles
+    // the arithmetic is compiled once per (residual mode, SiLU or not): see finish4
+    with_epilogue_mode(a.res ? a.res_mode : OCTO_RES_NONE, is_silu, [&](auto res_c, auto silu_c) __attribute__((always_inline)) {
+    constexpr int RES = decltype(res_c)::value;
+    constexpr bool SILU = decltype(silu_c)::value;
 #pragma unroll
     for (int j = 0; j < TP; ++j) {
       const int pl = wp * (BP / WP) + j * 32 + l32;          // pixel inside the tile
@@ -313,7 +315,7 @@ __global__ __launch_bounds__(THREADS, MINB) void conv_mfma_kernel(const ConvArgs
           floatx4 rv[4];
 #pragma unroll
           for (int q = 0; q < 4; ++q) rv[q] = floatx4{0.f, 0.f, 0.f, 0.f};
-          if (a.res) {
+          if (RES != OCTO_RES_NONE) {
             const T* rp = (const T*)a.res + (size_t)p * a.res_ld + a.res_coff + c0 + cblk;
             if (vec_ok && c0 + cblk + 28 <= a.Cout) {
 #pragma unroll
@@ -331,13 +333,8 @@ __global__ __launch_bounds__(THREADS, MINB) void conv_mfma_kernel(const ConvArgs
             const floatx4 b4 = *(const floatx4*)&sBias[cblk + q * 8];
             floatx4 v;
 #pragma unroll
-            for (int e = 0; e < 4; ++e) v[e] = fmaxf(acc[i][j][q * 4 + e] + b4[e] + res_pre * rv[q][e], act_lo);
-            if (is_silu) {
-#pragma unroll
-              for (int e = 0; e < 4; ++e) v[e] = silu(v[e]);
-            }
-#pragma unroll
-            for (int e = 0; e < 4; ++e) v[e] += res_post * rv[q][e];
+            for (int e = 0; e < 4; ++e) v[e] = acc[i][j][q * 4 + e];
+            v = finish4<RES, SILU>(v, b4, rv[q], act_lo);
             if (staged) store4<T>((T*)((char*)smem + (size_t)pl * OPITCH) + cblk + q * 8, v);
             else if (a.out_f32) store4<float>((float*)a.y + o + q * 8, v);
             else store4<T>((T*)a.y + o + q * 8, v);
@@ -352,10 +349,8 @@ __global__ __launch_bounds__(THREADS, MINB) void conv_mfma_kernel(const ConvArgs
               const int c = c0 + cl;
               if (c < a.Cout) {
                 float r = 0.f;
-                if (a.res) r = (float)((const T*)a.res)[(size_t)p * a.res_ld + a.res_coff + c];
-                float t = fmaxf(acc[i][j][q * 4 + e] + sBias[cl] + res_pre * r, act_lo);
-                if (is_silu) t = silu(t);
-                t += res_post * r;
+                if (RES != OCTO_RES_NONE) r = (float)((const T*)a.res)[(size_t)p * a.res_ld + a.res_coff + c];
+                const float t = finish1<RES, SILU>(acc[i][j][q * 4 + e], sBias[cl], r, act_lo);
                 const size_t o = (size_t)p * a.y_ld + a.y_coff + c;
                 if (a.out_f32) ((float*)a.y)[o] = t; else ((T*)a.y)[o] = (T)t;
               }
@@ -364,6 +359,7 @@ __global__ __launch_bounds__(THREADS, MINB) void conv_mfma_kernel(const ConvArgs
         }
       }
     }
+    });
     if (staged) {
       // staged tile -> global memory: consecutive lanes write consecutive 16-byte pieces of a pixel's channels
       __syncthreads();

@@ -58,8 +58,6 @@ __global__ __launch_bounds__(THREADS, 2) void conv3x3_patch_kernel(const ConvArg
   const long long img_elems = (long long)a.H * a.W * a.x_ld;
   const bool is_silu = a.act == OCTO_ACT_SILU;
   const float act_lo = a.act == OCTO_ACT_RELU ? 0.0f : -INFINITY;
-  const float res_pre = a.res_mode == OCTO_RES_BEFORE_ACT ? 1.0f : 0.0f;
-  const float res_post = a.res_mode == OCTO_RES_AFTER_ACT ? 1.0f : 0.0f;
   const int n_slices = a.Cin / CS;
 
   // weight tile: lane -> (row, slot); the slot holds logical vector slot ^ ((row / RPW) % KV)
@@ -162,6 +160,9 @@ __global__ __launch_bounds__(THREADS, 2) void conv3x3_patch_kernel(const ConvArg
     for (int half = 0; half < WC; ++half) {
       __syncthreads();                   // everyone is done with the patch / the previous half has been written out
       if (wc == half) {
+        with_epilogue_mode(a.res ? a.res_mode : OCTO_RES_NONE, is_silu, [&](auto res_c, auto silu_c) __attribute__((always_inline)) {
+        constexpr int RES = decltype(res_c)::value;
+        constexpr bool SILU = decltype(silu_c)::value;
 #pragma unroll
         for (int tp = 0; tp < TPW; ++tp) {
           const int py = wp * TPW + tp;
@@ -176,7 +177,7 @@ __global__ __launch_bounds__(THREADS, 2) void conv3x3_patch_kernel(const ConvArg
             floatx4 rv[4];
 #pragma unroll
             for (int q = 0; q < 4; ++q) rv[q] = floatx4{0.f, 0.f, 0.f, 0.f};
-            if (a.res && inside) {
+            if (RES != OCTO_RES_NONE && inside) {
               const T* rp = (const T*)a.res + p * a.res_ld + a.res_coff + cabs;
 #pragma unroll
               for (int q = 0; q < 4; ++q)
@@ -187,17 +188,13 @@ __global__ __launch_bounds__(THREADS, 2) void conv3x3_patch_kernel(const ConvArg
               const floatx4 b4 = *(const floatx4*)&sBias[half * 64 + cblk + q * 8];
               floatx4 v;
 #pragma unroll
-              for (int e = 0; e < 4; ++e) v[e] = fmaxf(acc[i][tp][q * 4 + e] + b4[e] + res_pre * rv[q][e], act_lo);
-              if (is_silu) {
-#pragma unroll
-                for (int e = 0; e < 4; ++e) v[e] = silu(v[e]);
-              }
-#pragma unroll
-              for (int e = 0; e < 4; ++e) v[e] += res_post * rv[q][e];
+              for (int e = 0; e < 4; ++e) v[e] = acc[i][tp][q * 4 + e];
+              v = finish4<RES, SILU>(v, b4, rv[q], act_lo);
               store4<T>((T*)((char*)sR + (size_t)pl * OPITCH) + cblk + q * 8, v);
             }
           }
         }
+              });
       }
       __syncthreads();
       constexpr int VPR = 8, PPP = THREADS / VPR;            // 8 vectors = 64 channels per pixel

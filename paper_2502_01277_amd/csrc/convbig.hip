@@ -300,8 +300,6 @@ __global__ __launch_bounds__(THREADS, 1) void conv3x3_big_kernel(const ConvArgs 
                       (!a.res || (((a.res_ld | a.res_coff) & 3) == 0 && (((uintptr_t)a.res & 7) == 0)));
   const bool is_silu = a.act == OCTO_ACT_SILU;
   const float act_lo = a.act == OCTO_ACT_RELU ? 0.0f : -INFINITY;
-  const float res_pre = a.res_mode == OCTO_RES_BEFORE_ACT ? 1.0f : 0.0f;
-  const float res_post = a.res_mode == OCTO_RES_AFTER_ACT ? 1.0f : 0.0f;
 
   bool more = true;
   // One K step = kernel tap TAP of the current slice.  The step's 2 x TC x TP MFMAs run in two halves (channels 0..15 and
@@ -392,6 +390,9 @@ __global__ __launch_bounds__(THREADS, 1) void conv3x3_big_kernel(const ConvArgs 
     // ---- epilogue of the finished tile, from registers: a lane holds one pixel of each 32 x 32 block and 4 groups of 4
     // consecutive channels; the tile's bias is in sBias[cpar] (its loads were among those already awaited)
     const float* bias_s = sBias + cpar * THREADS;
+    with_epilogue_mode(a.res ? a.res_mode : OCTO_RES_NONE, is_silu, [&](auto res_c, auto silu_c) __attribute__((always_inline)) {
+    constexpr int RES = decltype(res_c)::value;
+    constexpr bool SILU = decltype(silu_c)::value;
 #pragma unroll
     for (int j = 0; j < TP; ++j) {
       if (epix[j] < 0) continue;
@@ -399,7 +400,7 @@ __global__ __launch_bounds__(THREADS, 1) void conv3x3_big_kernel(const ConvArgs 
 #pragma unroll
       for (int i = 0; i < TC; ++i) {
         const int cblk = wc * (TC * 32) + i * 32 + g * 4;
-        const T* rp = a.res ? (const T*)a.res + p * a.res_ld + a.res_coff + ec0 + cblk : nullptr;
+        const T* rp = RES != OCTO_RES_NONE ? (const T*)a.res + p * a.res_ld + a.res_coff + ec0 + cblk : nullptr;
         T* yp = (T*)a.y + p * a.y_ld + a.y_coff + ec0 + cblk;
         if (vec_ok && ec0 + cblk + 28 <= a.Cout) {
           floatx4 rv[4];
@@ -414,13 +415,8 @@ __global__ __launch_bounds__(THREADS, 1) void conv3x3_big_kernel(const ConvArgs 
             const floatx4 b4 = *(const floatx4*)&bias_s[cblk + q * 8];
             floatx4 v;
 #pragma unroll
-            for (int e = 0; e < 4; ++e) v[e] = fmaxf(acc[i][j][q * 4 + e] + b4[e] + res_pre * rv[q][e], act_lo);
-            if (is_silu) {
-#pragma unroll
-              for (int e = 0; e < 4; ++e) v[e] = silu(v[e]);
-            }
-#pragma unroll
-            for (int e = 0; e < 4; ++e) v[e] += res_post * rv[q][e];
+            for (int e = 0; e < 4; ++e) v[e] = acc[i][j][q * 4 + e];
+            v = finish4<RES, SILU>(v, b4, rv[q], act_lo);
             store4<T>(yp + q * 8, v);
           }
         } else {
@@ -431,9 +427,7 @@ __global__ __launch_bounds__(THREADS, 1) void conv3x3_big_kernel(const ConvArgs 
               const int cl = cblk + q * 8 + e;
               if (ec0 + cl < a.Cout) {
                 const float r = rp ? (float)rp[q * 8 + e] : 0.f;
-                float t = fmaxf(acc[i][j][q * 4 + e] + bias_s[cl] + res_pre * r, act_lo);
-                if (is_silu) t = silu(t);
-                t += res_post * r;
+                const float t = finish1<RES, SILU>(acc[i][j][q * 4 + e], bias_s[cl], r, act_lo);
                 yp[q * 8 + e] = (T)t;
               }
             }
@@ -442,6 +436,7 @@ __global__ __launch_bounds__(THREADS, 1) void conv3x3_big_kernel(const ConvArgs 
         __builtin_amdgcn_sched_barrier(0);   // one block at a time: keeps the epilogue's register demand low
       }
     }
+    });
     cpar ^= 1;
   }
   // the loaders ran NST steps past the end (out-of-range offsets: zeros): let them land before the workgroup's LDS is released

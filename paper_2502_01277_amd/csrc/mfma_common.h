@@ -1,6 +1,8 @@
 // Pieces shared by the matrix-core kernels: 16-byte operand vectors, the MFMA instruction per storage type, packed
 // loads / stores of four values, the fast SiLU and the buffer-load constants.
 #pragma once
+#include <type_traits>
+
 #include "octo_internal.h"
 
 namespace octo {
@@ -59,6 +61,46 @@ __device__ __forceinline__ void store4(T* p, floatx4 v) {
 __device__ __forceinline__ unsigned udiv(unsigned n, unsigned magic, unsigned shift) { return __umulhi(n, magic) >> shift; }
 // x * sigmoid(x) with the hardware exp2 / reciprocal (about 1 ulp each: far below the storage precision)
 __device__ __forceinline__ float silu(float v) { return v * __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(v * -1.4426950408889634f)); }
+
+// Epilogue arithmetic of four values, specialised at compile time by where the residual enters (OCTO_RES_*) and whether
+// the activation is SiLU (otherwise max with act_lo: 0 for ReLU, -inf for none).  The epilogue is vector arithmetic that
+// competes with the matrix pipe for issue slots - 64 values per lane and tile - so terms that a layer does not have are
+// compiled out instead of being multiplied by zero.
+template <int RES, bool SILU>
+__device__ __forceinline__ floatx4 finish4(floatx4 acc, floatx4 bias, floatx4 res, float act_lo) {
+  floatx4 v;
+#pragma unroll
+  for (int e = 0; e < 4; ++e) {
+    float t = acc[e] + bias[e];
+    if (RES == OCTO_RES_BEFORE_ACT) t += res[e];
+    t = SILU ? silu(t) : fmaxf(t, act_lo);
+    if (RES == OCTO_RES_AFTER_ACT) t += res[e];
+    v[e] = t;
+  }
+  return v;
+}
+template <int RES, bool SILU>
+__device__ __forceinline__ float finish1(float acc, float bias, float res, float act_lo) {
+  float t = acc + bias;
+  if (RES == OCTO_RES_BEFORE_ACT) t += res;
+  t = SILU ? silu(t) : fmaxf(t, act_lo);
+  if (RES == OCTO_RES_AFTER_ACT) t += res;
+  return t;
+}
+// Calls f(residual mode, SiLU?) with both as compile-time constants (std::integral_constant) for a uniform run-time pair.
+template <typename F>
+__device__ __forceinline__ void with_epilogue_mode(int res_mode, bool is_silu, F&& f) {
+  using std::integral_constant;
+  if (is_silu) {
+    if (res_mode == OCTO_RES_BEFORE_ACT) f(integral_constant<int, OCTO_RES_BEFORE_ACT>{}, integral_constant<bool, true>{});
+    else if (res_mode == OCTO_RES_AFTER_ACT) f(integral_constant<int, OCTO_RES_AFTER_ACT>{}, integral_constant<bool, true>{});
+    else f(integral_constant<int, OCTO_RES_NONE>{}, integral_constant<bool, true>{});
+  } else {
+    if (res_mode == OCTO_RES_BEFORE_ACT) f(integral_constant<int, OCTO_RES_BEFORE_ACT>{}, integral_constant<bool, false>{});
+    else if (res_mode == OCTO_RES_AFTER_ACT) f(integral_constant<int, OCTO_RES_AFTER_ACT>{}, integral_constant<bool, false>{});
+    else f(integral_constant<int, OCTO_RES_NONE>{}, integral_constant<bool, false>{});
+  }
+}
 
 constexpr int THREADS = 256;
 constexpr unsigned BUF_FLAGS = 0x00020000u;      // raw buffer, 32-bit data format
