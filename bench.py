@@ -79,25 +79,25 @@ def conv_name(kid: int, dtype: str) -> str:
 # calibration pass of known size).  Valid only for the kernel sources it was taken with: keyed by their hash.
 TRAFFIC = {
     # hash of the convolution sources (conv_sources_key): {kernel name: HBM bytes per launch}
-    "0c021c99e876861f": {
-        "octo::conv_mfma_kernel<__bf16, 128, 128, 2, 2, 8, 1, 2, true, true>": 604261385,
-        "octo::conv3x3_patch_kernel<__bf16, 64, 64>": 4243579530,
-        "octo::conv3x3_big_kernel<__bf16, 4, 4, 2, 4>": 1169916604,
-        "octo::conv_mfma_kernel<__bf16, 64, 128, 2, 2, 8, 1, 3, true, true>": 292585672,
-        "octo::conv_mfma_kernel<__bf16, 64, 256, 1, 4, 4, 1, 3, true, true>": 868573743,
-        "octo::stem_conv_kernel<__bf16, 64, 7, 4, true>": 3364542274,
-        "octo::conv3x3_big_kernel<__bf16, 3, 4, 1, 4>": 523449603,
-        "octo::conv3x3_big_kernel<__bf16, 3, 4, 2, 4>": 243465383,
-        "octo::stem_conv_kernel<__bf16, 64, 6, 3, false>": 1808681601,
-        "octo::conv_mfma_kernel<_Float16, 128, 128, 2, 2, 8, 1, 2, true, true>": 28911888,
-        "octo::conv_mfma_kernel<_Float16, 64, 128, 2, 2, 8, 1, 3, true, true>": 17880487,
-        "octo::conv3x3_patch_kernel<_Float16, 64, 64>": 69328096,
-        "octo::conv_mfma_kernel<_Float16, 32, 128, 1, 4, 4, 2, 4, true, false>": 23960966,
-        "octo::conv_mfma_kernel<_Float16, 64, 64, 2, 2, 8, 1, 4, true, true>": 7608197,
-        "octo::stem_conv_kernel<_Float16, 32, 6, 3, false>": 78884047,
-        "octo::stem_conv_kernel<_Float16, 64, 7, 4, true>": 55154737,
-        "octo::conv3x3_patch_kernel<_Float16, 32, 64>": 39924660,
-        "octo::stem_conv_kernel<_Float16, 32, 3, 2, false>": 18001021,
+    "ba8f2a7f41cee1f9": {
+        "octo::conv_mfma_kernel<__bf16, 128, 128, 2, 2, 8, 1, 2, true, true>": 606087757,
+        "octo::conv3x3_patch_kernel<__bf16, 64, 64>": 4244923309,
+        "octo::conv3x3_big_kernel<__bf16, 4, 4, 2, 4>": 1154116998,
+        "octo::conv_mfma_kernel<__bf16, 64, 128, 2, 2, 8, 1, 3, true, true>": 292765310,
+        "octo::conv_mfma_kernel<__bf16, 64, 256, 1, 4, 4, 1, 3, true, true>": 873243687,
+        "octo::stem_conv_kernel<__bf16, 64, 7, 4, true>": 3364805210,
+        "octo::conv3x3_big_kernel<__bf16, 3, 4, 1, 4>": 525972204,
+        "octo::conv3x3_big_kernel<__bf16, 3, 4, 2, 4>": 244992614,
+        "octo::stem_conv_kernel<__bf16, 64, 6, 3, false>": 1821761106,
+        "octo::conv_mfma_kernel<_Float16, 128, 128, 2, 2, 8, 1, 2, true, true>": 28888981,
+        "octo::conv_mfma_kernel<_Float16, 64, 128, 2, 2, 8, 1, 3, true, true>": 17879481,
+        "octo::conv3x3_patch_kernel<_Float16, 64, 64>": 69342979,
+        "octo::conv_mfma_kernel<_Float16, 32, 128, 1, 4, 4, 2, 4, true, false>": 23975865,
+        "octo::conv_mfma_kernel<_Float16, 64, 64, 2, 2, 8, 1, 4, true, true>": 7629565,
+        "octo::stem_conv_kernel<_Float16, 32, 6, 3, false>": 78884065,
+        "octo::stem_conv_kernel<_Float16, 64, 7, 4, true>": 55154693,
+        "octo::conv3x3_patch_kernel<_Float16, 32, 64>": 39949184,
+        "octo::stem_conv_kernel<_Float16, 32, 3, 2, false>": 18001020,
     },
 }
 
