@@ -21,6 +21,9 @@ namespace octo {
 
 constexpr int P3_TH = 8, P3_TW = 32;       // output tile: rows x columns
 
+// wait until at most N of this wave's vector-memory operations are outstanding
+template <int N> __device__ __forceinline__ void wait_vmcnt() { asm volatile("s_waitcnt vmcnt(%0)" :: "n"(N) : "memory"); }
+
 // BC output channels per tile (64: four waves of 64 channels x 2 pixel rows; 128: 2 x 2 waves of 64 channels x 4 rows)
 template <typename T, int CS, int BC>
 __global__ __launch_bounds__(THREADS, 2) void conv3x3_patch_kernel(const ConvArgs a) {
@@ -42,7 +45,8 @@ __global__ __launch_bounds__(THREADS, 2) void conv3x3_patch_kernel(const ConvArg
   constexpr int ASTAGE = BC * KV;              // vectors per ring stage
   constexpr int OPITCH = 64 * 2 + 16;          // the output tile is staged 64 channels at a time
   constexpr int REGION_VECS = (PLOADS * THREADS > BP * OPITCH / 16) ? PLOADS * THREADS : BP * OPITCH / 16;
-  __shared__ u32x4 sA[2 * ASTAGE];
+  constexpr int NS = 4;                        // weight ring: the tile of tap t + NS - 1 is requested while tap t is computed
+  __shared__ u32x4 sA[NS * ASTAGE];
   __shared__ u32x4 sR[REGION_VECS];            // input patch slice, then the staged output tile
   __shared__ float sBias[BC];
 
@@ -70,7 +74,6 @@ __global__ __launch_bounds__(THREADS, 2) void conv3x3_patch_kernel(const ConvArg
   constexpr unsigned PASS_BYTES = RP * KV * 16, STAGE_BYTES = ASTAGE * 16;
   const unsigned patch_wave = (unsigned)__builtin_amdgcn_readfirstlane((int)((unsigned)(uintptr_t)sR + (unsigned)wave * 1024u));
 
-  int step = 0;                                        // ring position of the next weight tile to be consumed
   const long long per_die = (n_tiles + 7) >> 3;        // contiguous chunk of the tile list per die (see conv.hip)
   for (long long t = blockIdx.x; t < per_die * 8; t += gridDim.x) {
     const long long tile = (t & 7) * per_die + (t >> 3);
@@ -94,6 +97,30 @@ __global__ __launch_bounds__(THREADS, 2) void conv3x3_patch_kernel(const ConvArg
       for (int j = 0; j < TPW; ++j)
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
+
+    // The residual values this lane will add are requested now and converted in the epilogue, so that their trip to
+    // memory runs beside the patch's instead of after the main loop.
+    u32x2 rraw[TPW][2][4];
+#pragma unroll
+    for (int tp = 0; tp < TPW; ++tp)
+#pragma unroll
+      for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) rraw[tp][i][q] = u32x2{0u, 0u};
+    if (a.res && a.res_mode != OCTO_RES_NONE) {
+#pragma unroll
+      for (int tp = 0; tp < TPW; ++tp) {
+        const int oy = oy0 + wp * TPW + tp, ox = ox0 + l32;
+        if (oy < a.Ho && ox < a.Wo) {
+          const T* rp = (const T*)a.res + (((size_t)img * a.Ho + oy) * a.Wo + ox) * a.res_ld + a.res_coff + c0 + wc * 64 + g * 4;
+#pragma unroll
+          for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+              if (c0 + wc * 64 + g * 4 + i * 32 + q * 8 + 4 <= a.Cout) rraw[tp][i][q] = *(const u32x2*)(rp + i * 32 + q * 8);
+        }
+      }
+    }
 
     // this lane's pixel of block tp = 0 at tap (0, 0): patch pixel index; its slot swizzle changes with the tap
     const int ppix0 = (wp * TPW) * PW + l32;
@@ -125,13 +152,20 @@ __global__ __launch_bounds__(THREADS, 2) void conv3x3_patch_kernel(const ConvArg
         asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
                      :: "s"(patch_wave + i * (THREADS * 16)), "v"(off), "s"(rsrc_x) : "memory");
       }
-      OCTO_P3_WEIGHTS(cs0 * 2, step & 1)                              // tap 0 of this slice
+#pragma unroll
+      for (int t = 0; t < NS - 1; ++t) OCTO_P3_WEIGHTS((t * a.Cin + cs0) * 2, t)   // taps 0 .. NS-2 of this slice
 #pragma unroll 1
       for (int tap = 0; tap < 9; ++tap) {
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");              // this wave's part of the weight tile has landed
-        __syncthreads();                                              // ... everyone's, and the patch; the other stage is free
-        if (tap < 8) OCTO_P3_WEIGHTS(((tap + 1) * a.Cin + cs0) * 2, (step + 1) & 1)
-        const u32x4* pa = sA + (step & 1) * ASTAGE;
+        // This wave's part of the patch and of tap's weight tile has landed: loads complete in the order they were
+        // issued, and the only ones issued after them are the weight tiles of the following taps (LA loads each) -
+        // NS - 2 of them, fewer at the end.  A step of 16 MFMAs is shorter than a trip to the L2, so a ring of two
+        // stages left every tap waiting for its weights.
+        if (tap <= 9 - NS + 1) wait_vmcnt<(NS - 2) * LA>();
+        else if (tap == 9 - NS + 2 && NS > 3) wait_vmcnt<(NS - 3) * LA>();
+        else wait_vmcnt<0>();
+        __syncthreads();                                              // ... everyone's; the stage read at tap - 1 is free
+        if (tap + NS - 1 < 9) OCTO_P3_WEIGHTS(((tap + NS - 1) * a.Cin + cs0) * 2, (tap + NS - 1) % NS)
+        const u32x4* pa = sA + (tap % NS) * ASTAGE;
         const int r = tap / 3, s = tap - 3 * r;
         const int pp = ppix0 + r * PW + s;                            // patch pixel of block 0; block 1 is one row down
 #pragma unroll
@@ -149,7 +183,6 @@ __global__ __launch_bounds__(THREADS, 2) void conv3x3_patch_kernel(const ConvArg
 #pragma unroll
             for (int tp = 0; tp < TPW; ++tp) acc[i][tp] = E::mfma(fa[i], fb[tp], acc[i][tp]);
         }
-        ++step;
       }
     }
 #undef OCTO_P3_WEIGHTS
@@ -167,29 +200,18 @@ __global__ __launch_bounds__(THREADS, 2) void conv3x3_patch_kernel(const ConvArg
         for (int tp = 0; tp < TPW; ++tp) {
           const int py = wp * TPW + tp;
           const int pl = py * TW + l32;
-          const int oy = oy0 + py, ox = ox0 + l32;
-          const bool inside = oy < a.Ho && ox < a.Wo;
-          const size_t p = ((size_t)img * a.Ho + oy) * a.Wo + ox;
 #pragma unroll
           for (int i = 0; i < 2; ++i) {
             const int cblk = i * 32 + g * 4;                 // within the 64 channels of this half
-            const int cabs = c0 + half * 64 + cblk;
-            floatx4 rv[4];
-#pragma unroll
-            for (int q = 0; q < 4; ++q) rv[q] = floatx4{0.f, 0.f, 0.f, 0.f};
-            if (RES != OCTO_RES_NONE && inside) {
-              const T* rp = (const T*)a.res + p * a.res_ld + a.res_coff + cabs;
-#pragma unroll
-              for (int q = 0; q < 4; ++q)
-                if (cabs + q * 8 + 4 <= a.Cout) rv[q] = load4<T>(rp + q * 8);
-            }
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
               const floatx4 b4 = *(const floatx4*)&sBias[half * 64 + cblk + q * 8];
               floatx4 v;
 #pragma unroll
               for (int e = 0; e < 4; ++e) v[e] = acc[i][tp][q * 4 + e];
-              v = finish4<RES, SILU>(v, b4, rv[q], act_lo);
+              typedef T t4 __attribute__((ext_vector_type(4)));
+              const t4 r4 = __builtin_bit_cast(t4, rraw[tp][i][q]);
+              v = finish4<RES, SILU>(v, b4, floatx4{(float)r4[0], (float)r4[1], (float)r4[2], (float)r4[3]}, act_lo);
               store4<T>((T*)((char*)sR + (size_t)pl * OPITCH) + cblk + q * 8, v);
             }
           }
@@ -241,7 +263,7 @@ static hipError_t launch_p3_cfg(const ConvArgs& a, int num_cu, hipStream_t s, in
 // 3x3 / stride 1 / pad 1 layers in the 16-bit types whose input channels come in whole slices of 64 (or 32) and whose
 // tensors allow 16-byte accesses; anything else is left to the general kernel (hipErrorNotSupported).
 hipError_t launch_conv3x3_patch(int dtype, const ConvArgs& a, int num_cu, hipStream_t s, int* kernel_id, ConvTiming tm) {
-  if (dtype == OCTO_F32 || a.pair_view || a.kh != 3 || a.kw != 3 || a.stride_h != 1 || a.stride_w != 1 || a.pad_h != 1 || a.pad_w != 1 || a.out_f32)
+  if ((dtype != OCTO_F16 && dtype != OCTO_BF16) || a.pair_view || a.kh != 3 || a.kw != 3 || a.stride_h != 1 || a.stride_w != 1 || a.pad_h != 1 || a.pad_w != 1 || a.out_f32)
     return hipErrorNotSupported;
   if (a.Ho != a.H || a.Wo != a.W || a.K != 9 * a.Cin || a.w_rows < (a.Cout + 127) / 128 * 128) return hipErrorNotSupported;
   if (((a.x_ld | a.x_coff | a.y_ld | a.y_coff) & 7) || ((uintptr_t)a.x & 15) || ((uintptr_t)a.y & 15)) return hipErrorNotSupported;

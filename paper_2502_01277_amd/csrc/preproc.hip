@@ -182,12 +182,19 @@ __global__ __launch_bounds__(64) void crop_resize_rows_kernel(const ResizeArgs a
   const int wq = a.dst_w / 4;
   int n_items = a.n;
   if (a.n_dyn) { int d = *a.n_dyn; n_items = d < a.n ? (d < 0 ? 0 : d) : a.n; }
-  const unsigned total_rows = (unsigned)n_items * (unsigned)a.dst_h;       // < 2^31 (checked by the launcher)
   const int lane = threadIdx.x;
   T* dst = (T*)a.dst;
-  for (unsigned row = blockIdx.x; row < total_rows; row += gridDim.x) {
-    const int roi = (int)fast_div(row, a.div_h);
-    const int y = (int)(row - (unsigned)roi * (unsigned)a.dst_h);
+  // Workgroup b runs on die b % 8, and each die has its own L2.  The rows of one ROI tap the same source lines again
+  // and again (an enlarged crop reads every source row several times), so all rows of ROI r are given to die r % 8:
+  // spread over the dies, each of the eight L2s fetched the ROI's pixels from memory for itself.  Within a die the
+  // workgroups take consecutive rows, so the rows of one ROI are in flight together.  The grid is a multiple of 8.
+  const unsigned die = blockIdx.x & 7u, slot = blockIdx.x >> 3, slots = gridDim.x >> 3;
+  const unsigned die_rois = (unsigned)n_items > die ? ((unsigned)n_items - die + 7u) >> 3 : 0u;
+  const unsigned die_rows = die_rois * (unsigned)a.dst_h;                  // < 2^31 (checked by the launcher)
+  for (unsigned row = slot; row < die_rows; row += slots) {
+    const unsigned nth = fast_div(row, a.div_h);
+    const int roi = (int)(die + 8u * nth);
+    const int y = (int)(row - nth * (unsigned)a.dst_h);
     const octo_roi r = a.rois[roi];
     const int fr = clampi(r.frame, 0, a.n_frames - 1);
     const uint8_t* base = a.frames[fr];
@@ -324,9 +331,10 @@ template <typename T> static hipError_t letterbox_t(const ResizeArgs& a, hipStre
   return exact ? letterbox_e<T, true>(a, g, s) : letterbox_e<T, false>(a, g, s);
 }
 template <typename T> static hipError_t crop_t(const ResizeArgs& a, hipStream_t s) {
-  // one 64-thread workgroup per output row, at most 32 per compute unit at a time, striding over the rows
-  const long long rows = (long long)a.n * a.dst_h;
-  const unsigned row_grid = (unsigned)(rows < 256 * 32 ? (rows < 1 ? 1 : rows) : 256 * 32);
+  // one 64-thread workgroup per output row, at most 32 per compute unit at a time; each die strides over the rows of
+  // its own ROIs (every eighth), so the grid is 8 x the workgroups one die gets
+  const long long die_rows = (long long)((a.n + 7) / 8) * a.dst_h;
+  const unsigned row_grid = 8u * (unsigned)(die_rows < 32 * 32 ? (die_rows < 1 ? 1 : die_rows) : 32 * 32);
   if (a.dst_c == 4 && ((uintptr_t)a.dst & 15) == 0 && a.dst_w % 4 == 0) {
     hipLaunchKernelGGL((crop_resize_rows_kernel<T, true>), dim3(row_grid), dim3(64), 0, s, a);
   } else if (a.dst_c == 4) {
