@@ -48,7 +48,10 @@ typedef enum {
   OCTO_ENOTREADY = -6  /* non-blocking collect: nothing has finished yet */
 } octo_status;
 
-typedef enum { OCTO_F32 = 0, OCTO_F16 = 1, OCTO_BF16 = 2 } octo_dtype;
+/* OCTO_F8 is 8-bit floating point in the OCP E4M3 format: 1 sign bit, 4 exponent bits (bias 7), 3 mantissa bits,
+ * subnormals down to 2^-9, no infinities, 0x7F and 0xFF are NaN, largest finite value 448.  Only octo_op_conv and the
+ * two conversion helpers below take it; models of a pipeline are stored in one of the other three. */
+typedef enum { OCTO_F32 = 0, OCTO_F16 = 1, OCTO_BF16 = 2, OCTO_F8 = 3 } octo_dtype;
 typedef enum { OCTO_CONV = 0, OCTO_MAXPOOL = 1, OCTO_UPSAMPLE2X = 2, OCTO_CONCAT = 3, OCTO_ADD = 4, OCTO_GAP = 5, OCTO_FC = 6 } octo_op;
 typedef enum { OCTO_ACT_NONE = 0, OCTO_ACT_RELU = 1, OCTO_ACT_SILU = 2 } octo_act;
 typedef enum { OCTO_RES_NONE = 0, OCTO_RES_BEFORE_ACT = 1, OCTO_RES_AFTER_ACT = 2 } octo_res_mode;
@@ -404,7 +407,8 @@ octo_status octo_get_stage_ms(octo_pipeline* p, float* ms, int32_t cap, int32_t*
 /* Microbenchmarks of the GPU itself, for "fraction of what this machine sustains" beside the datasheet fractions.
  * octo_probe_copy: a plain 16-byte-per-lane copy of `bytes` from d_src to d_dst (device, 16-byte aligned), `reps`
  * timed passes after a warm-up; *gb_per_s = (bytes read + bytes written) / median time.
- * octo_probe_mfma: a register-only loop of the 32x32x16 matrix instruction of `dtype` (OCTO_F16 / OCTO_BF16) with
+ * octo_probe_mfma: a register-only loop of the 32x32x16 matrix instruction of `dtype` (OCTO_F16 / OCTO_BF16; for
+ * OCTO_F8 the 32x32x64 instruction on E4M3 operands) with
  * random operand values, 16 independent accumulators per wavefront, one workgroup of four wavefronts per compute
  * unit, `iters` x 16 instructions per wavefront; d_scratch (device, at least CUs x 1 KiB) receives checksums;
  * *tflops = dense FLOP / median time.  Both synchronise `hip_stream`. */
@@ -448,6 +452,48 @@ octo_status octo_op_crop_resize(const void* d_frame_ptrs, const void* d_pitches,
                                 const octo_roi* d_rois, const int32_t* d_n_rois, int32_t cap,
                                 void* d_dst, int32_t out_h, int32_t out_w, int32_t dtype, const float* scale3, const float* bias3,
                                 void* hip_stream);
+/* One convolution layer, batched over n items (the model execution whose batch latency L_m(bz) Eq. (1) is about; the
+ * pipeline runs its layers through the same kernels):
+ *   y[i,p,q,k] = act(bias[k] + sum_{r,s,c} x[i, p*stride + r - pad, q*stride + s - pad, c] * w[k,r,s,c]  (+ residual))
+ * on NHWC device tensors of `dtype`, accumulated in fp32.  x: [n][h][w] pixels x_ld elements apart (x_ld >= cin),
+ * y: [n][ho][wo] pixels y_ld apart with ho = (h + 2 pad - kh) / stride + 1, residual (or NULL) shaped like y with pitch
+ * res_ld, added before or after the activation (octo_res_mode).  out_f32 != 0 writes y as fp32 instead of `dtype`.
+ * d_w: the weights in the packed layout octo_op_conv_pack makes (device copy of it, octo_op_conv_packed_bytes long);
+ * d_bias: device, octo_op_conv_padded_cout(cout) floats, zero beyond cout.  The library keeps no pointer after the
+ * launch.  *kernel_id (may be NULL) receives the id of the kernel chosen (see octo_get_layer_info).
+ * OCTO_F8 (not from the paper: a reduced-precision variant of the same kernel on the 8-bit matrix instructions):
+ * x, w, residual and y hold E4M3 codes; real value = code value times a scale the caller chose.
+ *   y_real = act(acc * d_scale[k] + bias[k]  (+ res_code_value * res_scale)),   y_code = E4M3(y_real * y_inv_scale)
+ * with d_scale (device, padded like the bias) = weight scale of channel k times the scale of x; the conversion rounds
+ * to nearest even and saturates at +-448 (what a NaN result is stored as is not specified).  Needs cin, x_ld (and y_ld,
+ * res_ld unless out_f32 / no residual: else a slower element-wise store is used) multiples of 16 and 16-byte aligned
+ * x.  For the other types d_scale, res_scale and y_inv_scale are ignored.
+ * Errors: OCTO_EINVAL for null / non-positive / misaligned arguments and shapes beyond the kernel's 32-bit offsets. */
+typedef struct octo_conv_op {
+  int32_t dtype;
+  int32_t n, h, w, cin, x_ld;
+  int32_t cout, kh, kw, stride, pad;
+  int32_t act, res_mode, out_f32;
+  int32_t y_ld, res_ld;
+  const void* d_x;
+  const void* d_w;
+  const float* d_bias;
+  const float* d_scale;
+  const void* d_res;
+  void* d_y;
+  float res_scale, y_inv_scale;
+} octo_conv_op;
+octo_status octo_op_conv(const octo_conv_op* op, void* hip_stream, int32_t* kernel_id);
+/* Packed weight layout (host only, no GPU).  w: [cout][kh][kw][cin] in `dtype` (host).  packed: host buffer of
+ * octo_op_conv_packed_bytes(...) bytes, fully written (rows padded to whole K steps and the row count to
+ * octo_op_conv_padded_cout(cout), zero filled).  Copy it to the device as it is. */
+size_t octo_op_conv_packed_bytes(int32_t dtype, int32_t cout, int32_t kh, int32_t kw, int32_t cin);
+int32_t octo_op_conv_padded_cout(int32_t cout);
+octo_status octo_op_conv_pack(int32_t dtype, const void* w, int32_t cout, int32_t kh, int32_t kw, int32_t cin, void* packed);
+/* E4M3 conversion on the host (no GPU): dst[i] = E4M3(src[i] * inv_scale), round to nearest even, saturating at
+ * +-448, NaN -> 0x7F; and back: dst[i] = value(src[i]) * scale (NaN codes give NaN). */
+octo_status octo_quantize_e4m3(const float* src, size_t n, float inv_scale, uint8_t* dst);
+octo_status octo_dequantize_e4m3(const uint8_t* src, size_t n, float scale, float* dst);
 /* Decode + threshold of n items: d_heads[l] dense [n][G_l][G_l][A*(5+C)].  Appends candidates with
  * score > thr to d_cand[item*cap ...] (order unspecified), d_count[item] = number found (may exceed cap:
  * then only cap were stored).  Geometry and thresholds are read from `model`. */

@@ -22,7 +22,7 @@ LIB_PATH = os.path.join(_HERE, "libocto.so")
 
 MAX_LEVELS, MAX_ANCHORS, MAX_EDGES, MAX_CHILD_LABELS, MAX_LAYER_INPUTS = 3, 3, 4, 2, 4
 OK, EINVAL, ENOMEM, ECAP, ESTATE, EHIP, ENOTREADY = 0, -1, -2, -3, -4, -5, -6
-DTYPES = {"f32": 0, "f16": 1, "bf16": 2}
+DTYPES = {"f32": 0, "f16": 1, "bf16": 2, "f8": 3}       # f8 (E4M3): octo_op_conv only
 OPS = {"conv": 0, "maxpool": 1, "upsample2x": 2, "concat": 3, "add": 4, "gap": 5, "fc": 6}
 KINDS = {"detector": 0, "classifier": 1}
 
@@ -129,6 +129,14 @@ class OctoScaleEvent(C.Structure):
     _fields_ = [("t_s", C.c_float), ("queue", C.c_int32), ("change", C.c_int32)]
 
 
+class OctoConvOp(C.Structure):
+    _fields_ = [("dtype", C.c_int32), ("n", C.c_int32), ("h", C.c_int32), ("w", C.c_int32), ("cin", C.c_int32), ("x_ld", C.c_int32),
+                ("cout", C.c_int32), ("kh", C.c_int32), ("kw", C.c_int32), ("stride", C.c_int32), ("pad", C.c_int32),
+                ("act", C.c_int32), ("res_mode", C.c_int32), ("out_f32", C.c_int32), ("y_ld", C.c_int32), ("res_ld", C.c_int32),
+                ("d_x", C.c_void_p), ("d_w", C.c_void_p), ("d_bias", C.c_void_p), ("d_scale", C.c_void_p), ("d_res", C.c_void_p),
+                ("d_y", C.c_void_p), ("res_scale", C.c_float), ("y_inv_scale", C.c_float)]
+
+
 # Every symbol include/octo.h declares.
 EXPORTS = [
     "octo_pipeline_workspace_size", "octo_pipeline_create", "octo_pipeline_destroy", "octo_submit_frames", "octo_run",
@@ -141,6 +149,7 @@ EXPORTS = [
     "octo_debug_get_tensor", "octo_debug_tensor_shape", "octo_debug_set_head", "octo_debug_run_model",
     "octo_debug_get_detections", "octo_debug_get_rois", "octo_debug_get_labels", "octo_letterbox_geometry", "octo_op_letterbox",
     "octo_op_crop_resize", "octo_op_decode", "octo_op_topk", "octo_op_nms", "octo_op_nms_scratch_bytes", "octo_op_nms_static", "octo_op_compact", "octo_probe_copy", "octo_probe_mfma",
+    "octo_op_conv", "octo_op_conv_packed_bytes", "octo_op_conv_padded_cout", "octo_op_conv_pack", "octo_quantize_e4m3", "octo_dequantize_e4m3",
 ]
 
 _lib = None
@@ -220,6 +229,13 @@ def lib() -> C.CDLL:
         L.octo_probe_mfma.argtypes = [i32, vp, C.c_size_t, i32, i32, vp, vp]
         L.octo_op_nms_static.argtypes = [vp, vp, i32, i32, f32, i32, vp, vp, vp]
         L.octo_op_compact.argtypes = [vp, i32, vp, vp, i32, i32, i32, i32, i32, i32, vp, vp, vp, i32, vp, vp, vp, vp, vp]
+        L.octo_op_conv.argtypes = [vp, vp, vp]
+        L.octo_op_conv_packed_bytes.restype = C.c_size_t
+        L.octo_op_conv_packed_bytes.argtypes = [i32, i32, i32, i32, i32]
+        L.octo_op_conv_padded_cout.argtypes = [i32]
+        L.octo_op_conv_pack.argtypes = [i32, vp, i32, i32, i32, i32, vp]
+        L.octo_quantize_e4m3.argtypes = [vp, C.c_size_t, f32, vp]
+        L.octo_dequantize_e4m3.argtypes = [vp, C.c_size_t, f32, vp]
         _lib = L
     return _lib
 
@@ -598,6 +614,74 @@ def op_compact(top, keep, n_keep, src_hw, in_hw, class_mask: int, cap: int, stre
     r = rois.cpu().numpy().reshape(-1).view(ROI_DTYPE)[:nr].copy()
     b = boxes.cpu().numpy().reshape(n, max_det * 32).view(BOX_DTYPE)
     return r, roi_of.cpu().numpy(), b, flags.cpu().numpy()
+
+
+# ---- one convolution layer ------------------------------------------------------
+def quantize_e4m3(x: np.ndarray, inv_scale: float = 1.0) -> np.ndarray:
+    """fp32 values -> E4M3 codes of x * inv_scale (host, the library's own rounding)."""
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    out = np.empty(x.shape, np.uint8)
+    _st(lib().octo_quantize_e4m3(x.ctypes.data, x.size, inv_scale, out.ctypes.data))
+    return out
+
+
+def dequantize_e4m3(codes: np.ndarray, scale: float = 1.0) -> np.ndarray:
+    codes = np.ascontiguousarray(codes, dtype=np.uint8)
+    out = np.empty(codes.shape, np.float32)
+    _st(lib().octo_dequantize_e4m3(codes.ctypes.data, codes.size, scale, out.ctypes.data))
+    return out
+
+
+def conv_pack(w_raw: np.ndarray, dtype: str) -> np.ndarray:
+    """w_raw [cout][kh][kw][cin] in storage form (to_storage(...), or uint8 codes for f8) -> the packed bytes the kernels read."""
+    cout, kh, kw, cin = w_raw.shape
+    w_raw = np.ascontiguousarray(w_raw)
+    nbytes = lib().octo_op_conv_packed_bytes(DTYPES[dtype], cout, kh, kw, cin)
+    if not nbytes:
+        raise OctoError(-1, "bad weight shape or type")
+    out = np.empty(nbytes, np.uint8)
+    _st(lib().octo_op_conv_pack(DTYPES[dtype], w_raw.ctypes.data, cout, kh, kw, cin, out.ctypes.data))
+    return out
+
+
+class ConvOp:
+    """Device-side state of one convolution layer for op_conv: packed weights, padded bias and (f8) scale vector."""
+
+    def __init__(self, w_raw: np.ndarray, bias: np.ndarray, dtype: str, stride=1, pad=0, act=0, scale: np.ndarray = None):
+        t = _torch()
+        self.dtype, self.stride, self.pad, self.act = dtype, stride, pad, act
+        self.cout, self.kh, self.kw, self.cin = w_raw.shape
+        rows = lib().octo_op_conv_padded_cout(self.cout)
+        self.w = t.from_numpy(conv_pack(w_raw, dtype)).cuda()
+        b = np.zeros(rows, np.float32); b[:self.cout] = bias
+        self.bias = t.from_numpy(b).cuda()
+        self.scale = None
+        if dtype == "f8":
+            sc = np.zeros(rows, np.float32); sc[:self.cout] = scale
+            self.scale = t.from_numpy(sc).cuda()
+
+    def out_hw(self, h, w):
+        return (h + 2 * self.pad - self.kh) // self.stride + 1, (w + 2 * self.pad - self.kw) // self.stride + 1
+
+
+def op_conv(layer: ConvOp, x, y, res=None, res_mode=0, out_f32=False, res_scale=0.0, y_inv_scale=1.0, stream=None) -> int:
+    """y = conv(x) on device tensors [n][h][w][c] (channels contiguous; a wider last stride is passed on as the pitch).
+    Tensors of type f8 are uint8 tensors of E4M3 codes.  Returns the id of the kernel that ran."""
+    n, h, w, cin = x.shape
+    op = OctoConvOp()
+    op.dtype = DTYPES[layer.dtype]
+    op.n, op.h, op.w, op.cin, op.x_ld = n, h, w, cin, x.stride(2)
+    op.cout, op.kh, op.kw, op.stride, op.pad = layer.cout, layer.kh, layer.kw, layer.stride, layer.pad
+    op.act, op.res_mode, op.out_f32 = layer.act, res_mode, 1 if out_f32 else 0
+    op.y_ld = y.stride(2)
+    op.d_x, op.d_w, op.d_bias, op.d_y = x.data_ptr(), layer.w.data_ptr(), layer.bias.data_ptr(), y.data_ptr()
+    op.d_scale = layer.scale.data_ptr() if layer.scale is not None else None
+    if res is not None:
+        op.d_res, op.res_ld = res.data_ptr(), res.stride(2)
+    op.res_scale, op.y_inv_scale = res_scale, y_inv_scale
+    kid = C.c_int32(0)
+    _st(lib().octo_op_conv(C.byref(op), _stream_ptr(stream), C.byref(kid)))
+    return int(kid.value)
 
 
 # ---- CU-masked streams --------------------------------------------------------

@@ -66,6 +66,7 @@ __global__ __launch_bounds__(THREADS, MINB) void conv_mfma_kernel(const ConvArgs
   constexpr int SMEM_VECS = STAGED && STAGE_VECS > OPER_VECS ? STAGE_VECS : OPER_VECS;
   __shared__ u32x4 smem[SMEM_VECS];
   __shared__ float sBias[BC];
+  __shared__ float sScale[ES == 1 ? BC : 1];       // 8-bit storage: factor on the accumulator, per output channel
   u32x4 (*sA)[BC][ROWV] = (u32x4 (*)[BC][ROWV])smem;
   u32x4 (*sB)[BP][ROWV] = (u32x4 (*)[BP][ROWV])(smem + 2 * BC * ROWV);
 
@@ -167,6 +168,7 @@ __global__ __launch_bounds__(THREADS, MINB) void conv_mfma_kernel(const ConvArgs
     // k = (r*kw + s)*Cin + c; the two divisions use precomputed reciprocals (exact for k < 65536).
     __syncthreads();   // the previous tile's LDS reads are done
     if (tid < BC) sBias[tid] = a.bias[c0 + tid];     // bias is padded to a multiple of 128 channels
+    if constexpr (ES == 1) { if (tid < BC) sScale[tid] = a.scale[c0 + tid]; }     // padded alike
     if constexpr (DMA) {
       // LDS byte address of this wave's 1 KB slice of pass 0 of stage 0 (lane l writes at + 16 l)
       const unsigned lds_wave = (unsigned)__builtin_amdgcn_readfirstlane((int)((unsigned)(uintptr_t)smem + (unsigned)wave * 1024u));
@@ -201,6 +203,24 @@ __global__ __launch_bounds__(THREADS, MINB) void conv_mfma_kernel(const ConvArgs
         OCTO_CONV_DMA(kb + D, st_wr)     // refills the stage that step kb - 1 read; past the last step: zeros, never read
         const u32x4* pa = smem + st_rd * STAGE_VECS_OP;
         const u32x4* pb = pa + BC * ROWV;
+        if constexpr (ES == 1) {
+          // 8-bit operands: one instruction reduces over 64 values, two vectors per lane and operand
+#pragma unroll
+          for (int kk = 0; kk < KV / 4; ++kk) {
+            u32x4 fa[TC][2], fb[TP][2];
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+#pragma unroll
+              for (int i = 0; i < TC; ++i) fa[i][h] = pa[(wc * (BC / WC) + i * 32 + l32) * ROWV + ((kk * 4 + h * 2 + g) ^ rsw)];
+#pragma unroll
+              for (int j = 0; j < TP; ++j) fb[j][h] = pb[(wp * (BP / WP) + j * 32 + l32) * ROWV + ((kk * 4 + h * 2 + g) ^ rsw)];
+            }
+#pragma unroll
+            for (int i = 0; i < TC; ++i)
+#pragma unroll
+              for (int j = 0; j < TP; ++j) acc[i][j] = E::mfma2(fa[i][0], fa[i][1], fb[j][0], fb[j][1], acc[i][j]);
+          }
+        } else {
 #pragma unroll
         for (int kk = 0; kk < KV / 2; ++kk) {
           u32x4 fa[TC], fb[TP];
@@ -212,6 +232,7 @@ __global__ __launch_bounds__(THREADS, MINB) void conv_mfma_kernel(const ConvArgs
           for (int i = 0; i < TC; ++i)
 #pragma unroll
             for (int j = 0; j < TP; ++j) acc[i][j] = E::mfma(fa[i], fb[j], acc[i][j]);
+        }
         }
         st_rd = st_rd + 1 == NST ? 0 : st_rd + 1;
         st_wr = st_wr + 1 == NST ? 0 : st_wr + 1;
@@ -319,12 +340,17 @@ __global__ __launch_bounds__(THREADS, MINB) void conv_mfma_kernel(const ConvArgs
             const T* rp = (const T*)a.res + (size_t)p * a.res_ld + a.res_coff + c0 + cblk;
             if (vec_ok && c0 + cblk + 28 <= a.Cout) {
 #pragma unroll
-              for (int q = 0; q < 4; ++q) rv[q] = load4<T>(rp + q * 8);
+              for (int q = 0; q < 4; ++q) {
+                const floatx4 r4 = load4<T>(rp + q * 8);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) rv[q][e] = ES == 1 ? r4[e] * a.res_scale : r4[e];
+              }
             } else {
 #pragma unroll
               for (int q = 0; q < 4; ++q)
 #pragma unroll
-                for (int e = 0; e < 4; ++e) if (c0 + cblk + q * 8 + e < a.Cout) rv[q][e] = (float)rp[q * 8 + e];
+                for (int e = 0; e < 4; ++e)
+                  if (c0 + cblk + q * 8 + e < a.Cout) rv[q][e] = ES == 1 ? to_f32<T>(rp[q * 8 + e]) * a.res_scale : to_f32<T>(rp[q * 8 + e]);
             }
           }
           const size_t o = (size_t)p * a.y_ld + a.y_coff + c0 + cblk;
@@ -333,10 +359,14 @@ __global__ __launch_bounds__(THREADS, MINB) void conv_mfma_kernel(const ConvArgs
             const floatx4 b4 = *(const floatx4*)&sBias[cblk + q * 8];
             floatx4 v;
 #pragma unroll
-            for (int e = 0; e < 4; ++e) v[e] = acc[i][j][q * 4 + e];
+            for (int e = 0; e < 4; ++e) v[e] = ES == 1 ? acc[i][j][q * 4 + e] * sScale[cblk + q * 8 + e] : acc[i][j][q * 4 + e];
             v = finish4<RES, SILU>(v, b4, rv[q], act_lo);
+            if (a.out_f32) { store4<float>((float*)a.y + o + q * 8, v); continue; }
+            if constexpr (ES == 1) {
+#pragma unroll
+              for (int e = 0; e < 4; ++e) v[e] *= a.y_inv_scale;
+            }
             if (staged) store4<T>((T*)((char*)smem + (size_t)pl * OPITCH) + cblk + q * 8, v);
-            else if (a.out_f32) store4<float>((float*)a.y + o + q * 8, v);
             else store4<T>((T*)a.y + o + q * 8, v);
           }
         } else {
@@ -348,11 +378,14 @@ __global__ __launch_bounds__(THREADS, MINB) void conv_mfma_kernel(const ConvArgs
               const int cl = cblk + q * 8 + e;
               const int c = c0 + cl;
               if (c < a.Cout) {
-                float r = 0.f;
-                if (RES != OCTO_RES_NONE) r = (float)((const T*)a.res)[(size_t)p * a.res_ld + a.res_coff + c];
-                const float t = finish1<RES, SILU>(acc[i][j][q * 4 + e], sBias[cl], r, act_lo);
+                float r = 0.f, av = acc[i][j][q * 4 + e];
+                if (RES != OCTO_RES_NONE) r = to_f32<T>(((const T*)a.res)[(size_t)p * a.res_ld + a.res_coff + c]);
+                if constexpr (ES == 1) { r *= a.res_scale; av *= sScale[cl]; }
+                float t = finish1<RES, SILU>(av, sBias[cl], r, act_lo);
                 const size_t o = (size_t)p * a.y_ld + a.y_coff + c;
-                if (a.out_f32) ((float*)a.y)[o] = t; else ((T*)a.y)[o] = (T)t;
+                if (a.out_f32) { ((float*)a.y)[o] = t; continue; }
+                if constexpr (ES == 1) t *= a.y_inv_scale;
+                ((T*)a.y)[o] = from_f32<T>(t);
               }
             }
           }
@@ -376,6 +409,11 @@ __global__ __launch_bounds__(THREADS, MINB) void conv_mfma_kernel(const ConvArgs
           T* yp = (T*)a.y + (size_t)p * a.y_ld + a.y_coff + c;
           if (c + VN <= a.Cout) {
             *(u32x4*)yp = val;
+          } else if constexpr (ES == 1) {
+            typedef uint8_t bv __attribute__((ext_vector_type(16)));
+            const bv b = __builtin_bit_cast(bv, val);
+#pragma unroll
+            for (int e = 0; e < VN; ++e) if (c + e < a.Cout) yp[e].bits = b[e];
           } else {
             typedef T tv __attribute__((ext_vector_type(VN)));
             const tv tvv = __builtin_bit_cast(tv, val);
@@ -393,7 +431,7 @@ __global__ __launch_bounds__(THREADS, MINB) void conv_mfma_kernel(const ConvArgs
 int conv_kernel_id(int bc, int bp, int kv, int minb, bool vec, bool dma) { return 1000000000 + bc * 1000000 + bp * 1000 + kv * 100 + minb * 10 + (vec ? 1 : 0) + (dma ? 2 : 0); }
 
 size_t conv_packed_weight_elems(int cout, int kh, int kw, int cin, int dtype, int* kp_out, int* cout_pad_out) {
-  const int vn = dtype == OCTO_F32 ? 4 : 8;
+  const int vn = 16 / dtype_size(dtype);
   const int bk = 8 * vn;   // largest K step of any tile configuration
   const int K = kh * kw * cin;
   const int kp = (K + bk - 1) / bk * bk;
@@ -455,6 +493,23 @@ static hipError_t launch_typed(const ConvArgs& a, int num_cu, hipStream_t s, int
   return launch_cfg<T, 64, 64, 2, 2, 8, 1, 4, true, true>(a, num_cu, s, kernel_id, tm);
 }
 
+// 8-bit floating point (E4M3) storage: the direct-to-LDS tile shapes only, so the input channels must come in whole
+// 16-byte vectors.  Same choice of shape as for the 16-bit types; a K step is 128 (or 64) bytes of K as there, that is
+// twice as many values.
+static hipError_t launch_f8(const ConvArgs& a, int num_cu, hipStream_t s, int* kernel_id, const ConvTiming& tm) {
+  const bool vec = (a.Cin % 16 == 0) && (a.x_ld % 16 == 0) && (a.x_coff % 16 == 0) && (((uintptr_t)a.x & 15) == 0) && a.kh <= 15 && a.kw <= 15;
+  if (!vec || !a.scale || a.pair_view) return hipErrorInvalidValue;
+  const long long M = (long long)(a.n_hint > 0 && a.n_hint < a.n ? a.n_hint : a.n) * a.Ho * a.Wo;
+  auto tiles = [&](int bc, int bp) { return ((M + bp - 1) / bp) * ((a.Cout + bc - 1) / bc); };
+  const bool fits128 = a.Cout >= 96 && (a.Cout + 127) / 128 * 128 == (a.Cout + 63) / 64 * 64;
+  if (fits128 && tiles(128, 128) >= (a.Kp >= 2048 ? num_cu / 4 : 5 * num_cu / 4))
+    return launch_cfg<f8, 128, 128, 2, 2, 8, 1, 2, true, true>(a, num_cu, s, kernel_id, tm);
+  if (a.Cout <= 64 && tiles(64, 256) >= 4 * num_cu) return launch_cfg<f8, 64, 256, 1, 4, 4, 1, 3, true, true>(a, num_cu, s, kernel_id, tm);
+  if (tiles(64, 128) >= (a.Kp >= 1024 ? num_cu / 4 : 9 * num_cu / 8))
+    return launch_cfg<f8, 64, 128, 2, 2, 8, 1, 3, true, true>(a, num_cu, s, kernel_id, tm);
+  return launch_cfg<f8, 64, 64, 2, 2, 8, 1, 4, true, true>(a, num_cu, s, kernel_id, tm);
+}
+
 // Checks the limits the kernel relies on and fills the precomputed reciprocals.
 bool conv_prepare(ConvArgs& a, int dtype) {
   if (a.Cin < 1 || a.kw < 1 || a.kh < 1 || a.stride_h < 1 || a.stride_w < 1 || a.Kp >= 65536 || a.w_rows < 1) return false;
@@ -500,6 +555,7 @@ hipError_t launch_conv(int dtype, const ConvArgs& a0, int num_cu, hipStream_t s,
     if (eb != hipErrorNotSupported) return eb;
   }
   switch (dtype) {
+    case OCTO_F8: return launch_f8(a, num_cu, s, kernel_id, tm);
     case OCTO_F16: return launch_typed<_Float16>(a, num_cu, s, kernel_id, tm);
     case OCTO_BF16: return launch_typed<__bf16>(a, num_cu, s, kernel_id, tm);
     case OCTO_F32: return launch_typed<float>(a, num_cu, s, kernel_id, tm);

@@ -13,6 +13,12 @@ typedef float floatx16 __attribute__((ext_vector_type(16)));
 typedef float floatx4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));   // one 16-byte operand vector
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef int i32x8 __attribute__((ext_vector_type(8)));
+
+// One byte of 8-bit floating point, OCP E4M3: sign, 4 exponent bits (bias 7), 3 mantissa bits; no infinities, 0x7F and
+// 0xFF are NaN, the largest finite value is 448.  The conversion instructions of this GPU use that format.
+struct f8 { uint8_t bits; };
+constexpr float F8_MAX = 448.0f;
 
 template <typename T> struct Elem;
 template <> struct Elem<_Float16> {
@@ -27,6 +33,16 @@ template <> struct Elem<__bf16> {
     return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
   }
 };
+template <> struct Elem<f8> {
+  static constexpr int N = 16;
+  // K = 64 per instruction: a lane supplies 32 consecutive bytes per operand, here two 16-byte vectors.  Which K
+  // indices they are does not matter as long as both operands use the same ones.
+  static __device__ __forceinline__ floatx16 mfma2(u32x4 a0, u32x4 a1, u32x4 b0, u32x4 b1, floatx16 c) {
+    const i32x8 a = {(int)a0[0], (int)a0[1], (int)a0[2], (int)a0[3], (int)a1[0], (int)a1[1], (int)a1[2], (int)a1[3]};
+    const i32x8 b = {(int)b0[0], (int)b0[1], (int)b0[2], (int)b0[3], (int)b1[0], (int)b1[1], (int)b1[2], (int)b1[3]};
+    return __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a, b, c, 0, 0, 0, 0, 0, 0);   // formats 0 = E4M3, scales 2^0
+  }
+};
 template <> struct Elem<float> {
   static constexpr int N = 4;
   static __device__ __forceinline__ floatx16 mfma(u32x4 a, u32x4 b, floatx16 c) {
@@ -37,10 +53,37 @@ template <> struct Elem<float> {
   }
 };
 
+// E4M3 <-> fp32.  Encoding rounds to nearest even and saturates at +-448 (the clamp comes first, so the conversion
+// instruction never sees a value it would have to turn into NaN); NaN stays NaN.
+__device__ __forceinline__ uint32_t f8_pack4(floatx4 v) {
+  int w = 0;
+  w = __builtin_amdgcn_cvt_pk_fp8_f32(__builtin_amdgcn_fmed3f(v[0], -F8_MAX, F8_MAX), __builtin_amdgcn_fmed3f(v[1], -F8_MAX, F8_MAX), w, false);
+  w = __builtin_amdgcn_cvt_pk_fp8_f32(__builtin_amdgcn_fmed3f(v[2], -F8_MAX, F8_MAX), __builtin_amdgcn_fmed3f(v[3], -F8_MAX, F8_MAX), w, true);
+  return (uint32_t)w;
+}
+__device__ __forceinline__ floatx4 f8_unpack4(uint32_t w) {
+  return floatx4{__builtin_amdgcn_cvt_f32_fp8((int)w, 0), __builtin_amdgcn_cvt_f32_fp8((int)w, 1),
+                 __builtin_amdgcn_cvt_f32_fp8((int)w, 2), __builtin_amdgcn_cvt_f32_fp8((int)w, 3)};
+}
+template <typename T> __device__ __forceinline__ float to_f32(T v) {
+  if constexpr (std::is_same<T, f8>::value) return __builtin_amdgcn_cvt_f32_fp8((int)v.bits, 0);
+  else return (float)v;
+}
+template <typename T> __device__ __forceinline__ T from_f32(float f) {
+  if constexpr (std::is_same<T, f8>::value) {
+    const float c = __builtin_amdgcn_fmed3f(f, -F8_MAX, F8_MAX);
+    return f8{(uint8_t)(__builtin_amdgcn_cvt_pk_fp8_f32(c, c, 0, false) & 0xFF)};
+  } else {
+    return (T)f;
+  }
+}
+
 template <typename T>
 __device__ __forceinline__ floatx4 load4(const T* p) {
   if constexpr (sizeof(T) == 4) {
     return *(const floatx4*)p;
+  } else if constexpr (sizeof(T) == 1) {
+    return f8_unpack4(*(const uint32_t*)p);
   } else {
     typedef T t4 __attribute__((ext_vector_type(4)));
     const t4 v = __builtin_bit_cast(t4, *(const u32x2*)p);
@@ -51,6 +94,8 @@ template <typename T>
 __device__ __forceinline__ void store4(T* p, floatx4 v) {
   if constexpr (sizeof(T) == 4) {
     *(floatx4*)p = v;
+  } else if constexpr (sizeof(T) == 1) {
+    *(uint32_t*)p = f8_pack4(v);
   } else {
     typedef T t4 __attribute__((ext_vector_type(4)));
     const t4 o = {(T)v[0], (T)v[1], (T)v[2], (T)v[3]};

@@ -42,10 +42,14 @@ struct ConvArgs {
   // written and y is not touched; launch_conv returns hipErrorNotSupported if no kernel can do that for the layer.
   void* pool_y;
   int pool_ho, pool_wo, pool_ld, pool_coff;
+  // 8-bit floating point storage only: y = act(acc * scale[c] + bias[c] (+ res * res_scale)), stored as
+  // E4M3(y * y_inv_scale) unless out_f32.  scale: device, one factor per output channel, padded like the bias.
+  const float* scale;
+  float res_scale, y_inv_scale;
 };
 
 // element size of a storage type
-inline __host__ __device__ int dtype_size(int dt) { return dt == OCTO_F32 ? 4 : 2; }
+inline __host__ __device__ int dtype_size(int dt) { return dt == OCTO_F32 ? 4 : (dt == OCTO_F8 ? 1 : 2); }
 
 // ---- launchers (each enqueues on `s`, never synchronises) -------------------
 // Optional pair of events attached to the convolution's own dispatch (start and end of the kernel on the device).

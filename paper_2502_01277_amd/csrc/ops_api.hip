@@ -1,5 +1,6 @@
 // Stage-level C ABI entry points: argument checks and one launch each of the
 // kernels the pipeline itself uses, on caller-owned device buffers.
+#include <cmath>
 #include <cstring>
 #include <mutex>
 
@@ -72,6 +73,109 @@ octo_status octo_op_crop_resize(const void* d_frame_ptrs, const void* d_pitches,
   a.n_frames = n_frames;
   for (int c = 0; c < 3; ++c) { a.scale[c] = scale3[c]; a.bias[c] = bias3[c]; }
   return from_hip(launch_crop_resize(dtype, a, (hipStream_t)hip_stream));
+}
+
+// ---- E4M3 on the host ---------------------------------------------------------
+namespace {
+// nearest integer, ties to even, for 0 <= x <= 16 (independent of the floating-point rounding mode)
+int round_half_even(float x) {
+  const int r = (int)x;                       // floor for x >= 0
+  const float d = x - (float)r;
+  return d > 0.5f || (d == 0.5f && (r & 1)) ? r + 1 : r;
+}
+uint8_t e4m3_encode(float f) {
+  if (f != f) return 0x7F;
+  const uint8_t sign = std::signbit(f) ? 0x80 : 0x00;
+  float a = std::fabs(f);
+  if (a > 448.0f) a = 448.0f;
+  if (a < 0.015625f) return sign | (uint8_t)round_half_even(a * 512.0f);     // below 2^-6: multiples of 2^-9; 8 is the first normal code
+  int e = 0;
+  const float m = std::frexp(a, &e);          // a = m * 2^e, 0.5 <= m < 1
+  int q = round_half_even((m * 2.0f - 1.0f) * 8.0f), ex = e - 1;              // a = (1 + q/8) * 2^ex before rounding q
+  if (q == 8) { q = 0; ++ex; }
+  return sign | (uint8_t)(((ex + 7) << 3) | q);
+}
+float e4m3_decode(uint8_t c) {
+  const int ex = (c >> 3) & 15, q = c & 7;
+  if (ex == 15 && q == 7) return std::nanf("");
+  const float mag = ex == 0 ? std::ldexp((float)q, -9) : std::ldexp(1.0f + (float)q / 8.0f, ex - 7);
+  return (c & 0x80) ? -mag : mag;
+}
+int cached_cu_count() {
+  static std::mutex mu;
+  static int cus[MAX_DEVICES] = {};
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= MAX_DEVICES) return 0;
+  std::lock_guard<std::mutex> lock(mu);
+  if (!cus[dev]) {
+    hipDeviceProp_t prop;
+    if (hipGetDeviceProperties(&prop, dev) != hipSuccess) return 0;
+    cus[dev] = prop.multiProcessorCount;
+  }
+  return cus[dev];
+}
+bool conv_dtype(int dt) { return valid_dtype(dt) || dt == OCTO_F8; }
+}  // namespace
+
+octo_status octo_quantize_e4m3(const float* src, size_t n, float inv_scale, uint8_t* dst) {
+  if ((!src || !dst) && n) return OCTO_EINVAL;
+  for (size_t i = 0; i < n; ++i) dst[i] = e4m3_encode(src[i] * inv_scale);
+  return OCTO_OK;
+}
+octo_status octo_dequantize_e4m3(const uint8_t* src, size_t n, float scale, float* dst) {
+  if ((!src || !dst) && n) return OCTO_EINVAL;
+  for (size_t i = 0; i < n; ++i) dst[i] = e4m3_decode(src[i]) * scale;
+  return OCTO_OK;
+}
+
+// ---- one convolution layer ------------------------------------------------------
+int32_t octo_op_conv_padded_cout(int32_t cout) { return cout > 0 ? (cout + 127) / 128 * 128 : 0; }
+
+size_t octo_op_conv_packed_bytes(int32_t dtype, int32_t cout, int32_t kh, int32_t kw, int32_t cin) {
+  if (!conv_dtype(dtype) || cout < 1 || kh < 1 || kw < 1 || cin < 1) return 0;
+  // slack after the last row: the operand prefetch may read one K step past it
+  return conv_packed_weight_elems(cout, kh, kw, cin, dtype, nullptr, nullptr) * (size_t)dtype_size(dtype) + 512;
+}
+
+octo_status octo_op_conv_pack(int32_t dtype, const void* w, int32_t cout, int32_t kh, int32_t kw, int32_t cin, void* packed) {
+  const size_t bytes = octo_op_conv_packed_bytes(dtype, cout, kh, kw, cin);
+  if (!w || !packed || !bytes) return OCTO_EINVAL;
+  int kp = 0, rows = 0;
+  conv_packed_weight_elems(cout, kh, kw, cin, dtype, &kp, &rows);
+  const size_t es = (size_t)dtype_size(dtype), k = (size_t)kh * kw * cin;
+  memset(packed, 0, bytes);
+  for (int r = 0; r < cout; ++r) memcpy((char*)packed + (size_t)r * kp * es, (const char*)w + (size_t)r * k * es, k * es);
+  return OCTO_OK;
+}
+
+octo_status octo_op_conv(const octo_conv_op* op, void* hip_stream, int32_t* kernel_id) {
+  if (!op || !conv_dtype(op->dtype) || !op->d_x || !op->d_w || !op->d_bias || !op->d_y) return OCTO_EINVAL;
+  if (op->n < 0 || op->h < 1 || op->w < 1 || op->cin < 1 || op->cout < 1 || op->kh < 1 || op->kw < 1 || op->stride < 1 || op->pad < 0) return OCTO_EINVAL;
+  if (op->x_ld < op->cin || op->y_ld < op->cout || (op->d_res && op->res_ld < op->cout)) return OCTO_EINVAL;
+  if (op->act < OCTO_ACT_NONE || op->act > OCTO_ACT_SILU || op->res_mode < OCTO_RES_NONE || op->res_mode > OCTO_RES_AFTER_ACT) return OCTO_EINVAL;
+  if ((op->d_res != nullptr) != (op->res_mode != OCTO_RES_NONE)) return OCTO_EINVAL;
+  if ((((uintptr_t)op->d_x | (uintptr_t)op->d_y | (uintptr_t)op->d_res | (uintptr_t)op->d_w) & 15) != 0) return OCTO_EINVAL;
+  const int ho = (op->h + 2 * op->pad - op->kh) / op->stride + 1, wo = (op->w + 2 * op->pad - op->kw) / op->stride + 1;
+  if (op->h + 2 * op->pad < op->kh || op->w + 2 * op->pad < op->kw || ho < 1 || wo < 1) return OCTO_EINVAL;
+  if (op->dtype == OCTO_F8 && (!op->d_scale || op->cin % 16 || op->x_ld % 16 || !(op->y_inv_scale > 0.0f) || (op->d_res && !(op->res_scale > 0.0f)))) return OCTO_EINVAL;
+  if (op->n == 0) { if (kernel_id) *kernel_id = 0; return OCTO_OK; }
+  const int cus = cached_cu_count();
+  if (cus < 1) return OCTO_EHIP;
+  ConvArgs a{};
+  int kp = 0, rows = 0;
+  conv_packed_weight_elems(op->cout, op->kh, op->kw, op->cin, op->dtype, &kp, &rows);
+  a.x = op->d_x; a.w = op->d_w; a.bias = op->d_bias; a.y = op->d_y; a.n = op->n;
+  a.H = op->h; a.W = op->w; a.Cin = op->cin; a.x_ld = op->x_ld;
+  a.Ho = ho; a.Wo = wo; a.Cout = op->cout; a.y_ld = op->y_ld;
+  a.kh = op->kh; a.kw = op->kw; a.stride_h = a.stride_w = op->stride; a.pad_h = a.pad_w = op->pad;
+  a.K = op->kh * op->kw * op->cin; a.Kp = kp; a.w_rows = rows;
+  a.act = op->act; a.res_mode = op->res_mode; a.out_f32 = op->out_f32 ? 1 : 0;
+  if (op->d_res) { a.res = op->d_res; a.res_ld = op->res_ld; }
+  if (op->dtype == OCTO_F8) { a.scale = op->d_scale; a.res_scale = op->d_res ? op->res_scale : 0.0f; a.y_inv_scale = op->y_inv_scale; }
+  int kid = 0;
+  const hipError_t e = launch_conv(op->dtype, a, cus, (hipStream_t)hip_stream, &kid);
+  if (kernel_id) *kernel_id = kid;
+  return from_hip(e);
 }
 
 octo_status octo_op_decode(const octo_model_desc* model, const void* const* d_heads, int32_t n,

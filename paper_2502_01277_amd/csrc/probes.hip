@@ -25,7 +25,9 @@ __global__ __launch_bounds__(256, 1) void probe_mfma_kernel(float* out, int iter
   for (int i = 0; i < 4; ++i)
     for (int j = 0; j < 4; ++j) {
       const unsigned h1 = mix(threadIdx.x * 64 + i * 8 + j + blockIdx.x * 7919), h2 = mix(h1 + 12345);
-      if constexpr (std::is_same<T, __bf16>::value) {
+      if constexpr (std::is_same<T, f8>::value) {
+        a[i][j] = (h1 & 0x87878787u) | 0x38383838u; b[i][j] = (h2 & 0x87878787u) | 0x38383838u;      // four E4M3 per word, 1..1.875
+      } else if constexpr (std::is_same<T, __bf16>::value) {
         a[i][j] = (h1 & 0x80FF80FFu) | 0x3F003F00u; b[i][j] = (h2 & 0x80FF80FFu) | 0x3F003F00u;      // two bf16 per word
       } else {
         a[i][j] = (h1 & 0x87FF87FFu) | 0x38003800u; b[i][j] = (h2 & 0x87FF87FFu) | 0x38003800u;      // two fp16 per word
@@ -37,7 +39,10 @@ __global__ __launch_bounds__(256, 1) void probe_mfma_kernel(float* out, int iter
 #pragma unroll
     for (int i = 0; i < 4; ++i)
 #pragma unroll
-      for (int j = 0; j < 4; ++j) c[i][j] = Elem<T>::mfma(a[i], b[j], c[i][j]);
+      for (int j = 0; j < 4; ++j) {
+        if constexpr (std::is_same<T, f8>::value) c[i][j] = Elem<T>::mfma2(a[i], a[(i + 1) & 3], b[j], b[(j + 1) & 3], c[i][j]);   // K = 64 per instruction
+        else c[i][j] = Elem<T>::mfma(a[i], b[j], c[i][j]);
+      }
   }
   float s = 0.f;
   for (int i = 0; i < 4; ++i) for (int j = 0; j < 4; ++j) for (int r = 0; r < 16; ++r) s += c[i][j][r];
@@ -80,7 +85,7 @@ octo_status octo_probe_copy(const void* d_src, void* d_dst, size_t bytes, int32_
 }
 
 octo_status octo_probe_mfma(int32_t dtype, float* d_scratch, size_t scratch_bytes, int32_t iters, int32_t reps, void* hip_stream, double* tflops) {
-  if (!d_scratch || !tflops || iters < 1 || iters > 1000000 || reps < 1 || reps > 100 || (dtype != OCTO_F16 && dtype != OCTO_BF16)) return OCTO_EINVAL;
+  if (!d_scratch || !tflops || iters < 1 || iters > 1000000 || reps < 1 || reps > 100 || (dtype != OCTO_F16 && dtype != OCTO_BF16 && dtype != OCTO_F8)) return OCTO_EINVAL;
   hipStream_t s = (hipStream_t)hip_stream;
   int dev = 0; hipDeviceProp_t prop;
   if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess) return OCTO_EHIP;
@@ -93,7 +98,8 @@ octo_status octo_probe_mfma(int32_t dtype, float* d_scratch, size_t scratch_byte
   octo_status st = OCTO_OK;
   for (int r = 0; r < reps + 1 && st == OCTO_OK; ++r) {
     hipEventRecord(e0, s);
-    if (dtype == OCTO_F16) hipLaunchKernelGGL(probe_mfma_kernel<_Float16>, dim3(grid), dim3(256), 0, s, d_scratch, iters);
+    if (dtype == OCTO_F8) hipLaunchKernelGGL(probe_mfma_kernel<f8>, dim3(grid), dim3(256), 0, s, d_scratch, iters);
+    else if (dtype == OCTO_F16) hipLaunchKernelGGL(probe_mfma_kernel<_Float16>, dim3(grid), dim3(256), 0, s, d_scratch, iters);
     else hipLaunchKernelGGL(probe_mfma_kernel<__bf16>, dim3(grid), dim3(256), 0, s, d_scratch, iters);
     hipEventRecord(e1, s);
     float ms = 0.f;
@@ -102,7 +108,7 @@ octo_status octo_probe_mfma(int32_t dtype, float* d_scratch, size_t scratch_byte
   }
   hipEventDestroy(e0); hipEventDestroy(e1);
   if (st != OCTO_OK) return st;
-  const double flop = (double)grid * 4.0 * iters * 16.0 * (2.0 * 32 * 32 * 16);
+  const double flop = (double)grid * 4.0 * iters * 16.0 * (2.0 * 32 * 32 * (dtype == OCTO_F8 ? 64 : 16));
   *tflops = flop / (median_ms(t) * 1e-3) / 1e12;
   return OCTO_OK;
 }

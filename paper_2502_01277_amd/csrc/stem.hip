@@ -292,7 +292,7 @@ static hipError_t launch_stem_typed(const ConvArgs& a, int num_cu, hipStream_t s
 // rows and no residual; anything else is left to the general kernel (hipErrorNotSupported).  With a fused max-pool:
 // the 7x7 shape only, pooled size (Ho + 1) / 2 x (Wo + 1) / 2, 16-byte aligned pooled rows.
 hipError_t launch_stem(int dtype, const ConvArgs& a, int num_cu, hipStream_t s, int* kernel_id, ConvTiming tm) {
-  if (!a.pair_view || dtype == OCTO_F32 || a.stride_h != 2 || a.stride_w != 1 || a.Cin != 8 || a.x_ld != 8 || a.res || a.out_f32)
+  if (!a.pair_view || (dtype != OCTO_F16 && dtype != OCTO_BF16) || a.stride_h != 2 || a.stride_w != 1 || a.Cin != 8 || a.x_ld != 8 || a.res || a.out_f32)
     return hipErrorNotSupported;
   if (a.pool_y) {
     if (a.pool_ho != (a.Ho + 1) / 2 || a.pool_wo != (a.Wo + 1) / 2 || ((a.pool_ld | a.pool_coff) & 7) || ((uintptr_t)a.pool_y & 15)) return hipErrorNotSupported;

@@ -51,6 +51,18 @@ def storage_itemsize(dtype: str) -> int:
     return 4 if dtype == "f32" else 2
 
 
+def e4m3_codes(rng, shape, max_field: int = 8, p_zero: float = 0.05) -> np.ndarray:
+    """Random 8-bit floating-point codes (1 sign, 4 exponent, 3 mantissa bits): uniform sign and mantissa, exponent field
+    uniform in 0..max_field (field 0 = the subnormals), a fraction p_zero of exact zeros.  Never a NaN code (field 15
+    with mantissa 7) as long as max_field < 15.  Bits only: what the codes mean is the business of whoever reads them."""
+    assert 0 <= max_field < 15
+    sign = rng.integers(0, 2, shape).astype(np.uint8) << 7
+    field = rng.integers(0, max_field + 1, shape).astype(np.uint8) << 3
+    mant = rng.integers(0, 8, shape).astype(np.uint8)
+    codes = sign | field | mant
+    return np.where(rng.random(shape) < p_zero, np.uint8(0), codes).astype(np.uint8)
+
+
 # ---------------------------------------------------------------------------
 # object counts
 # ---------------------------------------------------------------------------

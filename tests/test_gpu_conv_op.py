@@ -1,0 +1,198 @@
+"""GPU parity of the single-layer convolution call (octo_op_conv) against the oracle: the 16-bit and fp32 types on the
+kernels the pipeline uses, and the 8-bit floating-point (E4M3) variant with its own bars.
+
+Bars for E4M3.  Products of two E4M3 values are exact (at most 8 significant bits), but the 8-bit matrix instruction
+does not add them in full fp32 precision.  Measured with single-row probes on the instruction (one large and one
+small product; one large and 63 small ones in either half; a large accumulator input; cancelling pairs): within each
+aligned group of 8 consecutive K values a product keeps only the bits down to 2^(e - 13), e the exponent of the
+group's largest product, the rest is cut off towards zero; the eight group sums and the accumulator input are then
+added without further loss beyond fp32 rounding.  So, with p_k the exact products of one output:
+  * fp32 output, every element:  |got - ref| <= scale * 7 * 2^-13 * sum_k |p_k| + 4e-6 * S + 2e-6 * |ref|
+    (at most 7 products per group lose less than 2^-13 of the largest, which is at most the group's sum of magnitudes;
+    S = scale * sum |p_k| + |bias| + |residual| carries the fp32 roundings of accumulation and epilogue);
+  * fp32 output, on a sample of outputs the cut-off bits are added up exactly:
+    |got - ref| <= scale * sum_groups sum_k (|p_k| mod 2^(e_group - 13)) + 4e-6 * S + 2e-6 * |ref|  - typically 1e-5 * S,
+    so that a single dropped or misplaced product of ordinary size fails it at any K;
+  * E4M3 output: the stored code must be a correctly rounded code of some value within the first bound of the
+    oracle's (it decides an integer from a floating-point value: both sides round the fp32 product with the inverse
+    scale, ties to even; where the oracle's value is nearer a rounding boundary than the bound, either neighbour is
+    valid), within the second bound on the sample, and more than 99 % of all codes must be exactly the oracle's.
+"""
+import numpy as np
+import pytest
+
+from oracle import fp8, nn
+from oracle.rounding import round_storage
+from paper_2502_01277_amd import synth, zoo
+from helpers import TOL, rel_err
+
+pytestmark = pytest.mark.gpu
+
+
+def _dev(raw, dtype):
+    import torch
+    if dtype == "bf16":
+        return torch.from_numpy(raw.view(np.int16)).cuda().view(torch.bfloat16)
+    return torch.from_numpy(raw).cuda()
+
+
+CASES16 = [
+    # (h, w, cin, cout, k, stride, pad, n, act, res_mode)
+    (20, 20, 64, 64, 3, 1, 1, 3, nn.ACT_SILU, nn.RES_NONE), (17, 23, 32, 96, 3, 2, 1, 2, nn.ACT_RELU, nn.RES_BEFORE_ACT),
+    (9, 9, 128, 256, 1, 1, 0, 5, nn.ACT_NONE, nn.RES_AFTER_ACT), (8, 8, 16, 255, 1, 1, 0, 4, nn.ACT_SILU, nn.RES_NONE),
+    (12, 11, 5, 40, 3, 1, 1, 3, nn.ACT_RELU, nn.RES_NONE),                    # channel count that forces the element-wise gather
+    (90, 92, 64, 64, 3, 1, 1, 17, nn.ACT_RELU, nn.RES_BEFORE_ACT),            # patch-in-LDS kernel
+    (14, 14, 256, 256, 3, 1, 1, 160, nn.ACT_RELU, nn.RES_BEFORE_ACT),         # wide 3x3 kernel
+    (128, 128, 16, 200, 1, 1, 0, 4, nn.ACT_SILU, nn.RES_NONE),
+]
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f16", "f32"])
+@pytest.mark.parametrize("case", CASES16)
+def test_conv_op_parity(octo, dtype, case):
+    import torch
+    h, w, cin, cout, k, stride, pad, n, act, res_mode = case
+    rng = np.random.default_rng(21)
+    x = zoo.round_to_dtype(rng.uniform(-1, 1, (n, h, w, cin)).astype(np.float32), dtype)
+    wt = zoo.round_to_dtype((rng.standard_normal((cout, k, k, cin)) / np.sqrt(k * k * cin)).astype(np.float32), dtype)
+    bias = rng.uniform(-0.1, 0.1, cout).astype(np.float32)
+    layer = octo.ConvOp(synth.to_storage(wt, dtype), bias, dtype, stride, pad, act)
+    ho, wo = layer.out_hw(h, w)
+    res = zoo.round_to_dtype(rng.uniform(-1, 1, (n, ho, wo, cout)).astype(np.float32), dtype) if res_mode else None
+    y = nn.conv2d(x, wt, stride, pad) + bias.astype(np.float64)
+    if res_mode == nn.RES_BEFORE_ACT:
+        y = nn.activation(y + res, act)
+    elif res_mode == nn.RES_AFTER_ACT:
+        y = nn.activation(y, act) + res
+    else:
+        y = nn.activation(y, act)
+    dx = octo.to_device(x, dtype)
+    dres = octo.to_device(res, dtype) if res_mode else None
+    dy = torch.zeros((n, ho, wo, cout), dtype=octo.torch_dtype(dtype), device="cuda")
+    kid = octo.op_conv(layer, dx, dy, dres, res_mode)
+    torch.cuda.synchronize()
+    assert kid > 0
+    assert rel_err(dy.float().cpu().numpy(), round_storage(y, dtype)) <= TOL[dtype]
+    # fp32 output of the same layer (kernels that cannot write it hand the layer to the general one)
+    dy32 = torch.zeros((n, ho, wo, cout), dtype=torch.float32, device="cuda")
+    octo.op_conv(layer, dx, dy32, dres, res_mode, out_f32=True)
+    torch.cuda.synchronize()
+    assert rel_err(dy32.cpu().numpy(), y) <= (1e-4 if dtype == "f32" else 2e-3)
+
+
+def test_conv_op_rejects_bad_arguments(octo):
+    import torch
+    layer = octo.ConvOp(np.zeros((32, 3, 3, 16), np.uint8), np.zeros(32, np.float32), "f8", 1, 1, 0, scale=np.ones(32, np.float32))
+    x = torch.zeros((1, 8, 8, 16), dtype=torch.uint8, device="cuda")
+    y = torch.zeros((1, 8, 8, 32), dtype=torch.uint8, device="cuda")
+    assert octo.op_conv(layer, x, y) > 0
+    for bad in (dict(y_inv_scale=0.0), dict(res=y, res_mode=0), dict(res=None, res_mode=1), dict(res=y, res_mode=1, res_scale=0.0)):
+        with pytest.raises(octo.OctoError):
+            octo.op_conv(layer, x, y, **bad)
+    with pytest.raises(octo.OctoError):                                         # input channels must come in whole 16-byte vectors
+        l2 = octo.ConvOp(np.zeros((32, 1, 1, 8), np.uint8), np.zeros(32, np.float32), "f8", scale=np.ones(32, np.float32))
+        octo.op_conv(l2, torch.zeros((1, 8, 8, 8), dtype=torch.uint8, device="cuda"), y)
+    with pytest.raises(octo.OctoError):                                         # misaligned tensor
+        octo.op_conv(layer, x.view(-1)[8:8 + 8 * 16].view(1, 1, 8, 16), y)
+    torch.cuda.synchronize()
+
+
+CASES8 = [
+    # (h, w, cin, cout, k, stride, pad, n, act, res_mode, x_extra, y_extra): extra = channels of a wider buffer around the tensor
+    (20, 20, 64, 64, 3, 1, 1, 3, nn.ACT_SILU, nn.RES_NONE, 0, 0),
+    (17, 23, 32, 96, 3, 2, 1, 2, nn.ACT_RELU, nn.RES_BEFORE_ACT, 16, 0),
+    (9, 9, 128, 256, 1, 1, 0, 5, nn.ACT_NONE, nn.RES_AFTER_ACT, 0, 32),
+    (8, 8, 16, 255, 1, 1, 0, 4, nn.ACT_SILU, nn.RES_NONE, 0, 0),              # odd pitch: element-wise stores
+    (8, 8, 16, 255, 1, 1, 0, 4, nn.ACT_RELU, nn.RES_BEFORE_ACT, 0, 1),        # pitch 256, channel tail inside a staged tile
+    (7, 7, 512, 512, 3, 1, 1, 2, nn.ACT_RELU, nn.RES_NONE, 0, 0),             # K = 4608
+    (5, 5, 208, 72, 3, 1, 1, 2, nn.ACT_SILU, nn.RES_NONE, 0, 8),              # K = 1872: the last K step is partly padding
+    (128, 128, 16, 200, 1, 1, 0, 4, nn.ACT_SILU, nn.RES_NONE, 0, 8),          # 128x128 tiles, ragged channel tail
+    (96, 96, 16, 128, 3, 1, 1, 4, nn.ACT_RELU, nn.RES_BEFORE_ACT, 0, 0),
+    (64, 64, 128, 64, 1, 1, 0, 4, nn.ACT_NONE, nn.RES_NONE, 0, 0),            # 64x128 tiles
+    (256, 256, 16, 48, 1, 1, 0, 4, nn.ACT_RELU, nn.RES_NONE, 0, 0),           # 64x256 tiles
+    (56, 56, 64, 64, 3, 1, 1, 40, nn.ACT_RELU, nn.RES_BEFORE_ACT, 0, 0),      # a classifier block's layer at a served batch
+    (33, 29, 48, 130, 5, 2, 2, 3, nn.ACT_SILU, nn.RES_NONE, 0, 14),           # 5x5, stride 2, ragged everything
+]
+
+
+@pytest.mark.parametrize("case", CASES8)
+def test_conv_op_e4m3_parity(octo, case):
+    import torch
+    h, w, cin, cout, k, stride, pad, n, act, res_mode, x_extra, y_extra = case
+    rng = np.random.default_rng(33)
+    K = k * k * cin
+    xc = synth.e4m3_codes(rng, (n, h, w, cin), 8)
+    wc = synth.e4m3_codes(rng, (cout, k, k, cin), 7)
+    scale = (rng.uniform(0.5, 2.0, cout) / np.sqrt(K)).astype(np.float32)
+    bias = rng.uniform(-0.5, 0.5, cout).astype(np.float32)
+    layer = octo.ConvOp(wc, bias, "f8", stride, pad, act, scale=scale)
+    ho, wo = layer.out_hw(h, w)
+    rc = synth.e4m3_codes(rng, (n, ho, wo, cout), 8) if res_mode else None
+    res_scale, y_inv = 0.4, 6.0
+    y = fp8.conv_e4m3(xc, wc, scale, bias, stride, pad, act, rc, res_scale, res_mode)
+    S = fp8.conv_e4m3(xc & 0x7F, wc & 0x7F, scale, np.abs(bias), stride, pad, nn.ACT_NONE)
+    if res_mode:
+        S = S + np.abs(fp8.e4m3_decode(rc)) * res_scale
+    fp32_part = 4e-6 * S + 2e-6 * np.abs(y)
+    acc_abs = fp8.conv_e4m3(xc & 0x7F, wc & 0x7F, np.ones(cout), np.zeros(cout), stride, pad, nn.ACT_NONE)
+    bound = scale * 7 * 2.0 ** -13 * acc_abs + fp32_part
+    # the sample: cut-off bits added up exactly, output by output
+    xv, wv = fp8.e4m3_decode(xc), fp8.e4m3_decode(wc).reshape(cout, K)
+    xpad = np.zeros((n, h + 2 * pad, w + 2 * pad, cin)); xpad[:, pad:pad + h, pad:pad + w] = xv
+    ns = 1500
+    si, sp, sq, sk = rng.integers(0, n, ns), rng.integers(0, ho, ns), rng.integers(0, wo, ns), rng.integers(0, cout, ns)
+    tight = np.empty(ns)
+    for j in range(ns):
+        taps = xpad[si[j], sp[j] * stride:sp[j] * stride + k, sq[j] * stride:sq[j] * stride + k].reshape(K)
+        prod = np.abs(taps * wv[sk[j]]).reshape(K // 8, 8)                       # K runs over (row, column, channel), channels in 16s
+        top = prod.max(axis=1, keepdims=True)
+        unit = np.exp2(np.floor(np.log2(np.where(top > 0, top, 1.0))) - 13)
+        tight[j] = scale[sk[j]] * np.where(top > 0, np.mod(prod, unit), 0.0).sum()
+    tight = tight + fp32_part[si, sp, sq, sk]
+
+    xb = torch.zeros((n, h, w, cin + x_extra), dtype=torch.uint8, device="cuda")
+    xb[..., :cin] = torch.from_numpy(xc).cuda()
+    if x_extra:
+        xb[..., cin:] = 0x7F                                                    # NaN codes beside the tensor: never to be read
+    dres = torch.from_numpy(rc).cuda() if res_mode else None
+
+    # fp32 output
+    yb32 = torch.full((n, ho, wo, cout + y_extra), -7.0, dtype=torch.float32, device="cuda")
+    kid = octo.op_conv(layer, xb[..., :cin], yb32[..., :cout], dres, res_mode, out_f32=True, res_scale=res_scale, y_inv_scale=y_inv)
+    torch.cuda.synchronize()
+    got = yb32.cpu().numpy()
+    assert kid > 0 and (got[..., cout:] == -7.0).all()
+    err = np.abs(got[..., :cout] - y)
+    assert (err <= bound).all(), (float((err / bound).max()), kid)
+    assert (err[si, sp, sq, sk] <= tight).all(), (float((err[si, sp, sq, sk] / tight).max()), kid)
+
+    # E4M3 output
+    yb = torch.full((n, ho, wo, cout + y_extra), 0x55, dtype=torch.uint8, device="cuda")
+    octo.op_conv(layer, xb[..., :cin], yb[..., :cout], dres, res_mode, res_scale=res_scale, y_inv_scale=y_inv)
+    torch.cuda.synchronize()
+    codes = yb.cpu().numpy()
+    assert (codes[..., cout:] == 0x55).all()
+    codes = codes[..., :cout]
+    u = y * y_inv
+    d = bound * y_inv + 1e-7 * np.abs(u)                                          # + the rounding of the product itself
+    lo = fp8.e4m3_decode(fp8.e4m3_encode((u - d).astype(np.float32)))
+    hi = fp8.e4m3_decode(fp8.e4m3_encode((u + d).astype(np.float32)))
+    val = fp8.e4m3_decode(codes)
+    assert not np.isnan(val).any()
+    assert ((val >= lo) & (val <= hi)).all()
+    us, ds = u[si, sp, sq, sk], tight * y_inv + 1e-7 * np.abs(u[si, sp, sq, sk])
+    los = fp8.e4m3_decode(fp8.e4m3_encode((us - ds).astype(np.float32)))
+    his = fp8.e4m3_decode(fp8.e4m3_encode((us + ds).astype(np.float32)))
+    assert ((val[si, sp, sq, sk] >= los) & (val[si, sp, sq, sk] <= his)).all()
+    exact = codes == fp8.store_e4m3(y, y_inv)
+    same_value = exact | ((val == 0) & (fp8.e4m3_decode(fp8.store_e4m3(y, y_inv)) == 0))      # +0 and -0
+    assert same_value.mean() > 0.99, float(same_value.mean())
+    # the outputs actually use the format's range: saturated codes, subnormals and ordinary ones all occur somewhere
+    if cout * ho * wo * n > 100000:
+        mag = codes & 0x7F
+        assert (mag == 0x7E).any() or u.max() < 440
+        assert ((mag > 0) & (mag < 8)).any()
+
+
+def test_e4m3_matrix_instruction_probe_runs(octo):
+    assert octo.probe_mfma("f8", iters=2000, reps=2) > octo.probe_mfma("bf16", iters=2000, reps=2) * 1.2
