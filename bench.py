@@ -79,25 +79,25 @@ def conv_name(kid: int, dtype: str) -> str:
 # calibration pass of known size).  Valid only for the kernel sources it was taken with: keyed by their hash.
 TRAFFIC = {
     # hash of the convolution sources (conv_sources_key): {kernel name: HBM bytes per launch}
-    "ba8f2a7f41cee1f9": {
-        "octo::conv_mfma_kernel<__bf16, 128, 128, 2, 2, 8, 1, 2, true, true>": 606087757,
-        "octo::conv3x3_patch_kernel<__bf16, 64, 64>": 4244923309,
-        "octo::conv3x3_big_kernel<__bf16, 4, 4, 2, 4>": 1154116998,
-        "octo::conv_mfma_kernel<__bf16, 64, 128, 2, 2, 8, 1, 3, true, true>": 292765310,
-        "octo::conv_mfma_kernel<__bf16, 64, 256, 1, 4, 4, 1, 3, true, true>": 873243687,
-        "octo::stem_conv_kernel<__bf16, 64, 7, 4, true>": 3364805210,
-        "octo::conv3x3_big_kernel<__bf16, 3, 4, 1, 4>": 525972204,
-        "octo::conv3x3_big_kernel<__bf16, 3, 4, 2, 4>": 244992614,
-        "octo::stem_conv_kernel<__bf16, 64, 6, 3, false>": 1821761106,
-        "octo::conv_mfma_kernel<_Float16, 128, 128, 2, 2, 8, 1, 2, true, true>": 28888981,
-        "octo::conv_mfma_kernel<_Float16, 64, 128, 2, 2, 8, 1, 3, true, true>": 17879481,
-        "octo::conv3x3_patch_kernel<_Float16, 64, 64>": 69342979,
-        "octo::conv_mfma_kernel<_Float16, 32, 128, 1, 4, 4, 2, 4, true, false>": 23975865,
-        "octo::conv_mfma_kernel<_Float16, 64, 64, 2, 2, 8, 1, 4, true, true>": 7629565,
-        "octo::stem_conv_kernel<_Float16, 32, 6, 3, false>": 78884065,
-        "octo::stem_conv_kernel<_Float16, 64, 7, 4, true>": 55154693,
-        "octo::conv3x3_patch_kernel<_Float16, 32, 64>": 39949184,
-        "octo::stem_conv_kernel<_Float16, 32, 3, 2, false>": 18001020,
+    "8589e6f9ff203f61": {
+        "octo::conv_mfma_kernel<__bf16, 128, 128, 2, 2, 8, 1, 2, true, true>": 605727266,
+        "octo::conv3x3_patch_kernel<__bf16, 64, 64>": 4276448257,
+        "octo::conv3x3_big_kernel<__bf16, 4, 4, 2, 4>": 1154130223,
+        "octo::conv_mfma_kernel<__bf16, 64, 128, 2, 2, 8, 1, 3, true, true>": 292741494,
+        "octo::conv_mfma_kernel<__bf16, 64, 256, 1, 4, 4, 1, 3, true, true>": 873162647,
+        "octo::stem_conv_kernel<__bf16, 64, 7, 4, true>": 3407955769,
+        "octo::conv3x3_big_kernel<__bf16, 3, 4, 1, 4>": 525864540,
+        "octo::conv3x3_big_kernel<__bf16, 3, 4, 2, 4>": 244966287,
+        "octo::stem_conv_kernel<__bf16, 64, 6, 3, false>": 1833323334,
+        "octo::conv_mfma_kernel<_Float16, 128, 128, 2, 2, 8, 1, 2, true, true>": 28909311,
+        "octo::conv_mfma_kernel<_Float16, 64, 128, 2, 2, 8, 1, 3, true, true>": 17904517,
+        "octo::conv3x3_patch_kernel<_Float16, 64, 64>": 69229931,
+        "octo::conv_mfma_kernel<_Float16, 32, 128, 1, 4, 4, 2, 4, true, false>": 24001593,
+        "octo::conv_mfma_kernel<_Float16, 64, 64, 2, 2, 8, 1, 4, true, true>": 7626066,
+        "octo::stem_conv_kernel<_Float16, 32, 6, 3, false>": 78884028,
+        "octo::stem_conv_kernel<_Float16, 64, 7, 4, true>": 55154680,
+        "octo::conv3x3_patch_kernel<_Float16, 32, 64>": 39928923,
+        "octo::stem_conv_kernel<_Float16, 32, 3, 2, false>": 18000950,
     },
 }
 
