@@ -465,10 +465,15 @@ octo_status octo_op_crop_resize(const void* d_frame_ptrs, const void* d_pitches,
  * x, w, residual and y hold E4M3 codes; real value = code value times a scale the caller chose.
  *   y_real = act(acc * d_scale[k] + bias[k]  (+ res_code_value * res_scale)),   y_code = E4M3(y_real * y_inv_scale)
  * with d_scale (device, padded like the bias) = weight scale of channel k times the scale of x; the conversion rounds
- * to nearest even and saturates at +-448 (what a NaN result is stored as is not specified).  Needs cin, x_ld (and y_ld,
- * res_ld unless out_f32 / no residual: else a slower element-wise store is used) multiples of 16 and 16-byte aligned
- * x.  For the other types d_scale, res_scale and y_inv_scale are ignored.
- * Errors: OCTO_EINVAL for null / non-positive / misaligned arguments and shapes beyond the kernel's 32-bit offsets. */
+ * to nearest even and saturates at +-448 (what a NaN result is stored as is not specified).  cin and x_ld must be
+ * multiples of 16 (OCTO_EINVAL otherwise); y_ld and res_ld may be anything, but pitches that are no multiple of 16
+ * (y) or 4 (residual) take a slower element-wise path.  For the other types d_scale, res_scale and y_inv_scale are
+ * ignored, and any cin / pitch is accepted (channel counts or pitches that are no multiple of 8, 4 for fp32, are
+ * gathered element by element).
+ * All types: d_x, d_w, d_y and d_res must be 16-byte aligned; res_mode and d_res must agree (both or neither).
+ * Errors: OCTO_EINVAL for null / non-positive / misaligned arguments and for shapes beyond the kernel's 32-bit
+ * offsets (two images plus 1024 strided pixels of x must stay below 2 GiB; n*ho*wo below 2^31; K padded below 65536);
+ * nothing is launched then.  The call only enqueues on hip_stream. */
 typedef struct octo_conv_op {
   int32_t dtype;
   int32_t n, h, w, cin, x_ld;
