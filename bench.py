@@ -505,6 +505,8 @@ def bench_cascade(args, workload, steps, warmup, ninst, measured, with_cpu):
     pipes, keep_heads = [], []
     for _ in range(ninst):
         P = binding.Pipeline(spec)
+        if getattr(args, "det_exec", 0):
+            P.set_detector_batch(args.det_exec)
         if heads is not None:
             dh = [binding.to_device(h, det.dtype) for h in heads]
             for l, h in enumerate(dh):
@@ -599,6 +601,10 @@ def bench_cascade(args, workload, steps, warmup, ninst, measured, with_cpu):
                 "avg_launch_us": 1e3 * t_ms / launches, "launches_per_step": launches / nsamp,
                 "avg_launch_us_overlapped": 1e3 * agg_ov[dom][0] / agg_ov[dom][3],
                 "flop_per_launch": fl / launches, "bytes_per_launch": by / launches,
+                # the same launches against the memory roofline (algorithmic bytes: input + output + residual + weights):
+                # many of them are 1x1 layers whose bound is HBM, not the matrix cores
+                "algorithmic_gbps": by / (t_ms * 1e-3) / 1e9, "hbm_frac": by / (t_ms * 1e-3) / 1e9 / 8000.0,
+                "hbm_frac_of_measured": by / (t_ms * 1e-3) / 1e9 / measured["copy_gbps"] if measured.get("copy_gbps") else None,
                 "share_of_conv_time": t_ms / sum(v[0] for v in conv.values()),
                 "all_conv_tflops_per_kernel": sum(v[1] for v in conv.values()) / (sum(v[0] for v in conv.values()) * 1e-3) / 1e12,
                 "conv_flop_per_step": sum(v[1] for v in conv.values()) / nsamp,
@@ -656,6 +662,7 @@ def main():
                     help="copies of the pipeline (own activations and tables) that take batches in turn, each on its own "
                          "stream, so that kernels of different batches overlap on the GPU (default: 4 for the traffic and "
                          "sweep workloads, 1 for the high-resolution one, whose batches fill the GPU by themselves)")
+    ap.add_argument("--det-exec", type=int, default=0, help="frames per execution of the detector's layers (0: the whole batch at once)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-traffic", action="store_true", help="high-resolution workload: do not also run the traffic workload for the extra key")
     ap.add_argument("--traffic-steps", type=int, default=400, help="timed batches of the traffic workload run beside the high-resolution one")

@@ -122,7 +122,8 @@ typedef struct {
                                                          1: and every layer runs on its own, so every tensor is written;
                                                          2: layers are fused as in normal operation (a first layer followed by
                                                          a 3x3 / stride-2 max-pool writes only the pooled tensor; the tensor
-                                                         in between then holds nothing) */
+                                                         in between then holds nothing; two consecutive 1x1 convolutions of
+                                                         one input with one activation run as one launch) */
 } octo_pipeline_desc;
 
 typedef struct octo_pipeline octo_pipeline;
@@ -394,7 +395,9 @@ octo_status octo_profile_layers(octo_pipeline* p, int32_t model, int32_t n, int3
  * channel slice SS; 19 0F BBB KK P: first-layer kernel, channel tile, kernel height, kernel width in pixel pairs,
  * F = 1 when it also computes the 3x3 / stride-2 max-pool that follows (that layer then reports kernel 0 and 0 ms);
  * 1 max-pool, 2 upsample, 3 channel copy, 4 add, 5 global average pool, 0 none), per ITEM dense FLOPs and activation
- * bytes (input, output and residual elements), and per LAUNCH weight and bias bytes. */
+ * bytes (input, output and residual elements), and per LAUNCH weight and bias bytes.  When two 1x1 convolutions of
+ * the same input run as one launch, the first reports the kernel, the time and the work of both (the shared input
+ * counted once) and the second kernel 0 and no work. */
 octo_status octo_set_layer_timing(octo_pipeline* p, int32_t enable);
 octo_status octo_get_layer_info(octo_pipeline* p, int32_t model, float* ms, int32_t* kernel_id, double* flops, double* bytes,
                                 double* weight_bytes, int32_t cap, int32_t* n);

@@ -316,6 +316,7 @@ __global__ __launch_bounds__(THREADS, MINB) void conv_mfma_kernel(const ConvArgs
     }
 
     // epilogue: a lane holds pixel column l32 of each 32x32 block and 4 groups of 4 consecutive channels
+    // (a launch with a second output tensor always takes the staged path: the host has checked its alignment)
     const bool staged = STAGED && !a.out_f32 && ((a.y_ld | a.y_coff) & (VN - 1)) == 0 && (((uintptr_t)a.y & 15) == 0);
     if (staged) __syncthreads();       // every wavefront is done reading the operand tiles
     // the arithmetic is compiled once per (residual mode, SiLU or not): see finish4
@@ -406,7 +407,9 @@ __global__ __launch_bounds__(THREADS, MINB) void conv_mfma_kernel(const ConvArgs
         const long long p = p0 + pl;
         if (p < M && c < a.Cout) {
           const u32x4 val = *(const u32x4*)((const char*)smem + (size_t)pl * OPITCH + (size_t)v * 16);
-          T* yp = (T*)a.y + (size_t)p * a.y_ld + a.y_coff + c;
+          // two layers in one launch: a vector never straddles the split (a multiple of 8 channels)
+          const bool second = a.split > 0 && c >= a.split;
+          T* yp = second ? (T*)a.y2 + (size_t)p * a.y2_ld + a.y2_coff + (c - a.split) : (T*)a.y + (size_t)p * a.y_ld + a.y_coff + c;
           if (c + VN <= a.Cout) {
             *(u32x4*)yp = val;
           } else if constexpr (ES == 1) {
@@ -536,6 +539,13 @@ bool conv_prepare(ConvArgs& a, int dtype) {
 hipError_t launch_conv(int dtype, const ConvArgs& a0, int num_cu, hipStream_t s, int* kernel_id, ConvTiming tm) {
   ConvArgs a = a0;
   if (!conv_prepare(a, dtype)) return hipErrorInvalidValue;
+  if (a.split > 0) {
+    // two layers in one launch: only the general kernel's staged epilogue knows the second output tensor
+    const bool ok = (dtype == OCTO_F16 || dtype == OCTO_BF16) && a.y2 && !a.res && !a.out_f32 && !a.pair_view && !a.pool_y && a.split < a.Cout &&
+                    ((a.split | a.Cout | a.y_ld | a.y_coff | a.y2_ld | a.y2_coff) & 7) == 0 && ((((uintptr_t)a.y | (uintptr_t)a.y2) & 15) == 0);
+    if (!ok) return hipErrorNotSupported;
+    return dtype == OCTO_F16 ? launch_typed<_Float16>(a, num_cu, s, kernel_id, tm) : launch_typed<__bf16>(a, num_cu, s, kernel_id, tm);
+  }
   const hipError_t es = launch_stem(dtype, a, num_cu, s, kernel_id, tm);
   if (es != hipErrorNotSupported || a.pool_y) return es;      // only the first-layer kernel can pool its own output
   // 3x3 layers with at most 64 output channels on wide images: the input patch of a tile lives in LDS (measured

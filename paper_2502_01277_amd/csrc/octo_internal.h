@@ -42,6 +42,10 @@ struct ConvArgs {
   // written and y is not touched; launch_conv returns hipErrorNotSupported if no kernel can do that for the layer.
   void* pool_y;
   int pool_ho, pool_wo, pool_ld, pool_coff;
+  // Two layers in one launch (general kernel, 16-bit types, no residual): output channels below `split` go to y as
+  // usual, channels split .. Cout - 1 to y2 as its channels 0 ..; split is a multiple of 8 and 0 when unused.
+  void* y2;
+  int y2_ld, y2_coff, split;
   // 8-bit floating point storage only: y = act(acc * scale[c] + bias[c] (+ res * res_scale)), stored as
   // E4M3(y * y_inv_scale) unless out_f32.  scale: device, one factor per output channel, padded like the bias.
   const float* scale;

@@ -41,6 +41,7 @@ struct LayerPlan {
   int K = 0, Kp = 0, cout_pad = 0;
   std::vector<int> copy_inputs;   // concat: inputs that could not be aliased into the output buffer
   double flops = 0, bytes = 0;    // per item
+  double input_bytes = 0;         // conv: the part of `bytes` that is the input tensor
   double weight_bytes = 0;        // per launch
   int kernel_id = KID_NONE;       // which kernel the last launch of this layer used
   // First layer on a 3-channel input: run on the pixel-pair view of the 4-channel-padded input (two neighbouring
@@ -52,6 +53,14 @@ struct LayerPlan {
   // convolution kernel pools its own tile and writes the pooled tensor, the pool layer does nothing (its kernel id
   // then reads KID_NONE).  Cleared for good the first time no kernel accepts the fused form.
   bool fuse_pool = false;
+  // The next layer is a 1x1 convolution of the same input with the same activation (the two entry convolutions of a
+  // cross-stage block): one launch computes both - the weight matrices stacked, the second layer's channels written to
+  // its own tensor - so the input is read once.  The next layer then does nothing (kernel id KID_NONE).  Cleared for
+  // good the first time the kernel refuses the fused form.
+  bool fuse_twin = false;
+  void* d_weight_twin = nullptr;
+  float* d_bias_twin = nullptr;
+  int twin_cout_pad = 0;
 };
 
 struct TensorPlan {
@@ -192,6 +201,7 @@ octo_status plan_shapes(ModelPlan& m, std::string& why) {
         lp.bytes = (double)es * x.h * x.w * x.c + (double)(y.f32 ? 4 : es) * y.h * y.w * y.c +
                    (L.n_in == 2 ? (double)es * y.h * y.w * y.c : 0.0);
         lp.weight_bytes = (double)es * L.cout * kh * kw * x.c + 4.0 * L.cout;
+        lp.input_bytes = (double)es * x.h * x.w * x.c;
         break;
       }
       case OCTO_MAXPOOL:
@@ -320,6 +330,19 @@ void plan_activations(ModelPlan& m, bool keep_all, bool allow_fusion) {
       for (int k = 0; k < q.L.n_in; ++k) readers += q.L.in[k] == i + 1;
     lp.fuse_pool = readers == 1;
   }
+  // two 1x1 convolutions in a row that read the same tensor: one launch (16-bit types; channel counts and output
+  // views in whole 16-byte vectors; no residual, not the first layer, no fp32 output)
+  for (int i = 0; i < (int)m.layers.size(); ++i) m.layers[i].fuse_twin = false;
+  for (int i = 0; i + 1 < (int)m.layers.size(); ++i) {
+    LayerPlan& a = m.layers[i];
+    const LayerPlan& b = m.layers[i + 1];
+    if (!allow_fusion || dtype_size(m.d.dtype) != 2 || a.fuse_pool || (i > 0 && m.layers[i - 1].fuse_twin)) continue;
+    if (a.L.op != OCTO_CONV || b.L.op != OCTO_CONV || a.L.n_in != 1 || b.L.n_in != 1 || a.L.in[0] != b.L.in[0] || a.pair_view || b.pair_view) continue;
+    if (a.L.kh != 1 || a.L.kw != 1 || b.L.kh != 1 || b.L.kw != 1 || a.L.stride != 1 || b.L.stride != 1 || a.L.pad != 0 || b.L.pad != 0 || a.L.act != b.L.act) continue;
+    const TensorPlan &ta = m.tensors[i + 1], &tb = m.tensors[i + 2];
+    if (ta.f32 || tb.f32 || ((a.L.cout | b.L.cout | ta.ld | ta.coff | tb.ld | tb.coff) & 7)) continue;
+    a.fuse_twin = true;
+  }
   // lifetimes of root buffers in layer steps: tensor t is written at step t-1 (input: -1)
   std::vector<int> birth(nt, 1 << 30), death(nt, -2);
   for (int t = 0; t < nt; ++t) {
@@ -328,7 +351,7 @@ void plan_activations(ModelPlan& m, bool keep_all, bool allow_fusion) {
     death[r] = std::max(death[r], t - 1);
   }
   for (int i = 0; i < (int)m.layers.size(); ++i)
-    if (m.layers[i].fuse_pool) {             // the pooled tensor is written one step early, by the convolution
+    if (m.layers[i].fuse_pool || m.layers[i].fuse_twin) {      // the next layer's output is written one step early, by this layer
       const int r = m.tensors[i + 2].root;
       birth[r] = std::min(birth[r], i);
     }
@@ -394,13 +417,21 @@ TensorView view_of(const ModelPlan& m, int t) {
 // ---- weights ----------------------------------------------------------------
 octo_status pack_weights(octo_pipeline* p, ModelPlan& m, Arena& ar) {
   const int es = dtype_size(m.d.dtype);
-  for (LayerPlan& lp : m.layers) {
+  for (size_t li = 0; li < m.layers.size(); ++li) {
+    LayerPlan& lp = m.layers[li];
     if (lp.L.op != OCTO_CONV && lp.L.op != OCTO_FC) continue;
     const int pk_kw = lp.pair_view ? lp.pair_kw : lp.L.kw, pk_cin = lp.pair_view ? 8 : lp.cin;
     lp.K = lp.L.kh * pk_kw * pk_cin;
     const size_t elems = conv_packed_weight_elems(lp.L.cout, lp.L.kh, pk_kw, pk_cin, m.d.dtype, &lp.Kp, &lp.cout_pad);
     lp.d_weight = ar.alloc(elems * es + 512);   // slack: the conv prefetch may read a K step past the last row
     lp.d_bias = (float*)ar.alloc((size_t)lp.cout_pad * sizeof(float));
+    size_t twin_elems = 0;
+    int twin_kp = 0;
+    if (lp.fuse_twin) {      // this layer's and the next one's weights as one matrix (both 1x1 on the same input: same K)
+      twin_elems = conv_packed_weight_elems(lp.L.cout + m.layers[li + 1].L.cout, 1, 1, lp.cin, m.d.dtype, &twin_kp, &lp.twin_cout_pad);
+      lp.d_weight_twin = ar.alloc(twin_elems * es + 512);
+      lp.d_bias_twin = (float*)ar.alloc((size_t)lp.twin_cout_pad * sizeof(float));
+    }
     if (!ar.base) continue;
     if (ar.failed) return OCTO_ENOMEM;
     std::vector<char> host(elems * es, 0);
@@ -424,6 +455,19 @@ octo_status pack_weights(octo_pipeline* p, ModelPlan& m, Arena& ar) {
     std::vector<float> hb(lp.cout_pad, 0.f);
     memcpy(hb.data(), lp.L.bias, (size_t)lp.L.cout * sizeof(float));
     HIPCHK(p, hipMemcpy(lp.d_bias, hb.data(), hb.size() * sizeof(float), hipMemcpyHostToDevice));
+    if (lp.fuse_twin) {
+      const octo_layer& N = m.layers[li + 1].L;       // not packed yet: its host arrays are still there
+      std::vector<char> tw(twin_elems * es, 0);
+      std::vector<float> tb(lp.twin_cout_pad, 0.f);
+      for (int k = 0; k < lp.L.cout; ++k)
+        memcpy(tw.data() + (size_t)k * twin_kp * es, (const char*)lp.L.weight + (size_t)k * lp.K * es, (size_t)lp.K * es);
+      for (int k = 0; k < N.cout; ++k)
+        memcpy(tw.data() + (size_t)(lp.L.cout + k) * twin_kp * es, (const char*)N.weight + (size_t)k * lp.K * es, (size_t)lp.K * es);
+      memcpy(tb.data(), lp.L.bias, (size_t)lp.L.cout * sizeof(float));
+      memcpy(tb.data() + lp.L.cout, N.bias, (size_t)N.cout * sizeof(float));
+      HIPCHK(p, hipMemcpy(lp.d_weight_twin, tw.data(), tw.size(), hipMemcpyHostToDevice));
+      HIPCHK(p, hipMemcpy(lp.d_bias_twin, tb.data(), tb.size() * sizeof(float), hipMemcpyHostToDevice));
+    }
     lp.L.weight = nullptr; lp.L.bias = nullptr;   // caller memory is not referenced after create
   }
   return OCTO_OK;
@@ -446,6 +490,16 @@ hipError_t run_layer(octo_pipeline* p, ModelPlan& m, int i, int n, const int* n_
       a.act = L.act; a.res_mode = L.res_mode; a.out_f32 = m.tensors[i + 1].f32 ? 1 : 0;
       if (L.n_in == 2) { const TensorView r = view_of(m, L.in[1]); a.res = r.ptr; a.res_ld = r.ld; a.res_coff = r.coff; }
       if (n_dyn && m.items_hint > 0) a.n_hint = std::max(1, (int)(m.items_hint + 0.999));
+      if (i > 0 && m.layers[i - 1].fuse_twin) { lp.kernel_id = KID_NONE; return hipSuccess; }     // computed by the layer before
+      if (lp.fuse_twin) {
+        const TensorView y2 = view_of(m, i + 2);
+        ConvArgs f = a;
+        f.Cout = L.cout + m.layers[i + 1].L.cout; f.w = lp.d_weight_twin; f.bias = lp.d_bias_twin; f.w_rows = lp.twin_cout_pad;
+        f.y2 = y2.ptr; f.y2_ld = y2.ld; f.y2_coff = y2.coff; f.split = L.cout;
+        const hipError_t e = launch_conv(m.d.dtype, f, p->num_cu, s, &lp.kernel_id, tm);
+        if (e != hipErrorNotSupported) return e;
+        lp.fuse_twin = false;
+      }
       if (lp.fuse_pool) {
         const TensorView py = view_of(m, i + 2);
         ConvArgs f = a;
@@ -996,11 +1050,17 @@ octo_status octo_collect(octo_pipeline* p, octo_frame_result* frames, int32_t fr
       const size_t L = p->models[k].layers.size();
       for (size_t i = 0; i < L && le.size() == 3 * L + 1; ++i) {
         // convolutions: the kernel's own run time from the events on its dispatch; other layers: stream bracket
-        const bool conv = p->models[k].layers[i].L.op == OCTO_CONV || p->models[k].layers[i].L.op == OCTO_FC;
+        // (a convolution that launched nothing - its work was done by the layer before - has no dispatch events; a
+        // failed query must not stay behind as the runtime's last error either: the next launch would report it)
+        const LayerPlan& lq = p->models[k].layers[i];
+        const bool conv = (lq.L.op == OCTO_CONV || lq.L.op == OCTO_FC) && lq.kernel_id != KID_NONE;
         float ms = 0.f;
         if (!B.model_ran[k]) ms = 0.f;
         else if (conv && hipEventElapsedTime(&ms, le[L + 1 + 2 * i], le[L + 2 + 2 * i]) == hipSuccess) {}
-        else if (hipEventElapsedTime(&ms, le[i], le[i + 1]) != hipSuccess) ms = 0.f;
+        else {
+          if (conv) (void)hipGetLastError();
+          if (hipEventElapsedTime(&ms, le[i], le[i + 1]) != hipSuccess) { ms = 0.f; (void)hipGetLastError(); }
+        }
         p->last_layer_ms[k].push_back(ms);
       }
       for (hipEvent_t e : le) p->event_pool.push_back(e);
@@ -1076,9 +1136,11 @@ octo_status octo_get_layer_info(octo_pipeline* p, int32_t model, float* ms, int3
   for (int i = 0; i < *n; ++i) {
     if (ms) ms[i] = (model < (int)p->last_layer_ms.size() && i < (int)p->last_layer_ms[model].size()) ? p->last_layer_ms[model][i] : 0.f;
     if (kernel_id) kernel_id[i] = m.layers[i].kernel_id;
-    if (flops) flops[i] = m.layers[i].flops;
-    if (bytes) bytes[i] = m.layers[i].bytes;
-    if (weight_bytes) weight_bytes[i] = m.layers[i].weight_bytes;
+    // two layers in one launch: the work is reported with the first, the second did nothing
+    const bool first = m.layers[i].fuse_twin && i + 1 < (int)m.layers.size(), second = i > 0 && m.layers[i - 1].fuse_twin;
+    if (flops) flops[i] = second ? 0.0 : m.layers[i].flops + (first ? m.layers[i + 1].flops : 0.0);
+    if (bytes) bytes[i] = second ? 0.0 : m.layers[i].bytes + (first ? m.layers[i + 1].bytes - m.layers[i].input_bytes : 0.0);
+    if (weight_bytes) weight_bytes[i] = second ? 0.0 : m.layers[i].weight_bytes + (first ? m.layers[i + 1].weight_bytes : 0.0);
   }
   return OCTO_OK;
 }
@@ -1102,8 +1164,10 @@ octo_status octo_profile_layers(octo_pipeline* p, int32_t model, int32_t n, int3
     float t = 0.f;
     HIPCHK(p, hipEventElapsedTime(&t, e0, e1));
     ms[i] = t / iters;
-    if (flops) flops[i] = m.layers[i].flops * n;
-    if (bytes) bytes[i] = m.layers[i].bytes * n + m.layers[i].weight_bytes;
+    const bool first = m.layers[i].fuse_twin && i + 1 < (int)m.layers.size(), second = i > 0 && m.layers[i - 1].fuse_twin;
+    if (flops) flops[i] = second ? 0.0 : (m.layers[i].flops + (first ? m.layers[i + 1].flops : 0.0)) * n;
+    if (bytes) bytes[i] = second ? 0.0 : (m.layers[i].bytes + (first ? m.layers[i + 1].bytes - m.layers[i].input_bytes : 0.0)) * n +
+                                             m.layers[i].weight_bytes + (first ? m.layers[i + 1].weight_bytes : 0.0);
   }
   hipEventDestroy(e0); hipEventDestroy(e1);
   return OCTO_OK;

@@ -213,6 +213,44 @@ def test_first_layer_with_fused_max_pool(octo, dtype, case):
 
 
 @pytest.mark.parametrize("dtype", ["f16", "bf16"])
+@pytest.mark.parametrize("case", [(40, 40, 96, 48, 48, 6), (23, 17, 64, 32, 96, 5), (80, 80, 192, 96, 96, 4), (9, 9, 384, 192, 192, 3), (12, 12, 48, 40, 24, 2)])
+def test_two_1x1_layers_of_one_input_in_one_launch(octo, dtype, case):
+    """The two entry convolutions of a cross-stage block read the same tensor: one launch computes both, the second
+    layer's channels going straight into its slice of the concatenation buffer.  Every tensor is compared with the
+    oracle and, bit for bit, with the path that runs every layer on its own; the layer table shows one kernel for the pair.
+    Sizes: equal and unequal halves, a ragged pixel count, enough pixels for the 128-pixel tiles, the channel counts of the
+    detector's stages."""
+    h, w, cin, c1, c2, n = case
+
+    def build(B):
+        x = B.conv(0, cin, 3, 1, 1, act=zoo.ACT_SILU)
+        a = B.conv(x, c1, 1, 1, 0, act=zoo.ACT_SILU)
+        b = B.conv(x, c2, 1, 1, 0, act=zoo.ACT_SILU)
+        a2 = B.conv(a, c1, 3, 1, 1, act=zoo.ACT_SILU)
+        return B.conv(B.cat([a2, b]), 64, 1, 1, 0, act=zoo.ACT_SILU)
+    m = _model(dtype, (h, w), 16, build, n)
+    x = zoo.round_to_dtype(np.random.default_rng(23).uniform(-1, 1, (n, h, w, 16)).astype(np.float32), dtype)
+    spec = zoo.PipelineSpec("t", [small_root(dtype), m], [], 200.0, 32, 32, 1, 1)
+    got, kids, work = {}, {}, {}
+    for keep in (0, 1, 2):
+        P = octo.Pipeline(spec, keep_all_tensors=keep)
+        P.run_model_on(1, octo.to_device(x, dtype))
+        got[keep] = [P.get_tensor(1, t, n) for t in ((2, 3, 4, 5, 6) if keep else ())] + [P.get_tensor(1, m.outputs[0], n)]   # keep = 0 recycles buffers
+        info = P.layer_info(1)
+        kids[keep], work[keep] = [int(k) for k in info[1][1:3]], (info[2].sum(), info[2][1:3].tolist())
+        P.close()
+    assert kids[0] == kids[2] and kids[2][0] > 1000000000 and kids[2][1] == 0 and kids[1][1] > 1000000000, kids
+    assert work[0][0] == work[1][0] and work[2][1][1] == 0 and work[2][1][0] == sum(work[1][1])       # the pair's work is reported with its first layer
+    ref = nn.run_model(m, x, keep_all=True)
+    for j, t in enumerate((2, 3, 4, 5, 6)):
+        assert rel_err(got[2][j], ref[t]) <= TOL[dtype], t
+        assert np.array_equal(got[2][j], got[1][j]), t
+    for keep in (0, 1, 2):
+        assert rel_err(got[keep][-1], ref[m.outputs[0]]) <= TOL[dtype]
+        assert np.array_equal(got[keep][-1], got[1][-1])
+
+
+@pytest.mark.parametrize("dtype", ["f16", "bf16"])
 def test_wide_3x3_layers_with_residuals(octo, dtype):
     """Large enough for the 3x3 kernel that keeps the input patch in LDS: both residual modes, SiLU and ReLU."""
     def build(B):
