@@ -60,6 +60,64 @@ __global__ void maxpool_kernel(const PoolArgs a) {
   }
 }
 
+// Stride-1 "same" max-pool (window K, padding K / 2: the chained 5x5 pools of a spatial-pyramid block).  A work item
+// owns one (image, row segment, column, 16-byte channel vector) and walks down the rows: of every input row it takes
+// the maximum over the K columns of its window once and keeps the last K of those row maxima in registers, so an
+// output costs K loads instead of K x K.  The row loop is unrolled K times so that the ring of row maxima is indexed
+// statically.  Same result as maxpool_kernel: a maximum does not depend on the order it is taken in.
+template <typename T, int K>
+__global__ __launch_bounds__(256) void maxpool_rows_kernel(const PoolArgs a, int seg_rows, int n_seg) {
+  constexpr int V = 16 / (int)sizeof(T), P = K / 2;
+  const int cv = a.C / V;
+  const long long total = (long long)dyn_items(a.n_dyn, a.n) * n_seg * a.W * cv;
+  const T* x = (const T*)a.x;
+  T* y = (T*)a.y;
+  for (long long i = blockIdx.x * (long long)blockDim.x + threadIdx.x; i < total; i += (long long)gridDim.x * blockDim.x) {
+    const int c = (int)(i % cv) * V;
+    long long t = i / cv;
+    const int wo = (int)(t % a.W); t /= a.W;
+    const int seg = (int)(t % n_seg);
+    const long long img = t / n_seg;
+    const int r0 = seg * seg_rows, r1 = r0 + seg_rows < a.H ? r0 + seg_rows : a.H;
+    const int s_lo = wo - P < 0 ? 0 : wo - P, s_hi = wo + P > a.W - 1 ? a.W - 1 : wo + P;
+    float ring[K][V];
+    // maximum of input row r over this item's window columns (a row outside the image contributes nothing)
+    auto row_max = [&](int r, float (&m)[V]) {
+#pragma unroll
+      for (int e = 0; e < V; ++e) m[e] = -INFINITY;
+      if ((unsigned)r >= (unsigned)a.H) return;
+      const T* p = x + ((size_t)(img * a.H + r) * a.W) * a.x_ld + a.x_coff + c;
+#pragma unroll
+      for (int j = 0; j < K; ++j) {
+        const int wi = s_lo + j;
+        if (wi > s_hi) break;
+        alignas(16) T v[V];
+        *(uint4*)v = *(const uint4*)(p + (size_t)wi * a.x_ld);
+#pragma unroll
+        for (int e = 0; e < V; ++e) m[e] = fmaxf(m[e], (float)v[e]);
+      }
+    };
+#pragma unroll
+    for (int j = 0; j < K - 1; ++j) row_max(r0 - P + j, ring[j]);
+    for (int ho = r0; ho < r1; ho += K) {
+#pragma unroll
+      for (int j = 0; j < K; ++j) {
+        if (ho + j >= r1) break;
+        row_max(ho + j + P, ring[(j + K - 1) % K]);        // replaces the row that left the window
+        alignas(16) T o[V];
+#pragma unroll
+        for (int e = 0; e < V; ++e) {
+          float m = ring[0][e];
+#pragma unroll
+          for (int q = 1; q < K; ++q) m = fmaxf(m, ring[q][e]);
+          o[e] = (T)m;
+        }
+        *(uint4*)(y + ((size_t)(img * a.H + ho + j) * a.W + wo) * a.y_ld + a.y_coff + c) = *(const uint4*)o;
+      }
+    }
+  }
+}
+
 // mode 0: nearest 2x upsample (y is 2H x 2W); mode 1: plain copy (y is H x W)
 template <typename T, int V, int MODE>
 __global__ void copy_kernel(const PoolArgs a) {
@@ -151,6 +209,21 @@ template <typename T> static bool vec_ok(const void* x, int x_ld, int x_coff, co
 template <typename T> static hipError_t maxpool_t(const PoolArgs& a, hipStream_t s) {
   constexpr int V = 16 / sizeof(T);
   if (vec_ok<T>(a.x, a.x_ld, a.x_coff, a.y, a.y_ld, a.y_coff, a.C)) {
+    // Stride-1 "same" pools with enough columns to give every SIMD a wavefront: the row-walking kernel.  (With fewer
+    // its serial walk down the rows is slower than the general kernel's k x k loads per output: 8 x 20 x 20 x 256 took
+    // 25 us against 14.)  Row segments: several windows long, since each re-reads k - 1 rows.
+    const long long columns = (long long)a.n * a.W * (a.C / V);
+    long long n_seg = (262144 + columns - 1) / columns;
+    if (n_seg > a.H / (2 * a.k)) n_seg = a.H / (2 * a.k);
+    if (n_seg < 1) n_seg = 1;
+    if (a.stride == 1 && (a.k == 5 || a.k == 3) && a.pad == a.k / 2 && a.Ho == a.H && a.Wo == a.W && a.H >= 2 * a.k && columns * n_seg >= 65536) {
+      const int seg_rows = (int)((a.H + n_seg - 1) / n_seg);
+      n_seg = (a.H + seg_rows - 1) / seg_rows;
+      const unsigned grid = grid_for(columns * n_seg, 256);
+      if (a.k == 5) hipLaunchKernelGGL((maxpool_rows_kernel<T, 5>), dim3(grid), dim3(256), 0, s, a, seg_rows, (int)n_seg);
+      else hipLaunchKernelGGL((maxpool_rows_kernel<T, 3>), dim3(grid), dim3(256), 0, s, a, seg_rows, (int)n_seg);
+      return hipGetLastError();
+    }
     long long work = (long long)a.n * a.Ho * a.Wo * (a.C / V);
     hipLaunchKernelGGL((maxpool_kernel<T, V>), dim3(grid_for(work, 256)), dim3(256), 0, s, a);
   } else {

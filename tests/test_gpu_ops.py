@@ -212,6 +212,31 @@ def test_first_layer_with_fused_max_pool(octo, dtype, case):
     assert np.array_equal(got[0][1], got[1][1]) and np.array_equal(got[2][1], got[1][1])
 
 
+@pytest.mark.parametrize("dtype", ["f32", "f16", "bf16"])
+@pytest.mark.parametrize("case", [(40, 40, 384, 5, 9), (23, 3, 512, 5, 176), (64, 9, 256, 3, 24), (11, 50, 256, 5, 48), (9, 9, 40, 5, 2), (40, 40, 64, 5, 4)])
+def test_stride_1_max_pools_walk_down_the_rows(octo, dtype, case):
+    """Chained k x k / stride-1 / pad k/2 pools (a spatial-pyramid block): the row-walking kernel keeps the last k row
+    maxima of its window in registers.  Each pooled tensor must equal, exactly, the window maximum (oracle) of the tensor
+    the GPU itself fed it.  The kernel is only chosen for launches with at least 65536 (column, segment) work items, so
+    the edge shapes come with many items and channels: the detector's own 40 x 40 x 384 in four row segments, a map
+    narrower than the window in two segments of 12 and 11 rows, 3 x 3 windows in ten segments, one segment of 11 rows
+    (two unrolled passes and one row); the last two cases take the general pool kernel (too few rows, too few columns)."""
+    h, w, c, k, n = case
+
+    def build(B):
+        x = B.conv(0, c, 1, 1, 0, act=zoo.ACT_NONE)
+        p1 = B.maxpool(x, k, 1, k // 2)
+        p2 = B.maxpool(p1, k, 1, k // 2)
+        return B.conv(B.cat([x, p1, p2]), 16, 1, 1, 0)
+    m = _model(dtype, (h, w), 8, build, n)
+    x = zoo.round_to_dtype(np.random.default_rng(29).uniform(-1, 1, (n, h, w, 8)).astype(np.float32), dtype)
+    got = _run_detached(octo, m, x)
+    assert np.array_equal(got[2], nn.maxpool(got[1], k, 1, k // 2).astype(np.float32))
+    assert np.array_equal(got[3], nn.maxpool(got[2], k, 1, k // 2).astype(np.float32))
+    ref = nn.run_model(m, x, keep_all=True)
+    assert rel_err(got[-1], ref[-1]) <= TOL[dtype]
+
+
 @pytest.mark.parametrize("dtype", ["f16", "bf16"])
 @pytest.mark.parametrize("case", [(40, 40, 96, 48, 48, 6), (23, 17, 64, 32, 96, 5), (80, 80, 192, 96, 96, 4), (9, 9, 384, 192, 192, 3), (12, 12, 48, 40, 24, 2)])
 def test_two_1x1_layers_of_one_input_in_one_launch(octo, dtype, case):
