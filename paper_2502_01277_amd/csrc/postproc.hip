@@ -416,12 +416,19 @@ __global__ __launch_bounds__(64) void nms_reduce_kernel(const NmsArgs a) {
         }
       }
       // fold the rows of the boxes kept in this block into the words of later blocks
+      // (four rows per round, so that their loads are in flight together; a round with fewer rows left repeats the last)
       if (lane > blk && lane < nblk) {
         unsigned long long k2 = kept;
+        const unsigned long long* col = mask + (size_t)blk * 64 * nb + lane;
         while (k2) {
-          const int t = __ffsll((long long)k2) - 1;
-          k2 &= k2 - 1;
-          removed |= mask[(size_t)(blk * 64 + t) * nb + lane];
+          int t[4];
+#pragma unroll
+          for (int q = 0; q < 4; ++q) {
+            t[q] = k2 ? __ffsll((long long)k2) - 1 : t[q > 0 ? q - 1 : 0];
+            k2 &= k2 - 1;                      // 0 stays 0
+          }
+          const unsigned long long r0 = col[(size_t)t[0] * nb], r1 = col[(size_t)t[1] * nb], r2 = col[(size_t)t[2] * nb], r3 = col[(size_t)t[3] * nb];
+          removed |= (r0 | r1) | (r2 | r3);
         }
       }
     }
