@@ -79,25 +79,25 @@ def conv_name(kid: int, dtype: str) -> str:
 # calibration pass of known size).  Valid only for the kernel sources it was taken with: keyed by their hash.
 TRAFFIC = {
     # hash of the convolution sources (conv_sources_key): {kernel name: HBM bytes per launch}
-    "8589e6f9ff203f61": {
-        "octo::conv_mfma_kernel<__bf16, 128, 128, 2, 2, 8, 1, 2, true, true>": 605727266,
-        "octo::conv3x3_patch_kernel<__bf16, 64, 64>": 4276448257,
-        "octo::conv3x3_big_kernel<__bf16, 4, 4, 2, 4>": 1154130223,
-        "octo::conv_mfma_kernel<__bf16, 64, 128, 2, 2, 8, 1, 3, true, true>": 292741494,
-        "octo::conv_mfma_kernel<__bf16, 64, 256, 1, 4, 4, 1, 3, true, true>": 873162647,
-        "octo::stem_conv_kernel<__bf16, 64, 7, 4, true>": 3407955769,
-        "octo::conv3x3_big_kernel<__bf16, 3, 4, 1, 4>": 525864540,
-        "octo::conv3x3_big_kernel<__bf16, 3, 4, 2, 4>": 244966287,
-        "octo::stem_conv_kernel<__bf16, 64, 6, 3, false>": 1833323334,
-        "octo::conv_mfma_kernel<_Float16, 128, 128, 2, 2, 8, 1, 2, true, true>": 28909311,
-        "octo::conv_mfma_kernel<_Float16, 64, 128, 2, 2, 8, 1, 3, true, true>": 17904517,
-        "octo::conv3x3_patch_kernel<_Float16, 64, 64>": 69229931,
-        "octo::conv_mfma_kernel<_Float16, 32, 128, 1, 4, 4, 2, 4, true, false>": 24001593,
-        "octo::conv_mfma_kernel<_Float16, 64, 64, 2, 2, 8, 1, 4, true, true>": 7626066,
-        "octo::stem_conv_kernel<_Float16, 32, 6, 3, false>": 78884028,
-        "octo::stem_conv_kernel<_Float16, 64, 7, 4, true>": 55154680,
-        "octo::conv3x3_patch_kernel<_Float16, 32, 64>": 39928923,
-        "octo::stem_conv_kernel<_Float16, 32, 3, 2, false>": 18000950,
+    "5888fed9d88a236e": {
+        "octo::conv_mfma_kernel<__bf16, 128, 128, 2, 2, 8, 1, 2, true, true>": 624811638,
+        "octo::conv3x3_patch_kernel<__bf16, 64, 64>": 4274865350,
+        "octo::conv3x3_big_kernel<__bf16, 4, 4, 2, 4>": 1154115296,
+        "octo::conv_mfma_kernel<__bf16, 64, 128, 2, 2, 8, 1, 3, true, true>": 348088736,
+        "octo::stem_conv_kernel<__bf16, 64, 7, 4, true>": 3364314218,
+        "octo::conv_mfma_kernel<__bf16, 64, 256, 1, 4, 4, 1, 3, true, true>": 792448096,
+        "octo::conv3x3_big_kernel<__bf16, 3, 4, 1, 4>": 526065361,
+        "octo::conv3x3_big_kernel<__bf16, 3, 4, 2, 4>": 245009744,
+        "octo::stem_conv_kernel<__bf16, 64, 6, 3, false>": 1821188443,
+        "octo::conv_mfma_kernel<_Float16, 128, 128, 2, 2, 8, 1, 2, true, true>": 29220352,
+        "octo::conv_mfma_kernel<_Float16, 64, 128, 2, 2, 8, 1, 3, true, true>": 18777533,
+        "octo::conv3x3_patch_kernel<_Float16, 64, 64>": 69226873,
+        "octo::stem_conv_kernel<_Float16, 32, 6, 3, false>": 78879936,
+        "octo::conv_mfma_kernel<_Float16, 64, 64, 2, 2, 8, 1, 4, true, true>": 6634909,
+        "octo::stem_conv_kernel<_Float16, 64, 7, 4, true>": 55150590,
+        "octo::conv_mfma_kernel<_Float16, 32, 128, 1, 4, 4, 2, 4, true, false>": 13645294,
+        "octo::conv3x3_patch_kernel<_Float16, 32, 64>": 39928755,
+        "octo::stem_conv_kernel<_Float16, 32, 3, 2, false>": 17996855,
     },
 }
 
