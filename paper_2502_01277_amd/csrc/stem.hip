@@ -5,7 +5,10 @@
 // pipeline.hip, which also re-packs the weights as [Cout][(row, pair, 8 values)]).  The general implicit-GEMM kernel
 // gathers every K vector of every output pixel from global memory: for a 7x7 kernel that is 28 loads of 16 bytes per
 // output pixel, almost all of them re-reads.  Here a workgroup instead
-//   - keeps the whole weight matrix in LDS for its lifetime (it is persistent over tiles),
+//   - keeps the weight matrix in registers for its lifetime (it is persistent over tiles): every lane holds the
+//     MFMA A fragments of its row of each 32-channel block, all K steps of them (112 registers for 64 channels x 7x7).
+//     Out of LDS they cost as many bytes per MFMA as the pixel operand, and the two together are exactly what a
+//     compute unit's LDS delivers at the full MFMA rate - with two workgroups per unit the loop ran at half of it,
 //   - loads the input patch of an 8 x 32 output tile once (21 x 35 pair vectors for 7x7), zero-filled outside the image,
 //   - feeds the MFMA B operand straight from the patch: for kernel tap (r, s) output pixel (y, x) needs patch vector
 //     (2y + r, x + s), so the 32 lanes of a block read 32 consecutive vectors (bank-conflict free),
@@ -45,12 +48,9 @@ __global__ __launch_bounds__(THREADS, 2) void stem_conv_kernel(const ConvArgs a)
   constexpr int NJ = (NV + 1) / 2;             // MFMA steps
   constexpr int PH = (TH - 1) * 2 + KH, PW = TW + PKW - 1, PVEC = PH * PW;
   constexpr int PLOADS = (PVEC + THREADS - 1) / THREADS;
-  constexpr int WPITCH = NV + 1;               // odd number of vectors per weight row: conflict-free column reads
-  static_assert(WPITCH % 2 == 1, "weight row pitch must be odd");
   constexpr int TC = BC / 32;
   constexpr int OPITCH = BC * 2 + 16;          // bytes per staged output pixel
   constexpr int REGION_VECS = (PLOADS * THREADS > BP * OPITCH / 16) ? PLOADS * THREADS : BP * OPITCH / 16;
-  __shared__ u32x4 sW[BC * WPITCH];
   __shared__ u32x4 sR[REGION_VECS];            // input patch, then the staged output tile
   __shared__ u32x4 sCarry[POOL ? 2 * TW * OPITCH / 16 : 1];   // last row of the previous tile of the strip (two buffers, alternating)
   __shared__ float sBias[BC];
@@ -69,16 +69,19 @@ __global__ __launch_bounds__(THREADS, 2) void stem_conv_kernel(const ConvArgs a)
   const bool is_silu = a.act == OCTO_ACT_SILU;
   const float act_lo = a.act == OCTO_ACT_RELU ? 0.0f : -INFINITY;
 
-  // weights -> LDS, once (rows beyond Cout and the pad column are zero in the packed matrix / written as zero here)
+  // weights -> registers, once: row i * 32 + l32 of the packed matrix, K vector 2 j + g of step j (rows beyond Cout
+  // are zero in the packed matrix; the half step past an odd number of vectors multiplies zeros)
+  u32x4 wreg[TC][NJ];
   {
     const long long w_bytes = (long long)a.w_rows * a.Kp * 2;
     const __amdgpu_buffer_rsrc_t rsrc_w = __builtin_amdgcn_make_buffer_rsrc((void*)a.w, 0, (int)(w_bytes < BUF_MAX ? w_bytes : BUF_MAX), BUF_FLAGS);
-    for (int q = tid; q < BC * WPITCH; q += THREADS) {
-      const int row = q / WPITCH, v = q - row * WPITCH;
-      u32x4 val = {0u, 0u, 0u, 0u};
-      if (v < NV) val = __builtin_amdgcn_raw_buffer_load_b128(rsrc_w, (row * a.Kp + v * 8) * 2, 0, 0);
-      sW[q] = val;
-    }
+#pragma unroll
+    for (int i = 0; i < TC; ++i)
+#pragma unroll
+      for (int j = 0; j < NJ; ++j) {
+        const int v = 2 * j + g;
+        wreg[i][j] = __builtin_amdgcn_raw_buffer_load_b128(rsrc_w, v < NV ? ((i * 32 + l32) * a.Kp + v * 8) * 2 : OOB, 0, 0);
+      }
     if (tid < BC) sBias[tid] = a.bias[tid];
   }
 
@@ -142,15 +145,13 @@ __global__ __launch_bounds__(THREADS, 2) void stem_conv_kernel(const ConvArgs a)
       const int v0 = 2 * j, v1 = 2 * j + 1 < NV ? 2 * j + 1 : NV - 1;   // a half step past the end re-reads a valid vector: its weights are zero
       const int off0 = (v0 / PKW) * PW + (v0 % PKW), off1 = (v1 / PKW) * PW + (v1 % PKW);
       const int boff = prow0 + (g ? off1 : off0);
-      u32x4 fa[TC], fb[2];
-#pragma unroll
-      for (int i = 0; i < TC; ++i) fa[i] = sW[(i * 32 + l32) * WPITCH + 2 * j + g];
+      u32x4 fb[2];
 #pragma unroll
       for (int tp = 0; tp < 2; ++tp) fb[tp] = sR[boff + tp * 2 * PW];
 #pragma unroll
       for (int i = 0; i < TC; ++i)
 #pragma unroll
-        for (int tp = 0; tp < 2; ++tp) acc[i][tp] = E::mfma(fa[i], fb[tp], acc[i][tp]);
+        for (int tp = 0; tp < 2; ++tp) acc[i][tp] = E::mfma(wreg[i][j], fb[tp], acc[i][tp]);
     }
 
     // the next tile's patch is fetched while this one is staged and written (or pooled)
