@@ -79,25 +79,25 @@ def conv_name(kid: int, dtype: str) -> str:
 # calibration pass of known size).  Valid only for the kernel sources it was taken with: keyed by their hash.
 TRAFFIC = {
     # hash of the convolution sources (conv_sources_key): {kernel name: HBM bytes per launch}
-    "eaf3d30b2a996fb7": {
-        "octo::conv_mfma_kernel<__bf16, 128, 128, 2, 2, 8, 1, 2, true, true>": 624719395,
-        "octo::conv3x3_patch_kernel<__bf16, 64, 64>": 4275322692,
-        "octo::conv3x3_big_kernel<__bf16, 4, 4, 2, 4>": 1154111704,
-        "octo::conv_mfma_kernel<__bf16, 64, 128, 2, 2, 8, 1, 3, true, true>": 348180369,
-        "octo::stem_conv_kernel<__bf16, 64, 7, 4, true>": 3472455873,
-        "octo::conv_mfma_kernel<__bf16, 64, 256, 1, 4, 4, 1, 3, true, true>": 792571270,
-        "octo::conv3x3_big_kernel<__bf16, 3, 4, 1, 4>": 525991043,
-        "octo::conv3x3_big_kernel<__bf16, 3, 4, 2, 4>": 244968558,
-        "octo::stem_conv_kernel<__bf16, 64, 6, 3, false>": 1762224073,
-        "octo::conv_mfma_kernel<_Float16, 128, 128, 2, 2, 8, 1, 2, true, true>": 29220355,
-        "octo::conv_mfma_kernel<_Float16, 64, 128, 2, 2, 8, 1, 3, true, true>": 18777106,
-        "octo::conv3x3_patch_kernel<_Float16, 64, 64>": 69228454,
-        "octo::stem_conv_kernel<_Float16, 32, 6, 3, false>": 78867661,
-        "octo::conv_mfma_kernel<_Float16, 64, 64, 2, 2, 8, 1, 4, true, true>": 6634909,
-        "octo::stem_conv_kernel<_Float16, 64, 7, 4, true>": 55154684,
-        "octo::conv_mfma_kernel<_Float16, 32, 128, 1, 4, 4, 2, 4, true, false>": 13645294,
-        "octo::conv3x3_patch_kernel<_Float16, 32, 64>": 39928419,
-        "octo::stem_conv_kernel<_Float16, 32, 3, 2, false>": 18000955,
+    "9a254b53ecc341a5": {
+        "octo::conv_mfma_kernel<__bf16, 128, 128, 2, 2, 8, 1, 2, true, true>": 624797962,
+        "octo::conv3x3_patch_kernel<__bf16, 64, 64>": 4275014608,
+        "octo::conv_mfma_kernel<__bf16, 64, 256, 1, 4, 4, 1, 3, true, true>": 413045769,
+        "octo::conv3x3_big_kernel<__bf16, 4, 4, 2, 4>": 1154094220,
+        "octo::stem_conv_kernel<__bf16, 64, 7, 4, true>": 3392080086,
+        "octo::conv3x3_big_kernel<__bf16, 3, 4, 1, 4>": 526075166,
+        "octo::conv3x3_big_kernel<__bf16, 3, 4, 2, 4>": 245016086,
+        "octo::stem_conv_kernel<__bf16, 64, 6, 3, false>": 1738177635,
+        "octo::conv_mfma_kernel<__bf16, 64, 128, 2, 2, 8, 1, 3, true, true>": 541447993,
+        "octo::conv_mfma_kernel<_Float16, 128, 128, 2, 2, 8, 1, 2, true, true>": 29258299,
+        "octo::conv_mfma_kernel<_Float16, 64, 128, 2, 2, 8, 1, 3, true, true>": 18777552,
+        "octo::conv3x3_patch_kernel<_Float16, 64, 64>": 69225153,
+        "octo::stem_conv_kernel<_Float16, 32, 6, 3, false>": 78867621,
+        "octo::conv_mfma_kernel<_Float16, 64, 64, 2, 2, 8, 1, 4, true, true>": 6634903,
+        "octo::stem_conv_kernel<_Float16, 64, 7, 4, true>": 55154646,
+        "octo::conv_mfma_kernel<_Float16, 32, 128, 1, 4, 4, 2, 4, true, false>": 13645283,
+        "octo::conv3x3_patch_kernel<_Float16, 32, 64>": 39926998,
+        "octo::stem_conv_kernel<_Float16, 32, 3, 2, false>": 18000938,
     },
 }
 
