@@ -416,7 +416,7 @@ __global__ __launch_bounds__(64) void nms_reduce_kernel(const NmsArgs a) {
         }
       }
       // fold the rows of the boxes kept in this block into the words of later blocks
-      // (four rows per round, so that their loads are in flight together; a round with fewer rows left repeats the last)
+      // (four rows per pass, so that their loads are in flight together; a pass with fewer rows left repeats the last)
       if (lane > blk && lane < nblk) {
         unsigned long long k2 = kept;
         const unsigned long long* col = mask + (size_t)blk * 64 * nb + lane;
