@@ -71,3 +71,17 @@ def test_other_workloads_print_one_json_line(args, keys):
     assert d["n_gpus"] == 1 and d["vs_baseline"] is None and d["unit"] == "frames/s" and d["value"] > 0 and "workload" in d["config"]
     for k in keys:
         assert k in d, k
+
+
+def test_e4m3_layer_comparison_prints_one_json_line():
+    """bench.py --workload conv8: every layer timed in both types, the E4M3 roofline against the fp8 peak."""
+    r = _bench("--workload", "conv8", "--steps", "3")
+    assert r.returncode == 0, r.stderr[-2000:]
+    lines = [l for l in r.stdout.splitlines() if l.strip()]
+    assert len(lines) == 1
+    d = json.loads(lines[0])
+    assert d["n_gpus"] == 1 and d["vs_baseline"] is None and d["dtype"] == "f8e4m3" and "workload" in d["config"]
+    assert d["roofline"]["bound"] == "mfma" and d["roofline"]["peak"] == 5000.0 and 0 < d["roofline"]["frac"] < 1
+    assert "f8" in d["roofline"]["kernel"] and d["measured_peaks"]["mfma_e4m3_tflops"] > d["measured_peaks"]["mfma_bf16_tflops"]
+    assert len(d["layers"]) > 30 and all(L["f8"]["ms"] > 0 and L["bf16"]["ms"] > 0 for L in d["layers"])
+    assert d["speedup"] > 1.0                      # the 8-bit variant must at least not lose over the whole list
