@@ -112,6 +112,7 @@ CASES8 = [
     (256, 256, 16, 48, 1, 1, 0, 4, nn.ACT_RELU, nn.RES_NONE, 0, 0),           # 64x256 tiles
     (56, 56, 64, 64, 3, 1, 1, 40, nn.ACT_RELU, nn.RES_BEFORE_ACT, 0, 0),      # a classifier block's layer at a served batch
     (33, 29, 48, 130, 5, 2, 2, 3, nn.ACT_SILU, nn.RES_NONE, 0, 14),           # 5x5, stride 2, ragged everything
+    (40, 40, 16, 24, 3, 1, 1, 2, nn.ACT_RELU, nn.RES_AFTER_ACT, 0, 8),        # fewer channels than half a tile
 ]
 
 
