@@ -9,7 +9,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OUT = os.path.join(HERE, "libocto.so")
-SOURCES = ["conv.hip", "convbig.hip", "stem.hip", "conv3x3.hip", "glue.hip", "preproc.hip", "postproc.hip", "pipeline.hip", "ops_api.hip", "probes.hip", "executor.hip", "sched.cpp", "runtime.cpp", "placement.cpp"]
+SOURCES = ["convbig_bf16.hip", "convbig_f16.hip", "conv_bf16.hip", "conv_f16.hip", "conv_f32.hip", "conv_f8.hip", "conv.hip", "convbig.hip", "stem.hip", "conv3x3.hip", "glue.hip", "preproc.hip", "postproc.hip", "pipeline.hip", "ops_api.hip", "probes.hip", "executor.hip", "sched.cpp", "runtime.cpp", "placement.cpp"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-ffp-contract=off",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wno-unused-result", "-Wno-unused-value"]
 

@@ -429,21 +429,10 @@ __global__ __launch_bounds__(THREADS, MINB) void conv_mfma_kernel(const ConvArgs
   }
 }
 
-// kernel id of a conv tile configuration, decimal digits 1 BBB PPP K M V: channel tile, pixel tile, 16-byte vectors per
-// K step, workgroups per CU the registers are sized for, vectorised gather
-int conv_kernel_id(int bc, int bp, int kv, int minb, bool vec, bool dma) { return 1000000000 + bc * 1000000 + bp * 1000 + kv * 100 + minb * 10 + (vec ? 1 : 0) + (dma ? 2 : 0); }
-
-size_t conv_packed_weight_elems(int cout, int kh, int kw, int cin, int dtype, int* kp_out, int* cout_pad_out) {
-  const int vn = 16 / dtype_size(dtype);
-  const int bk = 8 * vn;   // largest K step of any tile configuration
-  const int K = kh * kw * cin;
-  const int kp = (K + bk - 1) / bk * bk;
-  const int cp = (cout + 127) / 128 * 128;
-  if (kp_out) *kp_out = kp;
-  if (cout_pad_out) *cout_pad_out = cp;
-  return (size_t)kp * cp;
-}
-
+// This file is compiled once per storage type, so that the types build in parallel: conv_f16.hip, conv_bf16.hip,
+// conv_f32.hip and conv_f8.hip define OCTO_CONV_ONLY_<type> and include it; each then holds the kernel instances of
+// its type behind one entry point (launch_general_<type>).  Compiled as itself it holds no kernel, only the dispatch
+// (launch_conv) and the host helpers.
 #ifndef OCTO_CONV_NO_LAUNCHERS
 template <typename T, int BC, int BP, int WC, int WP, int KV, int D, int MINB, bool VEC, bool DMA = false>
 static hipError_t launch_cfg(const ConvArgs& a, int num_cu, hipStream_t s, int* kernel_id, const ConvTiming& tm) {
@@ -503,6 +492,7 @@ static hipError_t launch_typed(const ConvArgs& a, int num_cu, hipStream_t s, int
 // 8-bit floating point (E4M3) storage: the direct-to-LDS tile shapes only, so the input channels must come in whole
 // 16-byte vectors.  Same choice of shape as for the 16-bit types; a K step is 128 (or 64) bytes of K as there, that is
 // twice as many values.
+#if defined(OCTO_CONV_ONLY_F8)
 static hipError_t launch_f8(const ConvArgs& a, int num_cu, hipStream_t s, int* kernel_id, const ConvTiming& tm) {
   const bool vec = (a.Cin % 16 == 0) && (a.x_ld % 16 == 0) && (a.x_coff % 16 == 0) && (((uintptr_t)a.x & 15) == 0) && a.kh <= 15 && a.kw <= 15;
   if (!vec || !a.scale || a.pair_view) return hipErrorInvalidValue;
@@ -515,6 +505,36 @@ static hipError_t launch_f8(const ConvArgs& a, int num_cu, hipStream_t s, int* k
   if (tiles(64, 128) >= (a.Kp >= 1024 ? num_cu / 4 : 9 * num_cu / 8))
     return launch_cfg<f8, 64, 128, 2, 2, 8, 1, 3, true, true>(a, num_cu, s, kernel_id, tm);
   return launch_cfg<f8, 64, 64, 2, 2, 8, 1, 4, true, true>(a, num_cu, s, kernel_id, tm);
+}
+#endif
+
+#if defined(OCTO_CONV_ONLY_F16)
+hipError_t launch_general_f16(const ConvArgs& a, int num_cu, hipStream_t s, int* kernel_id, const ConvTiming& tm) { return launch_typed<_Float16>(a, num_cu, s, kernel_id, tm); }
+#elif defined(OCTO_CONV_ONLY_BF16)
+hipError_t launch_general_bf16(const ConvArgs& a, int num_cu, hipStream_t s, int* kernel_id, const ConvTiming& tm) { return launch_typed<__bf16>(a, num_cu, s, kernel_id, tm); }
+#elif defined(OCTO_CONV_ONLY_F32)
+hipError_t launch_general_f32(const ConvArgs& a, int num_cu, hipStream_t s, int* kernel_id, const ConvTiming& tm) { return launch_typed<float>(a, num_cu, s, kernel_id, tm); }
+#elif defined(OCTO_CONV_ONLY_F8)
+hipError_t launch_general_f8(const ConvArgs& a, int num_cu, hipStream_t s, int* kernel_id, const ConvTiming& tm) { return launch_f8(a, num_cu, s, kernel_id, tm); }
+#else
+hipError_t launch_general_f16(const ConvArgs& a, int num_cu, hipStream_t s, int* kernel_id, const ConvTiming& tm);
+hipError_t launch_general_bf16(const ConvArgs& a, int num_cu, hipStream_t s, int* kernel_id, const ConvTiming& tm);
+hipError_t launch_general_f32(const ConvArgs& a, int num_cu, hipStream_t s, int* kernel_id, const ConvTiming& tm);
+hipError_t launch_general_f8(const ConvArgs& a, int num_cu, hipStream_t s, int* kernel_id, const ConvTiming& tm);
+
+// kernel id of a conv tile configuration, decimal digits 1 BBB PPP K M V: channel tile, pixel tile, 16-byte vectors per
+// K step, workgroups per CU the registers are sized for, vectorised gather
+int conv_kernel_id(int bc, int bp, int kv, int minb, bool vec, bool dma) { return 1000000000 + bc * 1000000 + bp * 1000 + kv * 100 + minb * 10 + (vec ? 1 : 0) + (dma ? 2 : 0); }
+
+size_t conv_packed_weight_elems(int cout, int kh, int kw, int cin, int dtype, int* kp_out, int* cout_pad_out) {
+  const int vn = 16 / dtype_size(dtype);
+  const int bk = 8 * vn;   // largest K step of any tile configuration
+  const int K = kh * kw * cin;
+  const int kp = (K + bk - 1) / bk * bk;
+  const int cp = (cout + 127) / 128 * 128;
+  if (kp_out) *kp_out = kp;
+  if (cout_pad_out) *cout_pad_out = cp;
+  return (size_t)kp * cp;
 }
 
 // Checks the limits the kernel relies on and fills the precomputed reciprocals.
@@ -548,7 +568,7 @@ hipError_t launch_conv(int dtype, const ConvArgs& a0, int num_cu, hipStream_t s,
     const bool ok = (dtype == OCTO_F16 || dtype == OCTO_BF16) && a.y2 && !a.res && !a.out_f32 && !a.pair_view && !a.pool_y && a.split < a.Cout &&
                     ((a.split | a.Cout | a.y_ld | a.y_coff | a.y2_ld | a.y2_coff) & 7) == 0 && ((((uintptr_t)a.y | (uintptr_t)a.y2) & 15) == 0);
     if (!ok) return hipErrorNotSupported;
-    return dtype == OCTO_F16 ? launch_typed<_Float16>(a, num_cu, s, kernel_id, tm) : launch_typed<__bf16>(a, num_cu, s, kernel_id, tm);
+    return dtype == OCTO_F16 ? launch_general_f16(a, num_cu, s, kernel_id, tm) : launch_general_bf16(a, num_cu, s, kernel_id, tm);
   }
   const hipError_t es = launch_stem(dtype, a, num_cu, s, kernel_id, tm);
   if (es != hipErrorNotSupported || a.pool_y) return es;      // only the first-layer kernel can pool its own output
@@ -569,13 +589,14 @@ hipError_t launch_conv(int dtype, const ConvArgs& a0, int num_cu, hipStream_t s,
     if (eb != hipErrorNotSupported) return eb;
   }
   switch (dtype) {
-    case OCTO_F8: return launch_f8(a, num_cu, s, kernel_id, tm);
-    case OCTO_F16: return launch_typed<_Float16>(a, num_cu, s, kernel_id, tm);
-    case OCTO_BF16: return launch_typed<__bf16>(a, num_cu, s, kernel_id, tm);
-    case OCTO_F32: return launch_typed<float>(a, num_cu, s, kernel_id, tm);
+    case OCTO_F8: return launch_general_f8(a, num_cu, s, kernel_id, tm);
+    case OCTO_F16: return launch_general_f16(a, num_cu, s, kernel_id, tm);
+    case OCTO_BF16: return launch_general_bf16(a, num_cu, s, kernel_id, tm);
+    case OCTO_F32: return launch_general_f32(a, num_cu, s, kernel_id, tm);
   }
   return hipErrorInvalidValue;
 }
-#endif
+#endif   // the main translation unit
+#endif   // launchers
 
 }  // namespace octo

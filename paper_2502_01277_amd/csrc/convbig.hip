@@ -479,6 +479,8 @@ inline size_t big_lds_bytes(int BC, int BP, int NST, const BigGeom& gm) {
          (size_t)(BP / 32) * THREADS * sizeof(int) + 4096;
 }
 
+// Compiled once per storage type so that the two build in parallel: convbig_f16.hip and convbig_bf16.hip define
+// OCTO_BIG_ONLY_<type> and include this file; compiled as itself it holds only the entry point below.
 #ifndef OCTO_CONV_NO_LAUNCHERS
 namespace {
 
@@ -536,6 +538,14 @@ hipError_t launch_big_typed(const ConvArgs& a, int num_cu, hipStream_t s, int* k
 
 }  // namespace
 
+#if defined(OCTO_BIG_ONLY_F16)
+hipError_t launch_big_f16(const ConvArgs& a, int num_cu, hipStream_t s, int* kernel_id, const ConvTiming& tm) { return launch_big_typed<_Float16>(a, num_cu, s, kernel_id, tm); }
+#elif defined(OCTO_BIG_ONLY_BF16)
+hipError_t launch_big_bf16(const ConvArgs& a, int num_cu, hipStream_t s, int* kernel_id, const ConvTiming& tm) { return launch_big_typed<__bf16>(a, num_cu, s, kernel_id, tm); }
+#else
+hipError_t launch_big_f16(const ConvArgs& a, int num_cu, hipStream_t s, int* kernel_id, const ConvTiming& tm);
+hipError_t launch_big_bf16(const ConvArgs& a, int num_cu, hipStream_t s, int* kernel_id, const ConvTiming& tm);
+
 // hipErrorNotSupported when the layer does not fit this kernel (the caller then takes the general kernel).
 hipError_t launch_conv3x3_big(int dtype, const ConvArgs& a, int num_cu, hipStream_t s, int* kernel_id, ConvTiming tm) {
   if (dtype != OCTO_F16 && dtype != OCTO_BF16) return hipErrorNotSupported;
@@ -543,11 +553,12 @@ hipError_t launch_conv3x3_big(int dtype, const ConvArgs& a, int num_cu, hipStrea
   if (a.Cin % 32 || a.x_ld % 8 || a.x_coff % 8 || ((uintptr_t)a.x & 15) || a.Cout < 80) return hipErrorNotSupported;
   if (a.Ho != a.H || a.Wo != a.W) return hipErrorNotSupported;
   switch (dtype) {
-    case OCTO_F16: return launch_big_typed<_Float16>(a, num_cu, s, kernel_id, tm);
-    case OCTO_BF16: return launch_big_typed<__bf16>(a, num_cu, s, kernel_id, tm);
+    case OCTO_F16: return launch_big_f16(a, num_cu, s, kernel_id, tm);
+    case OCTO_BF16: return launch_big_bf16(a, num_cu, s, kernel_id, tm);
   }
   return hipErrorNotSupported;
 }
-#endif
+#endif   // the main translation unit
+#endif   // launchers
 
 }  // namespace octo
