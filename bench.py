@@ -79,25 +79,25 @@ def conv_name(kid: int, dtype: str) -> str:
 # calibration pass of known size).  Valid only for the kernel sources it was taken with: keyed by their hash.
 TRAFFIC = {
     # hash of the convolution sources (conv_sources_key): {kernel name: HBM bytes per launch}
-    "9a254b53ecc341a5": {
-        "octo::conv_mfma_kernel<__bf16, 128, 128, 2, 2, 8, 1, 2, true, true>": 624797962,
-        "octo::conv3x3_patch_kernel<__bf16, 64, 64>": 4275014608,
-        "octo::conv_mfma_kernel<__bf16, 64, 256, 1, 4, 4, 1, 3, true, true>": 413045769,
-        "octo::conv3x3_big_kernel<__bf16, 4, 4, 2, 4>": 1154094220,
-        "octo::stem_conv_kernel<__bf16, 64, 7, 4, true>": 3392080086,
-        "octo::conv3x3_big_kernel<__bf16, 3, 4, 1, 4>": 526075166,
-        "octo::conv3x3_big_kernel<__bf16, 3, 4, 2, 4>": 245016086,
-        "octo::stem_conv_kernel<__bf16, 64, 6, 3, false>": 1738177635,
-        "octo::conv_mfma_kernel<__bf16, 64, 128, 2, 2, 8, 1, 3, true, true>": 541447993,
-        "octo::conv_mfma_kernel<_Float16, 128, 128, 2, 2, 8, 1, 2, true, true>": 29258299,
-        "octo::conv_mfma_kernel<_Float16, 64, 128, 2, 2, 8, 1, 3, true, true>": 18777552,
-        "octo::conv3x3_patch_kernel<_Float16, 64, 64>": 69225153,
-        "octo::stem_conv_kernel<_Float16, 32, 6, 3, false>": 78867621,
-        "octo::conv_mfma_kernel<_Float16, 64, 64, 2, 2, 8, 1, 4, true, true>": 6634903,
-        "octo::stem_conv_kernel<_Float16, 64, 7, 4, true>": 55154646,
-        "octo::conv_mfma_kernel<_Float16, 32, 128, 1, 4, 4, 2, 4, true, false>": 13645283,
-        "octo::conv3x3_patch_kernel<_Float16, 32, 64>": 39926998,
-        "octo::stem_conv_kernel<_Float16, 32, 3, 2, false>": 18000938,
+    "93d07c228e907e2c": {
+        "octo::conv_mfma_kernel<__bf16, 128, 128, 2, 2, 8, 1, 2, true, true>": 624532799,
+        "octo::conv3x3_patch_kernel<__bf16, 64, 64>": 4275894878,
+        "octo::conv_mfma_kernel<__bf16, 64, 256, 1, 4, 4, 1, 3, true, true>": 412985885,
+        "octo::conv3x3_big_kernel<__bf16, 4, 4, 2, 4>": 1153790470,
+        "octo::stem_conv_kernel<__bf16, 64, 7, 4, true>": 3409215376,
+        "octo::conv3x3_big_kernel<__bf16, 3, 4, 1, 4>": 526039832,
+        "octo::conv3x3_big_kernel<__bf16, 3, 4, 2, 4>": 244944910,
+        "octo::stem_conv_kernel<__bf16, 64, 6, 3, false>": 1753120816,
+        "octo::conv_mfma_kernel<__bf16, 64, 128, 2, 2, 8, 1, 3, true, true>": 541911139,
+        "octo::conv_mfma_kernel<_Float16, 128, 128, 2, 2, 8, 1, 2, true, true>": 29254610,
+        "octo::conv_mfma_kernel<_Float16, 64, 128, 2, 2, 8, 1, 3, true, true>": 18779512,
+        "octo::conv3x3_patch_kernel<_Float16, 64, 64>": 69226266,
+        "octo::stem_conv_kernel<_Float16, 32, 6, 3, false>": 78867677,
+        "octo::conv_mfma_kernel<_Float16, 64, 64, 2, 2, 8, 1, 4, true, true>": 6645295,
+        "octo::stem_conv_kernel<_Float16, 64, 7, 4, true>": 55154702,
+        "octo::conv_mfma_kernel<_Float16, 32, 128, 1, 4, 4, 2, 4, true, false>": 13644829,
+        "octo::conv3x3_patch_kernel<_Float16, 32, 64>": 39928727,
+        "octo::stem_conv_kernel<_Float16, 32, 3, 2, false>": 18000958,
     },
 }
 
